@@ -1,0 +1,235 @@
+#!/usr/bin/env python3
+"""Benchmark of the R-TOSS hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input: pattern selection
+over every weight tensor of the workload, packing of every layer, and the pattern-sparse
+convolution of every layer.  Inputs are resident in HBM before the timed region starts.
+Prints ONE JSON line.  `value` is effective TFLOP/s counted on non-zero MACs only
+(2 * N*Ho*Wo*k*groups / time), whole step; `roofline` describes the dominant kernel (the
+convolution) from HIP-event timings taken inside the timed region; `cpu_baseline` is the
+fp64 CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_MFMA_16BIT_TFLOPS = 2500.0   # MI355X dense fp16/bf16 matrix peak
+PEAK_FP32_VECTOR_TFLOPS = 157.3   # MI355X fp32 vector peak
+PEAK_HBM_GBS = 8000.0             # MI355X HBM3E peak
+
+WORKLOADS = {"cfg1": 1, "cfg2": 2, "cfg3": 3, "cfg4": 4, "cfg5": 5}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", choices=sorted(WORKLOADS), default="cfg4",
+                    help="cfg4 (RetinaNet-shaped head, the largest shapes) is the headline workload")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense", action="store_true", help="skip the dense torch conv2d comparator")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0, help="target wall time of the oracle sample")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only; --gpus %d is not supported "
+              "(the path shards by batch with no collective, see DESIGN.md)" % args.gpus, file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2303_02191_amd import binding as B
+    from paper_2303_02191_amd import pipeline as pl
+    from paper_2303_02191_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    B.lib()  # fail loudly if the HIP library is missing
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    cfg = wl.get_config(WORKLOADS[args.workload])
+    masks = B.rtoss_pattern_dict(cfg.k)
+    tdt = pl.TORCH_DTYPE[cfg.dtype]
+    eb = wl.ELEM_BYTES[cfg.dtype]
+
+    # ---- inputs: weights drawn on the host (seeded numpy), activations on the device (seeded torch) ----
+    rng = np.random.default_rng(cfg.seed)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(cfg.seed)
+    w_host = [wl.draw_w(rng, cfg, L) for L in cfg.layers]
+    # all 3x3 tensors live in one contiguous buffer so that one select call covers them
+    n3 = sum(L.n_weights for L in cfg.layers if L.ksize == 3)
+    w3_all = torch.empty(max(n3, 1), dtype=tdt, device=dev)
+    idx3_all = torch.empty(max(n3 // 9, 1), dtype=torch.uint8, device=dev)
+    w_dev, idx_dev, off = [], [], 0
+    for L, (ws, _) in zip(cfg.layers, w_host):
+        if L.ksize == 3:
+            view = w3_all[off: off + L.n_weights]
+            view.copy_(pl.to_device(ws.reshape(-1), cfg.dtype))
+            w_dev.append(view)
+            idx_dev.append(idx3_all[off // 9: (off + L.n_weights) // 9])
+            off += L.n_weights
+        else:
+            w_dev.append(pl.to_device(ws.reshape(-1), cfg.dtype))
+            idx_dev.append(torch.empty(max(L.groups, 1), dtype=torch.uint8, device=dev))
+
+    def draw_act(L):
+        shape = (cfg.N, L.H, L.W, L.Ci)  # channels-last
+        if cfg.x_dist == "normal":
+            a = torch.randn(shape, generator=gen, device=dev, dtype=torch.float32)
+        else:
+            a = torch.rand(shape, generator=gen, device=dev, dtype=torch.float32) * 2 - 1
+        return a.to(tdt)
+
+    xs, ys = [], []
+    for i, L in enumerate(cfg.layers):
+        if cfg.chained and i > 0:
+            xs.append(ys[i - 1])
+        else:
+            xs.append(draw_act(L))
+        ys.append(torch.empty((cfg.N, L.Ho, L.Wo, L.Co), dtype=tdt, device=dev))
+    layers = [pl.PackedLayer(L.Co, L.Ci, L.ksize, cfg.k, cfg.dtype, masks) for L in cfg.layers]
+    torch.cuda.synchronize()
+
+    stream = torch.cuda.current_stream().cuda_stream
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def step(events=None):
+        if events:
+            events[0].record()
+        if n3:
+            B.rtoss_select_patterns(w3_all.data_ptr(), cfg.dtype, n3, masks, idx3_all.data_ptr(), stream)
+        for L, w, idx in zip(cfg.layers, w_dev, idx_dev):
+            if L.ksize == 1:
+                B.rtoss_select_patterns(w.data_ptr(), cfg.dtype, L.n_weights, masks, idx.data_ptr(), stream)
+        if events:
+            events[1].record()
+        for lay, w, idx in zip(layers, w_dev, idx_dev):
+            lay.pack(w, idx)
+        if events:
+            events[2].record()
+        for L, lay, x, y in zip(cfg.layers, layers, xs, ys):
+            lay.conv(x, stride=L.stride, relu=L.relu, y=y)
+        if events:
+            events[3].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    all_events = [[ev() for _ in range(4)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(all_events[s])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    sel_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in all_events]))
+    pack_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in all_events]))
+    conv_ms = float(np.mean([e[2].elapsed_time(e[3]) for e in all_events]))
+
+    nz_flops = 2.0 * cfg.nonzero_macs()
+    value = nz_flops / (ms_per_step * 1e-3) / 1e12
+
+    # ---- roofline of the dominant kernel (the convolution), per launch ----
+    n_conv = len(cfg.layers)
+    conv_launch_s = conv_ms * 1e-3 / n_conv
+    hbm_bound = args.workload in ("cfg2", "cfg3", "cfg5")
+    if hbm_bound:
+        alg_bytes = cfg.algorithmic_bytes() / n_conv
+        achieved = alg_bytes / conv_launch_s / 1e9
+        roofline = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": achieved / PEAK_HBM_GBS, "traffic": None}
+    elif cfg.dtype == wl.F32:
+        achieved = nz_flops / n_conv / conv_launch_s / 1e12
+        roofline = {"bound": "alu", "achieved": achieved, "peak": PEAK_FP32_VECTOR_TFLOPS, "unit": "TFLOP/s",
+                    "frac": achieved / PEAK_FP32_VECTOR_TFLOPS, "traffic": None}
+    else:
+        achieved = nz_flops / n_conv / conv_launch_s / 1e12
+        roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_MFMA_16BIT_TFLOPS, "unit": "TFLOP/s",
+                    "frac": achieved / PEAK_MFMA_16BIT_TFLOPS, "traffic": None}
+    roofline["kernel"] = "rtoss_conv2d_pattern"
+    roofline["avg_launch_us"] = conv_launch_s * 1e6
+    roofline["launches_per_step"] = n_conv
+
+    # ---- dense comparator: torch conv2d (MIOpen / hipBLASLt) on the same shapes, bench only ----
+    dense_ms = None
+    if not args.no_dense:
+        try:
+            dense_ms = 0.0
+            for L, (ws, _), x in zip(cfg.layers, w_host, xs):
+                wt = pl.to_device(ws, cfg.dtype).contiguous(memory_format=torch.channels_last)
+                xt = x.permute(0, 3, 1, 2)  # NCHW view of channels-last storage
+                for _ in range(3):
+                    torch.nn.functional.conv2d(xt, wt, stride=L.stride, padding=L.pad)
+                torch.cuda.synchronize()
+                a, b = ev(), ev()
+                a.record()
+                for _ in range(10):
+                    torch.nn.functional.conv2d(xt, wt, stride=L.stride, padding=L.pad)
+                b.record()
+                torch.cuda.synchronize()
+                dense_ms += a.elapsed_time(b) / 10
+        except Exception as e:  # comparator only
+            dense_ms = None
+            print("dense comparator failed: %r" % (e,), file=sys.stderr)
+
+    # ---- CPU baseline: the oracle on a bounded sample (first layer, batch item 0, a few output channels) ----
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        L = cfg.layers[0]
+        ws, wv = w_host[0]
+        x0 = pl.to_host(xs[0][:1]).copy()  # [1, H, W, Ci] storage
+        xv = wl.to_f64(wl.nhwc_to_nchw(x0), cfg.dtype)
+        t_a = time.perf_counter()
+        idx = oracle.select(wv, masks)
+        wm = oracle.mask(wv, masks, idx)
+        t_b = time.perf_counter()
+        probe_c = 1
+        t_c = time.perf_counter()
+        oracle.conv2d(xv, wm[:probe_c], stride=L.stride)
+        t_d = time.perf_counter()
+        rate = max(t_d - t_c, 1e-4) / probe_c
+        n_co = int(max(1, min(L.Co, args.cpu_seconds / rate)))
+        t_e = time.perf_counter()
+        oracle.conv2d(xv, wm[:n_co], stride=L.stride)
+        t_f = time.perf_counter()
+        sample_nz_macs = L.Ho * L.Wo * cfg.k * n_co * (L.Ci * L.ksize * L.ksize / 9.0)
+        cpu = {"value": 2.0 * sample_nz_macs / (t_f - t_e) / 1e12, "unit": "TFLOP/s", "cores": oracle.threads(),
+               "kind": "oracle",
+               "sample": "layer 0 of %s, batch item 0, output channels 0..%d, all positions (%.2f s); "
+                         "select+mask of the layer's %d groups took %.3f s" % (cfg.name, n_co - 1, t_f - t_e,
+                                                                              L.groups, t_b - t_a)}
+
+    out = {
+        "metric": "effective TFLOP/s on non-zero MACs, select+pack+pattern-sparse conv",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.DTYPE_NAMES[cfg.dtype], "data": "synthetic",
+        "config": {"workload": cfg.name, "batch": cfg.N, "layers": len(cfg.layers), "k": cfg.k,
+                   "patterns": int(masks.size), "nonzero_gflop_per_step": nz_flops / 1e9,
+                   "dense_gflop_per_step": 2.0 * cfg.dense_macs() / 1e9},
+        "breakdown_ms": {"select": sel_ms, "pack": pack_ms, "conv": conv_ms,
+                         "dense_torch_conv2d": dense_ms},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

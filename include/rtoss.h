@@ -1,0 +1,195 @@
+/*
+ * rtoss.h -- C ABI of the MI355X (gfx950) hot path of R-TOSS pattern pruning.
+ *
+ * Three steps, each one or a few kernel launches on a caller-supplied HIP stream:
+ *
+ *   rtoss_select_patterns   per-kernel best pattern      (Section IV.C, Algorithm 2;
+ *                                                          Section IV.D, Algorithm 3)
+ *   rtoss_pack              prune + compact weight layout (Section II.B mask semantics;
+ *                                                          Section IV.C, last sentence:
+ *                                                          kernels laid out by pattern)
+ *   rtoss_conv2d_pattern    convolution over the surviving weights only
+ *                                                         (Section II.B cost model)
+ *
+ * plus the host-side dictionary generator rtoss_pattern_dict (Section IV.B, Eq. 1 and the
+ * adjacency criterion).
+ *
+ * Conventions shared by every call
+ *   - Pointers named *_dev are device (HBM) pointers, pointers named *_host are host
+ *     pointers.  The library allocates no device memory and keeps no pointer after a call
+ *     returns: every buffer is caller-owned.  Host arrays (the dictionary) are copied into
+ *     the launch arguments before the call returns.
+ *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     validate their arguments on the host BEFORE touching the GPU, enqueue their kernels
+ *     and return without synchronising.
+ *   - Return value: RTOSS_OK or an error code; rtoss_last_error() gives a thread-local,
+ *     statically stored message for the last failing call on this thread.  No exception
+ *     crosses the boundary.
+ *   - Tap numbering: a "group" is 9 contiguous weights; tap t is offset t in the group,
+ *     i.e. row t/3, column t%3 of a 3x3 kernel.  A pattern is a uint16_t with bit t set
+ *     iff tap t survives.  A dictionary is an array of P such masks that all have the
+ *     same number k of set bits (one k per call: the paper's 2EP/3EP/4EP/5EP variants are
+ *     separate dictionaries, Table 3), 1 <= P <= 255.
+ *   - Determinism: identical inputs give bit-identical outputs (no atomics are used in any
+ *     accumulation).
+ *   - Activations are finite numbers.  (A pruned weight is an exact zero; zero times a
+ *     non-finite activation is not defined by this interface.)
+ */
+#ifndef RTOSS_H
+#define RTOSS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    RTOSS_OK = 0,
+    RTOSS_EINVAL = 1,   /* NULL pointer, bad enum value, bad dictionary, misaligned pointer */
+    RTOSS_ESHAPE = 2,   /* unsupported kernel size / stride / padding / extent */
+    RTOSS_EDTYPE = 3,   /* unsupported dtype combination */
+    RTOSS_ELAYOUT = 4,  /* unsupported activation layout */
+    RTOSS_ENOSPACE = 5, /* a caller buffer is smaller than the size the library asked for */
+    RTOSS_EHIP = 6      /* the HIP runtime reported an error (text in rtoss_last_error) */
+} rtoss_status;
+
+typedef enum { RTOSS_F32 = 0, RTOSS_F16 = 1, RTOSS_BF16 = 2 } rtoss_dtype;
+
+typedef enum { RTOSS_NCHW = 0, RTOSS_NHWC = 1 } rtoss_layout;
+
+/* Which k-subsets of the 9 taps enter the dictionary (Section IV.B: "drop all patterns
+ * without adjacent non-zero weights").  The paper's figure of example patterns is not
+ * reproducible from its text, so the reading is a parameter:
+ *   ALL         every k-subset (Eq. 1 only);
+ *   ANYPAIR4    at least one pair of edge-sharing live taps;
+ *   CONNECTED4  the live taps form one edge-connected set (the default reading);
+ *   CONNECTED8  connected when corner-sharing taps also count as neighbours.
+ * A single tap (k = 1) passes every rule. */
+typedef enum {
+    RTOSS_RULE_ALL = 0,
+    RTOSS_RULE_ANYPAIR4 = 1,
+    RTOSS_RULE_CONNECTED4 = 2,
+    RTOSS_RULE_CONNECTED8 = 3
+} rtoss_rule;
+
+/*
+ * Section IV.B, Eq. 1 + first narrowing criterion.  Host only, no GPU needed.
+ * Enumerates the k-subsets of taps {0..8} as ascending tuples in lexicographic order and
+ * keeps those that pass `rule`; pattern index = rank among the kept ones.
+ *   k      1..9
+ *   masks  host array of `cap` entries, may be NULL when cap == 0 (count query)
+ *   P      out: number of patterns in the dictionary (always the full count)
+ * Returns RTOSS_EINVAL for a bad k / rule / NULL P, RTOSS_ENOSPACE when cap > 0 is smaller
+ * than the count (the first cap masks are still written).
+ */
+rtoss_status rtoss_pattern_dict(int k, rtoss_rule rule, uint16_t* masks_host, int cap, int* P);
+
+/*
+ * Section IV.C (Algorithm 2: score every dictionary pattern on every kernel, keep the
+ * best) on the flat view of Section IV.D (Algorithm 3: the weight tensor flattened
+ * row-major and cut into groups of 9; for a [Co][Ci][3][3] tensor the groups are its
+ * kernels, group g = co*Ci + ci).
+ *
+ *   w_dev       n_elems contiguous weights of type dt (device), aligned to its element size
+ *   n_elems     >= 0; G = n_elems / 9 groups are scored, the n_elems % 9 tail is ignored
+ *   masks_host  dictionary, P masks of equal popcount (host)
+ *   idx_dev     out: G bytes (device); idx[g] = index of the pattern that maximises the
+ *               retained energy  sum_{t live} w[9g+t]^2
+ *
+ * Arithmetic is fixed so that the result is reproducible bit for bit: each weight is
+ * converted exactly to fp64, squares are summed in fp64 over the live taps in ascending
+ * tap order starting from 0, patterns are scanned in ascending index with a strict
+ * "greater than", so ties go to the lowest index, a NaN score never wins, and a group
+ * whose every score is NaN gets index 0.
+ * Several tensors may be scored by one call on their concatenation only if each has a
+ * multiple of 9 elements (3x3 layers); a 1x1 tensor needs its own call because its tail
+ * is per tensor.
+ */
+rtoss_status rtoss_select_patterns(const void* w_dev, rtoss_dtype dt, int64_t n_elems,
+                                   const uint16_t* masks_host, int P,
+                                   uint8_t* idx_dev, void* hip_stream);
+
+/* One convolution layer's weight tensor: [Co][Ci][ksize][ksize] contiguous, ksize 1 or 3,
+ * k = number of survivors per group of 9 (the popcount of the dictionary's masks). */
+typedef struct {
+    int Co, Ci;
+    int ksize; /* 1 or 3 */
+    int k;     /* 1..9 */
+    rtoss_dtype dt;
+} rtoss_wdesc;
+
+/*
+ * Size in bytes of the packed blob rtoss_pack writes for this layer and dictionary, and
+ * of the scratch workspace it needs (may be 0).  Host only.  The blob size depends on the
+ * dictionary because the dictionary decides which compute layouts are legal (see below).
+ */
+rtoss_status rtoss_pack_size(const rtoss_wdesc* desc, const uint16_t* masks_host, int P,
+                             size_t* packed_bytes, size_t* workspace_bytes);
+
+/*
+ * Prune and pack one layer (Section II.B: a mask keeps the weights it covers, the others
+ * become zero; Section IV.D: the n_elems % 9 tail of a flattened 1x1 tensor is pruned;
+ * Section IV.C, closing sentences: kernels are laid out by their pattern so that
+ * inference touches only the survivors).
+ *
+ *   w_dev         the unpruned weights, Co*Ci*ksize*ksize elements of desc->dt (device)
+ *   idx_dev       G = Co*Ci*ksize*ksize / 9 pattern indices from rtoss_select_patterns
+ *   packed_dev    out: packed_bytes from rtoss_pack_size, 256-byte aligned (device).
+ *                 The blob is position independent: it may be copied, saved and reloaded.
+ *   workspace_dev scratch of workspace_bytes (may be NULL when that size is 0)
+ *
+ * Blob layout.  Section 0, always present and part of this interface (the tests decode it):
+ *     [G][k]  surviving weights of each group in ascending tap order, type desc->dt
+ *     [G]     pattern index of each group (uint8), starting at the next multiple of 256 B
+ * Further sections (each starting at a multiple of 256 bytes) are private to the
+ * convolution kernels: tiles of the pruned weights arranged as matrix-core operand
+ * fragments, dense with explicit zeros or 2-of-4 compressed when every pattern of the
+ * dictionary allows it.
+ * Errors: RTOSS_EINVAL (NULL, bad dictionary, popcount != desc->k, misaligned blob),
+ * RTOSS_ESHAPE (ksize not 1 or 3, non-positive extents), RTOSS_ENOSPACE.
+ */
+rtoss_status rtoss_pack(const rtoss_wdesc* desc, const void* w_dev, const uint8_t* idx_dev,
+                        const uint16_t* masks_host, int P,
+                        void* packed_dev, size_t packed_bytes,
+                        void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
+/* One convolution call. */
+typedef struct {
+    int N, H, W;         /* batch, input height, input width */
+    int stride;          /* 1 or 2 (1 only for ksize 1) */
+    int pad;             /* must equal ksize / 2 */
+    rtoss_layout layout; /* RTOSS_NHWC: x is [N][H][W][Ci], y is [N][Ho][Wo][Co] */
+    rtoss_dtype out_dt;  /* the weight dtype, or RTOSS_F32 */
+    int fuse_relu;       /* non-zero: y = max(y, 0) */
+} rtoss_cdesc;
+
+/*
+ * Convolution over the pruned weights (cross-correlation, zero padding, no bias, groups 1,
+ * dilation 1), multiplying only surviving taps:
+ *     y[n][oh][ow][co] = sum_ci sum_{t live in kernel (co,ci)}
+ *                            w[co][ci][t] * x[n][oh*stride - pad + t/3][ow*stride - pad + t%3][ci]
+ * with Ho = (H + 2*pad - ksize)/stride + 1 (same for Wo); for ksize 1 the weight matrix is
+ * the pruned [Co][Ci] matrix of Section IV.D.
+ *
+ *   packed_dev  blob from rtoss_pack for the same desc and dictionary
+ *   x_dev       activations of type desc->dt, 16-byte aligned; must not overlap y_dev
+ *   y_dev       out: type cdesc->out_dt, 16-byte aligned
+ * Products are accumulated in fp32 (inputs fp16/bf16/fp32 are multiplied exactly or in
+ * fp32); the result is rounded once (nearest-even) when out_dt is a 16-bit type.
+ * Errors: RTOSS_ELAYOUT for RTOSS_NCHW (not implemented: the kernels stream channels-last
+ * tensors), RTOSS_ESHAPE, RTOSS_EDTYPE, RTOSS_EINVAL.
+ */
+rtoss_status rtoss_conv2d_pattern(const rtoss_wdesc* desc, const rtoss_cdesc* cdesc,
+                                  const uint16_t* masks_host, int P,
+                                  const void* packed_dev, const void* x_dev, void* y_dev,
+                                  void* hip_stream);
+
+/* Message for the last error on the calling thread ("" if none).  Static storage. */
+const char* rtoss_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RTOSS_H */

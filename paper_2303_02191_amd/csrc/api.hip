@@ -1,0 +1,246 @@
+// Host side of the C ABI: dictionary generation, argument validation, blob geometry and
+// dispatch to the kernel launchers.  Every check happens before the first HIP call, so
+// the error paths can be exercised on a machine without a GPU.
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <vector>
+
+#include "common.h"
+
+namespace rtoss {
+
+static thread_local char g_err[512] = "";
+
+rtoss_status fail(rtoss_status st, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+rtoss_status check_hip(hipError_t e, const char* what)
+{
+    if (e == hipSuccess) return RTOSS_OK;
+    return fail(RTOSS_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+// ---------------------------------------------------------------------------------------
+// Dictionary (Section IV.B): Eq. 1 candidates filtered by adjacency.
+// ---------------------------------------------------------------------------------------
+static unsigned neighbours_of(int t, bool eight)
+{
+    const int r = t / 3, c = t % 3;
+    unsigned nb = 0;
+    for (int dr = -1; dr <= 1; ++dr)
+        for (int dc = -1; dc <= 1; ++dc) {
+            if (!dr && !dc) continue;
+            if (!eight && dr && dc) continue;
+            const int rr = r + dr, cc = c + dc;
+            if (rr >= 0 && rr < 3 && cc >= 0 && cc < 3) nb |= 1u << (rr * 3 + cc);
+        }
+    return nb;
+}
+
+static unsigned halo_of(unsigned set, bool eight)
+{
+    unsigned h = 0;
+    for (int t = 0; t < 9; ++t)
+        if (set >> t & 1u) h |= neighbours_of(t, eight);
+    return h;
+}
+
+static bool one_component(unsigned m, bool eight)
+{
+    unsigned reach = m & (~m + 1u);  // lowest live tap
+    for (;;) {
+        const unsigned grown = reach | (halo_of(reach, eight) & m);
+        if (grown == reach) break;
+        reach = grown;
+    }
+    return reach == m;
+}
+
+static bool passes(unsigned m, rtoss_rule rule)
+{
+    switch (rule) {
+    case RTOSS_RULE_ALL: return true;
+    case RTOSS_RULE_ANYPAIR4: return __builtin_popcount(m) == 1 || (halo_of(m, false) & m) != 0;
+    case RTOSS_RULE_CONNECTED4: return one_component(m, false);
+    case RTOSS_RULE_CONNECTED8: return one_component(m, true);
+    }
+    return false;
+}
+
+static unsigned reverse9(unsigned m)
+{
+    unsigned r = 0;
+    for (int t = 0; t < 9; ++t) r |= (m >> t & 1u) << (8 - t);
+    return r;
+}
+
+// Validates a caller dictionary and copies it into launch-argument form.
+static rtoss_status load_dict(const uint16_t* masks_host, int P, Dict* out)
+{
+    if (!masks_host) return fail(RTOSS_EINVAL, "dictionary pointer is NULL");
+    if (P < 1 || P > kMaxPatterns) return fail(RTOSS_EINVAL, "dictionary size P=%d outside 1..%d", P, kMaxPatterns);
+    std::memset(out, 0, sizeof *out);
+    const int k = __builtin_popcount(masks_host[0]);
+    for (int p = 0; p < P; ++p) {
+        const unsigned m = masks_host[p];
+        if (m == 0 || m > 0x1ffu) return fail(RTOSS_EINVAL, "pattern %d (0x%x) is not a non-empty 9-bit mask", p, m);
+        if (__builtin_popcount(m) != k)
+            return fail(RTOSS_EINVAL, "pattern %d keeps %d taps but pattern 0 keeps %d: one k per dictionary", p,
+                        __builtin_popcount(m), k);
+        out->mask[p] = (uint16_t)m;
+    }
+    out->P = P;
+    out->k = k;
+    return RTOSS_OK;
+}
+
+static rtoss_status check_wdesc(const rtoss_wdesc* d)
+{
+    if (!d) return fail(RTOSS_EINVAL, "weight descriptor is NULL");
+    if (d->ksize != 1 && d->ksize != 3) return fail(RTOSS_ESHAPE, "ksize %d: only 1 and 3 are supported", d->ksize);
+    if (d->Co < 1 || d->Ci < 1) return fail(RTOSS_ESHAPE, "Co=%d Ci=%d must be positive", d->Co, d->Ci);
+    if ((int64_t)d->Co * d->Ci * d->ksize * d->ksize > (int64_t)1 << 40) return fail(RTOSS_ESHAPE, "weight tensor too large");
+    if (d->dt != RTOSS_F32 && d->dt != RTOSS_F16 && d->dt != RTOSS_BF16) return fail(RTOSS_EDTYPE, "bad weight dtype %d", (int)d->dt);
+    if (d->k < 1 || d->k > 9) return fail(RTOSS_EINVAL, "k=%d outside 1..9", d->k);
+    return RTOSS_OK;
+}
+
+rtoss_status blob_geometry(const rtoss_wdesc* d, const Dict& dict, BlobGeometry* g)
+{
+    (void)dict;
+    std::memset(g, 0, sizeof *g);
+    g->n_elems = (int64_t)d->Co * d->Ci * d->ksize * d->ksize;
+    g->G = g->n_elems / 9;
+    g->live_off = 0;
+    g->idx_off = align_up((size_t)g->G * d->k * elem_bytes(d->dt), 256);
+    size_t end = align_up(g->idx_off + (size_t)g->G, 256);
+    g->format = kFormatNone;
+    g->mat_off = 0;
+    g->mat_bytes = 0;
+    g->total = std::max<size_t>(end, 256);
+    return RTOSS_OK;
+}
+
+static bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) != 0; }
+
+}  // namespace rtoss
+
+using namespace rtoss;
+
+extern "C" {
+
+const char* rtoss_last_error(void) { return g_err; }
+
+rtoss_status rtoss_pattern_dict(int k, rtoss_rule rule, uint16_t* masks_host, int cap, int* P)
+{
+    if (!P) return fail(RTOSS_EINVAL, "P is NULL");
+    if (k < 1 || k > 9) return fail(RTOSS_EINVAL, "k=%d outside 1..9", k);
+    if ((int)rule < 0 || (int)rule > 3) return fail(RTOSS_EINVAL, "unknown rule %d", (int)rule);
+    if (cap < 0 || (cap > 0 && !masks_host)) return fail(RTOSS_EINVAL, "masks is NULL but cap=%d", cap);
+    // Lexicographic order of ascending tap tuples == descending order of the bit-reversed mask.
+    std::vector<unsigned> kept;
+    for (unsigned m = 1; m < 512; ++m)
+        if (__builtin_popcount(m) == k && passes(m, rule)) kept.push_back(m);
+    std::sort(kept.begin(), kept.end(), [](unsigned a, unsigned b) { return reverse9(a) > reverse9(b); });
+    *P = (int)kept.size();
+    for (int i = 0; i < cap && i < (int)kept.size(); ++i) masks_host[i] = (uint16_t)kept[i];
+    if (cap > 0 && cap < (int)kept.size()) return fail(RTOSS_ENOSPACE, "dictionary has %d patterns, cap is %d", *P, cap);
+    return RTOSS_OK;
+}
+
+rtoss_status rtoss_select_patterns(const void* w_dev, rtoss_dtype dt, int64_t n_elems, const uint16_t* masks_host, int P,
+                                   uint8_t* idx_dev, void* hip_stream)
+{
+    if (dt != RTOSS_F32 && dt != RTOSS_F16 && dt != RTOSS_BF16) return fail(RTOSS_EDTYPE, "bad dtype %d", (int)dt);
+    if (n_elems < 0) return fail(RTOSS_EINVAL, "n_elems=%lld is negative", (long long)n_elems);
+    Dict dict;
+    if (rtoss_status st = load_dict(masks_host, P, &dict)) return st;
+    const int64_t G = n_elems / 9;
+    if (G == 0) return RTOSS_OK;
+    if (!w_dev || !idx_dev) return fail(RTOSS_EINVAL, "w_dev or idx_dev is NULL");
+    if (misaligned(w_dev, elem_bytes(dt))) return fail(RTOSS_EINVAL, "w_dev is not aligned to its element size");
+    return launch_select(w_dev, dt, G, dict, idx_dev, (hipStream_t)hip_stream);
+}
+
+rtoss_status rtoss_pack_size(const rtoss_wdesc* desc, const uint16_t* masks_host, int P, size_t* packed_bytes,
+                             size_t* workspace_bytes)
+{
+    if (rtoss_status st = check_wdesc(desc)) return st;
+    if (!packed_bytes || !workspace_bytes) return fail(RTOSS_EINVAL, "size output pointer is NULL");
+    Dict dict;
+    if (rtoss_status st = load_dict(masks_host, P, &dict)) return st;
+    if (dict.k != desc->k) return fail(RTOSS_EINVAL, "dictionary keeps %d taps, descriptor says k=%d", dict.k, desc->k);
+    BlobGeometry g;
+    if (rtoss_status st = blob_geometry(desc, dict, &g)) return st;
+    *packed_bytes = g.total;
+    *workspace_bytes = 0;
+    return RTOSS_OK;
+}
+
+rtoss_status rtoss_pack(const rtoss_wdesc* desc, const void* w_dev, const uint8_t* idx_dev, const uint16_t* masks_host,
+                        int P, void* packed_dev, size_t packed_bytes, void* workspace_dev, size_t workspace_bytes,
+                        void* hip_stream)
+{
+    (void)workspace_dev;
+    (void)workspace_bytes;
+    if (rtoss_status st = check_wdesc(desc)) return st;
+    Dict dict;
+    if (rtoss_status st = load_dict(masks_host, P, &dict)) return st;
+    if (dict.k != desc->k) return fail(RTOSS_EINVAL, "dictionary keeps %d taps, descriptor says k=%d", dict.k, desc->k);
+    BlobGeometry g;
+    if (rtoss_status st = blob_geometry(desc, dict, &g)) return st;
+    if (!packed_dev) return fail(RTOSS_EINVAL, "packed_dev is NULL");
+    if (packed_bytes < g.total)
+        return fail(RTOSS_ENOSPACE, "packed buffer has %zu bytes, %zu needed", packed_bytes, g.total);
+    if (misaligned(packed_dev, 256)) return fail(RTOSS_EINVAL, "packed_dev is not 256-byte aligned");
+    if (g.G > 0 && (!w_dev || !idx_dev)) return fail(RTOSS_EINVAL, "w_dev or idx_dev is NULL");
+    if (misaligned(w_dev, elem_bytes(desc->dt))) return fail(RTOSS_EINVAL, "w_dev is not aligned to its element size");
+    hipStream_t s = (hipStream_t)hip_stream;
+    char* blob = (char*)packed_dev;
+    return launch_pack_live(*desc, w_dev, idx_dev, dict, blob + g.live_off, (uint8_t*)(blob + g.idx_off), g.G, s);
+}
+
+rtoss_status rtoss_conv2d_pattern(const rtoss_wdesc* desc, const rtoss_cdesc* c, const uint16_t* masks_host, int P,
+                                  const void* packed_dev, const void* x_dev, void* y_dev, void* hip_stream)
+{
+    if (rtoss_status st = check_wdesc(desc)) return st;
+    if (!c) return fail(RTOSS_EINVAL, "conv descriptor is NULL");
+    Dict dict;
+    if (rtoss_status st = load_dict(masks_host, P, &dict)) return st;
+    if (dict.k != desc->k) return fail(RTOSS_EINVAL, "dictionary keeps %d taps, descriptor says k=%d", dict.k, desc->k);
+    if (c->layout == RTOSS_NCHW) return fail(RTOSS_ELAYOUT, "NCHW activations are not implemented; pass channels-last tensors");
+    if (c->layout != RTOSS_NHWC) return fail(RTOSS_EINVAL, "unknown layout %d", (int)c->layout);
+    if (c->stride != 1 && c->stride != 2) return fail(RTOSS_ESHAPE, "stride %d: only 1 and 2 are supported", c->stride);
+    if (desc->ksize == 1 && c->stride != 1) return fail(RTOSS_ESHAPE, "1x1 convolution supports stride 1 only");
+    if (c->pad != desc->ksize / 2) return fail(RTOSS_ESHAPE, "pad %d must equal ksize/2 = %d", c->pad, desc->ksize / 2);
+    if (c->N < 1 || c->H < 1 || c->W < 1) return fail(RTOSS_ESHAPE, "N=%d H=%d W=%d must be positive", c->N, c->H, c->W);
+    if (c->out_dt != desc->dt && c->out_dt != RTOSS_F32)
+        return fail(RTOSS_EDTYPE, "out_dt must be the weight dtype or fp32");
+    const int64_t Ho = (c->H + 2 * c->pad - desc->ksize) / c->stride + 1;
+    const int64_t Wo = (c->W + 2 * c->pad - desc->ksize) / c->stride + 1;
+    if (Ho < 1 || Wo < 1) return fail(RTOSS_ESHAPE, "empty output %lldx%lld", (long long)Ho, (long long)Wo);
+    if ((int64_t)c->N * c->H * c->W * desc->Ci >= (int64_t)1 << 40 || (int64_t)c->N * Ho * Wo * desc->Co >= (int64_t)1 << 40)
+        return fail(RTOSS_ESHAPE, "activation tensor too large");
+    if (!packed_dev || !x_dev || !y_dev) return fail(RTOSS_EINVAL, "packed_dev, x_dev or y_dev is NULL");
+    if (misaligned(packed_dev, 256)) return fail(RTOSS_EINVAL, "packed_dev is not 256-byte aligned");
+    if (misaligned(x_dev, 16) || misaligned(y_dev, 16)) return fail(RTOSS_EINVAL, "x_dev and y_dev must be 16-byte aligned");
+    const size_t xb = (size_t)c->N * c->H * c->W * desc->Ci * elem_bytes(desc->dt);
+    const size_t yb = (size_t)c->N * Ho * Wo * desc->Co * elem_bytes(c->out_dt);
+    const char *xa = (const char*)x_dev, *ya = (const char*)y_dev;
+    if (xa < ya + yb && ya < xa + xb) return fail(RTOSS_EINVAL, "x and y overlap");
+    BlobGeometry g;
+    if (rtoss_status st = blob_geometry(desc, dict, &g)) return st;
+    const char* blob = (const char*)packed_dev;
+    return launch_conv_direct(*desc, *c, dict, blob + g.live_off, (const uint8_t*)(blob + g.idx_off), x_dev, y_dev,
+                              (hipStream_t)hip_stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,65 @@
+// Internal declarations shared by the host API and the kernel launchers.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "rtoss.h"
+
+namespace rtoss {
+
+constexpr int kMaxPatterns = 255;
+
+// A dictionary travels to every kernel by value in the launch arguments, so the host
+// array can be released as soon as the call returns and no device copy is needed.
+struct Dict {
+    uint16_t mask[256];
+    int P;
+    int k;
+};
+
+// Decoded dictionary for the convolution kernels: tap[p][j] = j-th live tap of pattern p
+// in ascending order (unused entries 0).
+struct TapTable {
+    uint8_t tap[256][9];
+};
+
+inline int elem_bytes(rtoss_dtype dt) { return dt == RTOSS_F32 ? 4 : 2; }
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ----- packed blob geometry (host side; the kernels receive section pointers) -----
+enum MatrixFormat {
+    kFormatNone = 0,    // only the live list (section 0): direct kernels
+    kFormatDense = 1,   // zero-filled matrix-core fragments
+    kFormatSparse24 = 2 // 2-of-4 compressed fragments + indices
+};
+
+struct BlobGeometry {
+    int64_t G;          // number of groups of 9
+    int64_t n_elems;    // Co*Ci*ksize*ksize
+    size_t live_off;    // [G][k] values
+    size_t idx_off;     // [G] bytes
+    MatrixFormat format;
+    size_t mat_off;     // matrix-core section (0 if none)
+    size_t mat_bytes;
+    size_t total;
+};
+
+// Filled by host code in api.cpp.
+rtoss_status blob_geometry(const rtoss_wdesc* d, const Dict& dict, BlobGeometry* out);
+
+// ----- error plumbing -----
+rtoss_status fail(rtoss_status st, const char* fmt, ...);
+rtoss_status check_hip(hipError_t e, const char* what);
+
+// ----- launchers (one per kernel family; defined next to the kernels) -----
+rtoss_status launch_select(const void* w, rtoss_dtype dt, int64_t G, const Dict& dict, uint8_t* idx, hipStream_t s);
+
+rtoss_status launch_pack_live(const rtoss_wdesc& d, const void* w, const uint8_t* idx, const Dict& dict,
+                              void* live_values, uint8_t* live_idx, int64_t G, hipStream_t s);
+
+rtoss_status launch_conv_direct(const rtoss_wdesc& d, const rtoss_cdesc& c, const Dict& dict, const void* live_values,
+                                const uint8_t* live_idx, const void* x, void* y, hipStream_t s);
+
+}  // namespace rtoss

@@ -1,0 +1,165 @@
+// Direct pattern-sparse convolution on the vector ALUs (fp32 accumulate).
+//
+// This is the path for layers the matrix cores do not fit: fp32 tensors, very small
+// channel counts, and any shape the fragment layouts do not cover.  It multiplies only
+// the k surviving taps of every kernel (Section II.B: zero weights are skipped).
+//
+// Mapping: a workgroup owns an 8x8 tile of output positions (one position per lane) and a
+// block of output channels; each of its 4 wavefronts owns kCoPerWave of those channels, so
+// the weight, its pattern index and its tap offsets are wave-uniform and every lane reads
+// the activation tile in LDS at "own position + uniform tap offset", which is conflict
+// free for stride 1.  The activation tile (with its halo) is staged channel-chunk by
+// channel-chunk from channels-last global memory into LDS as fp32, channel-major.
+#include "common.h"
+#include "dtypes.h"
+
+namespace rtoss {
+
+constexpr int kTile = 8;        // output tile is kTile x kTile positions
+constexpr int kCoPerWave = 8;   // accumulators per lane
+constexpr int kWaves = 4;
+constexpr int kCoPerBlock = kCoPerWave * kWaves;
+constexpr int kChunk = 16;      // input channels staged per round
+
+template <int KS, int S> struct Halo {
+    static constexpr int side = (kTile - 1) * S + KS;
+    static constexpr int count = side * side;
+    static constexpr int padded = count | 1;  // odd row length: channel-major writes spread over banks
+};
+
+template <typename T, typename TO, int KS, int S>
+__global__ __launch_bounds__(256) void conv_direct_kernel(const T* __restrict__ x, TO* __restrict__ y,
+                                                          const T* __restrict__ live, const uint8_t* __restrict__ lidx,
+                                                          Dict dict, int N, int H, int W, int Ci, int Co, int Ho, int Wo,
+                                                          int tiles_w, int relu, int64_t G)
+{
+    using HL = Halo<KS, S>;
+    __shared__ float xs[kChunk * HL::padded];
+    __shared__ int16_t tapoff[256 * 9];  // LDS offset of the j-th live tap of pattern p (3x3 only)
+    __shared__ uint16_t masks[256];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int tile = blockIdx.x;
+    const int th = tile / tiles_w, tw = tile % tiles_w;
+    const int n = blockIdx.z;
+    const int co_base = blockIdx.y * kCoPerBlock + wave * kCoPerWave;
+    const int k = dict.k;
+
+    masks[tid] = dict.mask[tid];
+    if (KS == 3) {
+        const unsigned m = dict.mask[tid];
+        int j = 0;
+        for (int t = 0; t < 9; ++t)
+            if ((m >> t) & 1u) tapoff[tid * 9 + j++] = (int16_t)((t / 3) * HL::side + (t % 3));
+        for (; j < 9; ++j) tapoff[tid * 9 + j] = 0;
+    }
+
+    const int oh0 = th * kTile, ow0 = tw * kTile;
+    const int ih0 = oh0 * S - (KS / 2), iw0 = ow0 * S - (KS / 2);
+    const int r = lane / kTile, c = lane % kTile;
+    const int base = (r * S) * HL::side + c * S;
+
+    float acc[kCoPerWave];
+#pragma unroll
+    for (int i = 0; i < kCoPerWave; ++i) acc[i] = 0.f;
+
+    for (int ci0 = 0; ci0 < Ci; ci0 += kChunk) {
+        const int nch = Ci - ci0 < kChunk ? Ci - ci0 : kChunk;
+        __syncthreads();  // previous chunk fully consumed (also orders the table writes above)
+        for (int e = tid; e < HL::count * kChunk; e += 256) {
+            const int ch = e % kChunk, pos = e / kChunk;
+            const int ih = ih0 + pos / HL::side, iw = iw0 + pos % HL::side;
+            float v = 0.f;
+            if (ch < nch && ih >= 0 && ih < H && iw >= 0 && iw < W)
+                v = to_f32(x[(((int64_t)n * H + ih) * W + iw) * Ci + ci0 + ch]);
+            xs[ch * HL::padded + pos] = v;
+        }
+        __syncthreads();
+
+        for (int ch = 0; ch < nch; ++ch) {
+            const float* xc = xs + ch * HL::padded + base;
+#pragma unroll
+            for (int i = 0; i < kCoPerWave; ++i) {
+                const int co = co_base + i;
+                if (co >= Co) break;  // wave-uniform
+                if (KS == 3) {
+                    const int64_t g = (int64_t)co * Ci + ci0 + ch;
+                    const int p = lidx[g];
+                    const T* wv = live + g * k;
+                    const int16_t* to = tapoff + p * 9;
+                    for (int j = 0; j < k; ++j) acc[i] += to_f32(wv[j]) * xc[to[j]];
+                } else {
+                    // 1x1: the 9-groups run along the flattened [Co][Ci] matrix and may
+                    // straddle rows; element f belongs to group f/9 at tap f%9.
+                    const int64_t f = (int64_t)co * Ci + ci0 + ch;
+                    const int64_t g = f / 9;
+                    const int t = (int)(f - g * 9);
+                    if (g < G) {
+                        const unsigned m = masks[lidx[g]];
+                        if ((m >> t) & 1u) {
+                            const int j = __builtin_popcount(m & ((1u << t) - 1u));
+                            acc[i] += to_f32(live[g * k + j]) * xc[0];
+                        }
+                    }
+                }
+            }
+        }
+    }
+
+    const int oh = oh0 + r, ow = ow0 + c;
+    if (oh < Ho && ow < Wo) {
+        TO* yp = y + (((int64_t)n * Ho + oh) * Wo + ow) * Co;
+#pragma unroll
+        for (int i = 0; i < kCoPerWave; ++i) {
+            const int co = co_base + i;
+            if (co < Co) {
+                float v = acc[i];
+                if (relu) v = v > 0.f ? v : 0.f;
+                store_from_f32<TO>(yp + co, v);
+            }
+        }
+    }
+}
+
+template <typename T, typename TO>
+static rtoss_status launch_typed(const rtoss_wdesc& d, const rtoss_cdesc& c, const Dict& dict, const void* live,
+                                 const uint8_t* lidx, const void* x, void* y, hipStream_t s)
+{
+    const int Ho = (c.H + 2 * c.pad - d.ksize) / c.stride + 1;
+    const int Wo = (c.W + 2 * c.pad - d.ksize) / c.stride + 1;
+    const int tiles_h = (Ho + kTile - 1) / kTile, tiles_w = (Wo + kTile - 1) / kTile;
+    const int64_t G = (int64_t)d.Co * d.Ci * d.ksize * d.ksize / 9;
+    if (c.N > 65535 || (d.Co + kCoPerBlock - 1) / kCoPerBlock > 65535)
+        return fail(RTOSS_ESHAPE, "conv: batch or channel count too large for the direct kernel");
+    dim3 grid((unsigned)(tiles_h * tiles_w), (unsigned)((d.Co + kCoPerBlock - 1) / kCoPerBlock), (unsigned)c.N);
+    dim3 block(256);
+#define RTOSS_LAUNCH(KS, S)                                                                                       \
+    conv_direct_kernel<T, TO, KS, S><<<grid, block, 0, s>>>((const T*)x, (TO*)y, (const T*)live, lidx, dict, c.N, c.H, \
+                                                            c.W, d.Ci, d.Co, Ho, Wo, tiles_w, c.fuse_relu, G)
+    if (d.ksize == 3 && c.stride == 1) RTOSS_LAUNCH(3, 1);
+    else if (d.ksize == 3 && c.stride == 2) RTOSS_LAUNCH(3, 2);
+    else if (d.ksize == 1 && c.stride == 1) RTOSS_LAUNCH(1, 1);
+    else return fail(RTOSS_ESHAPE, "conv: unsupported ksize/stride %d/%d", d.ksize, c.stride);
+#undef RTOSS_LAUNCH
+    return check_hip(hipGetLastError(), "conv launch");
+}
+
+rtoss_status launch_conv_direct(const rtoss_wdesc& d, const rtoss_cdesc& c, const Dict& dict, const void* live_values,
+                                const uint8_t* live_idx, const void* x, void* y, hipStream_t s)
+{
+    const bool f32out = c.out_dt == RTOSS_F32;
+    switch (d.dt) {
+    case RTOSS_F32: return launch_typed<float, float>(d, c, dict, live_values, live_idx, x, y, s);
+    case RTOSS_F16:
+        return f32out ? launch_typed<f16_t, float>(d, c, dict, live_values, live_idx, x, y, s)
+                      : launch_typed<f16_t, f16_t>(d, c, dict, live_values, live_idx, x, y, s);
+    case RTOSS_BF16:
+        return f32out ? launch_typed<bf16_t, float>(d, c, dict, live_values, live_idx, x, y, s)
+                      : launch_typed<bf16_t, bf16_t>(d, c, dict, live_values, live_idx, x, y, s);
+    }
+    return fail(RTOSS_EDTYPE, "conv: bad dtype");
+}
+
+}  // namespace rtoss

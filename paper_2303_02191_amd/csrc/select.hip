@@ -1,0 +1,79 @@
+// Pattern selection (Section IV.C, Algorithm 2 scoring loop and best-fit choice, on the
+// flat 9-element groups of Section IV.D, Algorithm 3).
+//
+// Mapping: one workgroup of 256 lanes scores 64 groups.  The 9*64 weights of those groups
+// are one contiguous span; the lanes load it element-wise (coalesced), square it in fp64
+// and park the squares in LDS.  Four neighbouring lanes share a group: lane q scores the
+// patterns q, q+4, q+8, ... in ascending order, then the four (score, index) pairs are
+// merged with two cross-lane exchanges.  Sums run over the live taps in ascending tap
+// order in fp64, comparisons are strict, and the merge prefers the lower index on equal
+// scores, so the result equals a serial ascending scan bit for bit.
+#include "common.h"
+#include "dtypes.h"
+
+namespace rtoss {
+
+constexpr int kSelLanesPerGroup = 4;
+constexpr int kSelBlock = 256;
+constexpr int kSelGroupsPerBlock = kSelBlock / kSelLanesPerGroup;
+
+template <typename T>
+__global__ __launch_bounds__(kSelBlock) void select_kernel(const T* __restrict__ w, int64_t G, Dict dict,
+                                                           uint8_t* __restrict__ idx)
+{
+    __shared__ double sq[kSelGroupsPerBlock * 9];
+    __shared__ uint16_t masks[256];
+
+    const int tid = threadIdx.x;
+    const int64_t g0 = (int64_t)blockIdx.x * kSelGroupsPerBlock;
+    const int64_t remaining = G - g0;
+    const int ngroups = remaining < kSelGroupsPerBlock ? (int)remaining : kSelGroupsPerBlock;
+
+    masks[tid] = dict.mask[tid];
+    const T* span = w + g0 * 9;
+    for (int e = tid; e < ngroups * 9; e += kSelBlock) {
+        double v = (double)to_f32(span[e]);
+        sq[e] = v * v;
+    }
+    __syncthreads();
+
+    const int gl = tid / kSelLanesPerGroup;
+    const int q = tid % kSelLanesPerGroup;
+    double best_s = -1.0;  // below every real score
+    int best_p = 0xffff;   // "none yet"
+    if (gl < ngroups) {
+        double s9[9];
+#pragma unroll
+        for (int t = 0; t < 9; ++t) s9[t] = sq[gl * 9 + t];
+        for (int p = q; p < dict.P; p += kSelLanesPerGroup) {
+            const unsigned m = masks[p];
+            double s = 0.0;
+#pragma unroll
+            for (int t = 0; t < 9; ++t) s = ((m >> t) & 1u) ? s + s9[t] : s;
+            if (s > best_s) { best_s = s; best_p = p; }
+        }
+    }
+#pragma unroll
+    for (int d = 1; d < kSelLanesPerGroup; d <<= 1) {
+        const double o_s = __shfl_xor(best_s, d);
+        const int o_p = __shfl_xor(best_p, d);
+        if (o_s > best_s || (o_s == best_s && o_p < best_p)) { best_s = o_s; best_p = o_p; }
+    }
+    if (gl < ngroups && q == 0) idx[g0 + gl] = (uint8_t)(best_p == 0xffff ? 0 : best_p);
+}
+
+rtoss_status launch_select(const void* w, rtoss_dtype dt, int64_t G, const Dict& dict, uint8_t* idx, hipStream_t s)
+{
+    if (G == 0) return RTOSS_OK;
+    const int64_t blocks = (G + kSelGroupsPerBlock - 1) / kSelGroupsPerBlock;
+    if (blocks > 0x7fffffffLL) return fail(RTOSS_ESHAPE, "select: too many groups (%lld)", (long long)G);
+    dim3 grid((unsigned)blocks), block(kSelBlock);
+    switch (dt) {
+    case RTOSS_F32: select_kernel<float><<<grid, block, 0, s>>>((const float*)w, G, dict, idx); break;
+    case RTOSS_F16: select_kernel<f16_t><<<grid, block, 0, s>>>((const f16_t*)w, G, dict, idx); break;
+    case RTOSS_BF16: select_kernel<bf16_t><<<grid, block, 0, s>>>((const bf16_t*)w, G, dict, idx); break;
+    }
+    return check_hip(hipGetLastError(), "select launch");
+}
+
+}  // namespace rtoss

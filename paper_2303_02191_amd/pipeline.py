@@ -1,0 +1,75 @@
+"""Convenience wrappers that hold torch device buffers and call the C ABI in order.
+
+No arithmetic happens here: torch is used for device memory and the current stream only;
+selection, packing and convolution all run in librtoss.so.
+"""
+import torch
+
+from . import binding as B
+
+TORCH_DTYPE = {B.F32: torch.float32, B.F16: torch.float16, B.BF16: torch.bfloat16}
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def to_device(store, dt):
+    """numpy storage array (float32 / float16 / uint16 bfloat16 bits) -> torch cuda tensor of dtype dt."""
+    t = torch.from_numpy(store)
+    if dt == B.BF16:
+        t = t.view(torch.bfloat16)
+    return t.cuda()
+
+
+def to_host(t):
+    """torch tensor -> numpy storage array (bfloat16 comes back as uint16 bits)."""
+    t = t.detach().cpu().contiguous()
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.uint16).numpy()
+    return t.numpy()
+
+
+def select_patterns(w, dt, masks):
+    """w: contiguous cuda tensor of weights (any shape). Returns uint8 cuda tensor [numel // 9]."""
+    assert w.is_cuda and w.is_contiguous()
+    idx = torch.empty(max(w.numel() // 9, 1), dtype=torch.uint8, device=w.device)
+    B.rtoss_select_patterns(w.data_ptr(), dt, w.numel(), masks, idx.data_ptr(), _stream())
+    return idx[: w.numel() // 9]
+
+
+class PackedLayer:
+    """One layer's packed blob plus the descriptors the convolution call needs."""
+
+    def __init__(self, Co, Ci, ksize, k, dt, masks, device="cuda"):
+        self.wdesc = B.WDesc(Co, Ci, ksize, k, dt)
+        self.masks = masks
+        self.dt = dt
+        self.packed_bytes, self.workspace_bytes = B.rtoss_pack_size(self.wdesc, masks)
+        # torch's caching allocator returns 512-byte aligned blocks
+        self.blob = torch.empty(self.packed_bytes, dtype=torch.uint8, device=device)
+        self.workspace = torch.empty(max(self.workspace_bytes, 1), dtype=torch.uint8, device=device)
+
+    def pack(self, w, idx):
+        assert w.is_cuda and w.is_contiguous() and idx.is_cuda
+        B.rtoss_pack(self.wdesc, w.data_ptr(), idx.data_ptr(), self.masks, self.blob.data_ptr(), self.packed_bytes,
+                     self.workspace.data_ptr(), self.workspace_bytes, _stream())
+        return self
+
+    def out_shape(self, x_shape, stride):
+        N, H, W, _ = x_shape
+        ks = self.wdesc.ksize
+        pad = ks // 2
+        return (N, (H + 2 * pad - ks) // stride + 1, (W + 2 * pad - ks) // stride + 1, self.wdesc.Co)
+
+    def conv(self, x, stride=1, relu=False, out_dt=None, y=None):
+        """x: channels-last cuda tensor [N, H, W, Ci] of the layer's dtype. Returns y [N, Ho, Wo, Co]."""
+        assert x.is_cuda and x.is_contiguous() and x.shape[3] == self.wdesc.Ci
+        out_dt = self.dt if out_dt is None else out_dt
+        if y is None:
+            y = torch.empty(self.out_shape(x.shape, stride), dtype=TORCH_DTYPE[out_dt], device=x.device)
+        N, H, W, _ = x.shape
+        cdesc = B.CDesc(N, H, W, stride, self.wdesc.ksize // 2, B.NHWC, out_dt, int(bool(relu)))
+        B.rtoss_conv2d_pattern(self.wdesc, cdesc, self.masks, self.blob.data_ptr(), x.data_ptr(), y.data_ptr(),
+                               _stream())
+        return y

@@ -1,0 +1,114 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol
+the header declares, generates the same dictionary as the oracle, and rejects bad arguments
+before touching the GPU."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2303_02191_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "rtoss.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(rtoss_[a-z0-9_]+)\s*\(", hdr))
+    assert {"rtoss_select_patterns", "rtoss_pack", "rtoss_conv2d_pattern"} <= declared
+    L = B.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert declared == set(B.EXPORTS)
+
+
+@pytest.mark.parametrize("rule", [0, 1, 2, 3])
+@pytest.mark.parametrize("k", range(1, 10))
+def test_dictionary_matches_oracle(k, rule):
+    assert B.rtoss_pattern_dict(k, rule).tolist() == oracle.pattern_dict(k, rule).tolist()
+
+
+def test_dictionary_errors():
+    P = ctypes.c_int(0)
+    L = B.lib()
+    assert L.rtoss_pattern_dict(0, 2, None, 0, ctypes.byref(P)) == B.EINVAL
+    assert L.rtoss_pattern_dict(3, 9, None, 0, ctypes.byref(P)) == B.EINVAL
+    assert L.rtoss_pattern_dict(3, 2, None, 0, None) == B.EINVAL
+    assert L.rtoss_pattern_dict(3, 2, None, 4, ctypes.byref(P)) == B.EINVAL
+    buf = (ctypes.c_uint16 * 4)()
+    assert L.rtoss_pattern_dict(3, 2, buf, 4, ctypes.byref(P)) == B.ENOSPACE
+    assert P.value == 22 and list(buf) == oracle.pattern_dict(3).tolist()[:4]
+    assert "22" in B.rtoss_last_error()
+
+
+def _status(fn, *a, **kw):
+    try:
+        fn(*a, **kw)
+    except B.RtossError as e:
+        return e.status
+    return B.OK
+
+
+def test_select_argument_errors():
+    masks = B.rtoss_pattern_dict(3)
+    fake = 0x1000  # never dereferenced: every case below fails validation first
+    assert _status(B.rtoss_select_patterns, fake, 7, 90, masks, fake) == B.EDTYPE
+    assert _status(B.rtoss_select_patterns, fake, B.F16, -1, masks, fake) == B.EINVAL
+    assert _status(B.rtoss_select_patterns, fake, B.F16, 90, None, fake) == B.EINVAL
+    assert _status(B.rtoss_select_patterns, fake, B.F16, 90, np.zeros(0, np.uint16), fake) == B.EINVAL
+    assert _status(B.rtoss_select_patterns, fake, B.F16, 90, np.ones(256, np.uint16), fake) == B.EINVAL
+    assert _status(B.rtoss_select_patterns, fake, B.F16, 90, np.array([7, 3], np.uint16), fake) == B.EINVAL  # mixed k
+    assert _status(B.rtoss_select_patterns, fake, B.F16, 90, np.array([0x200], np.uint16), fake) == B.EINVAL
+    assert _status(B.rtoss_select_patterns, fake, B.F16, 90, np.array([0], np.uint16), fake) == B.EINVAL
+    assert _status(B.rtoss_select_patterns, 0, B.F16, 90, masks, fake) == B.EINVAL
+    assert _status(B.rtoss_select_patterns, fake, B.F16, 90, masks, 0) == B.EINVAL
+    assert _status(B.rtoss_select_patterns, fake + 1, B.F16, 90, masks, fake) == B.EINVAL  # misaligned
+    # fewer than 9 elements: nothing to do, pointers are not looked at
+    assert _status(B.rtoss_select_patterns, 0, B.F16, 8, masks, 0) == B.OK
+
+
+def test_pack_size_and_pack_errors():
+    masks = B.rtoss_pattern_dict(3)
+    d = B.WDesc(64, 32, 3, 3, B.F16)
+    nbytes, ws = B.rtoss_pack_size(d, masks)
+    assert nbytes >= 64 * 32 * (3 * 2 + 1) and nbytes % 256 == 0
+    assert _status(B.rtoss_pack_size, B.WDesc(64, 32, 5, 3, B.F16), masks) == B.ESHAPE
+    assert _status(B.rtoss_pack_size, B.WDesc(0, 32, 3, 3, B.F16), masks) == B.ESHAPE
+    assert _status(B.rtoss_pack_size, B.WDesc(64, 32, 3, 2, B.F16), masks) == B.EINVAL  # k != popcount
+    assert _status(B.rtoss_pack_size, B.WDesc(64, 32, 3, 3, 9), masks) == B.EDTYPE
+    assert _status(B.rtoss_pack_size, None, masks) == B.EINVAL
+    fake = 0x10000
+    assert _status(B.rtoss_pack, d, fake, fake, masks, fake, nbytes - 1) == B.ENOSPACE
+    assert _status(B.rtoss_pack, d, fake, fake, masks, 0, nbytes) == B.EINVAL
+    assert _status(B.rtoss_pack, d, fake, fake, masks, fake + 16, nbytes) == B.EINVAL  # blob alignment
+    assert _status(B.rtoss_pack, d, 0, fake, masks, fake, nbytes) == B.EINVAL
+    assert _status(B.rtoss_pack, d, fake, 0, masks, fake, nbytes) == B.EINVAL
+
+
+def test_conv_argument_errors():
+    masks = B.rtoss_pattern_dict(3)
+    d = B.WDesc(64, 32, 3, 3, B.F16)
+    fake_p, fake_x, fake_y = 0x10000, 0x200000, 0x4000000
+    good = dict(N=1, H=16, W=16, stride=1, pad=1, layout=B.NHWC, out_dt=B.F16, fuse_relu=0)
+
+    def cd(**kw):
+        a = dict(good)
+        a.update(kw)
+        return B.CDesc(a["N"], a["H"], a["W"], a["stride"], a["pad"], a["layout"], a["out_dt"], a["fuse_relu"])
+
+    call = B.rtoss_conv2d_pattern
+    assert _status(call, d, cd(layout=B.NCHW), masks, fake_p, fake_x, fake_y) == B.ELAYOUT
+    assert _status(call, d, cd(stride=3), masks, fake_p, fake_x, fake_y) == B.ESHAPE
+    assert _status(call, d, cd(pad=0), masks, fake_p, fake_x, fake_y) == B.ESHAPE
+    assert _status(call, d, cd(N=0), masks, fake_p, fake_x, fake_y) == B.ESHAPE
+    assert _status(call, d, cd(out_dt=B.BF16), masks, fake_p, fake_x, fake_y) == B.EDTYPE
+    assert _status(call, d, None, masks, fake_p, fake_x, fake_y) == B.EINVAL
+    assert _status(call, d, cd(), masks, 0, fake_x, fake_y) == B.EINVAL
+    assert _status(call, d, cd(), masks, fake_p, fake_x + 2, fake_y) == B.EINVAL
+    assert _status(call, d, cd(), masks, fake_p, fake_x, fake_x + 64) == B.EINVAL  # overlap
+    assert _status(call, d, cd(), B.rtoss_pattern_dict(2), fake_p, fake_x, fake_y) == B.EINVAL  # k mismatch
+    d1 = B.WDesc(64, 32, 1, 3, B.F16)
+    assert _status(call, d1, cd(stride=2, pad=0), masks, fake_p, fake_x, fake_y) == B.ESHAPE

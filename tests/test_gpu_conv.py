@@ -1,0 +1,188 @@
+"""GPU parity: rtoss_conv2d_pattern vs the oracle's direct fp64 convolution.
+
+Tolerances: fp32 tensors  max|y - ref| <= 1e-5 * max|ref|;
+            fp16 / bf16 tensors with fp32 output  max|y - ref| <= 2e-3 * rms(ref);
+            16-bit output must equal the fp32 output rounded once to nearest-even.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2303_02191_amd import binding as B
+from paper_2303_02191_amd import workloads as wl
+
+from gpu_util import GpuLayer
+
+pytestmark = pytest.mark.gpu
+
+
+def check(y, ref, dt):
+    y = np.asarray(y, dtype=np.float64)
+    err = np.max(np.abs(y - ref))
+    if dt == wl.F32:
+        bound = 1e-5 * np.max(np.abs(ref))
+    else:
+        bound = 2e-3 * np.sqrt(np.mean(ref ** 2))
+    assert err <= bound, "max err %.3e > bound %.3e" % (err, bound)
+
+
+def run_case(dt, N, Ci, Co, H, W, ks, stride, k, relu, seed, x_dist="normal", w_std=0.05, rule=B.RULE_CONNECTED4):
+    rng = np.random.default_rng(seed)
+    masks = B.rtoss_pattern_dict(k, rule)
+    xa = rng.standard_normal((N, Ci, H, W)) if x_dist == "normal" else rng.uniform(-1, 1, (N, Ci, H, W))
+    xs = wl.round_to_dtype(xa, dt)
+    ws = wl.round_to_dtype(rng.standard_normal((Co, Ci, ks, ks)) * w_std, dt)
+    xv, wv = wl.to_f64(xs, dt), wl.to_f64(ws, dt)
+    idx = oracle.select(wv, masks)
+    ref = oracle.conv2d(xv, oracle.mask(wv, masks, idx), stride=stride, relu=relu)
+    g = GpuLayer(ws, dt, masks, k)
+    assert np.array_equal(g.idx_host(), idx)
+    y32 = g.conv_nchw(xs, stride=stride, relu=relu, out_dt=wl.F32)
+    assert y32.shape == ref.shape and y32.dtype == np.float32
+    check(y32, ref, dt)
+    if dt != wl.F32:
+        y16 = g.conv_nchw(xs, stride=stride, relu=relu)
+        assert np.array_equal(y16, wl.round_to_dtype(y32.astype(np.float64), dt))
+    return y32, ref
+
+
+SMALL = [
+    # N, Ci, Co, H,  W, ks, stride, k, relu
+    (1, 3, 32, 20, 20, 3, 2, 3, False),
+    (2, 16, 40, 9, 13, 3, 1, 2, True),
+    (1, 64, 64, 17, 23, 3, 1, 3, False),
+    (1, 64, 64, 17, 23, 3, 2, 3, True),
+    (3, 5, 7, 8, 8, 3, 1, 4, False),
+    (1, 1, 1, 1, 1, 3, 1, 2, False),
+    (1, 8, 8, 1, 5, 3, 2, 3, False),
+    (2, 32, 48, 10, 12, 1, 1, 2, False),
+    (1, 13, 7, 5, 6, 1, 1, 3, True),
+    (1, 256, 64, 6, 6, 1, 1, 2, False),
+    (1, 2, 2, 3, 3, 1, 1, 2, False),  # fewer than 9 weights: everything is tail, output is zero
+]
+
+
+@pytest.mark.parametrize("dt", [wl.F32, wl.F16, wl.BF16])
+@pytest.mark.parametrize("case", SMALL)
+def test_conv_small_shapes(dt, case):
+    N, Ci, Co, H, W, ks, stride, k, relu = case
+    run_case(dt, N, Ci, Co, H, W, ks, stride, k, relu, seed=hash(case) % 10000 + dt)
+
+
+def test_conv_all_ones_pattern_is_dense():
+    # k = 9: one pattern that keeps every tap -> ordinary dense convolution
+    run_case(wl.F16, 1, 16, 16, 9, 9, 3, 1, 9, False, seed=1, rule=B.RULE_ALL)
+    run_case(wl.F32, 1, 8, 8, 7, 7, 3, 2, 9, False, seed=2, rule=B.RULE_ALL)
+
+
+def test_conv_other_dictionaries():
+    run_case(wl.F16, 1, 32, 32, 12, 12, 3, 1, 3, False, seed=3, rule=B.RULE_ALL)        # 84 patterns
+    run_case(wl.BF16, 1, 32, 32, 12, 12, 3, 1, 4, True, seed=4, rule=B.RULE_CONNECTED8)  # 85 patterns
+    run_case(wl.F16, 1, 32, 32, 12, 12, 3, 2, 5, False, seed=5)
+
+
+def test_cfg1_full():
+    cfg = wl.get_config(1)
+    L = cfg.layers[0]
+    rng = wl.make_rng(cfg)
+    xs, xv = wl.draw_x(rng, cfg, L)
+    ws, wv = wl.draw_w(rng, cfg, L)
+    masks = B.rtoss_pattern_dict(cfg.k)
+    assert masks.size == 36
+    idx = oracle.select(wv, masks)
+    ref = oracle.conv2d(xv, oracle.mask(wv, masks, idx), stride=1)
+    g = GpuLayer(ws, cfg.dtype, masks, cfg.k)
+    assert np.array_equal(g.idx_host(), idx)
+    check(g.conv_nchw(xs, stride=1), ref, wl.F32)
+
+
+def _sample_points(rng, N, Co, Ho, Wo, n):
+    pts = np.stack([rng.integers(0, N, n), rng.integers(0, Co, n), rng.integers(0, Ho, n), rng.integers(0, Wo, n)], 1)
+    # always include the four corners and an edge midpoint (padding paths)
+    extra = [[0, 0, 0, 0], [N - 1, Co - 1, Ho - 1, Wo - 1], [0, Co - 1, 0, Wo - 1], [N - 1, 0, Ho - 1, 0],
+             [0, Co // 2, Ho // 2, 0]]
+    return np.concatenate([pts, np.array(extra)]).astype(np.int32)
+
+
+def _check_layer_sampled(cfg, L, xs, xv, ws, wv, masks, relu, npts, seed):
+    """Full-size layer: selection bit-exact, conv checked on sampled outputs + rms bound from them."""
+    idx = oracle.select(wv, masks)
+    wm = oracle.mask(wv, masks, idx)
+    g = GpuLayer(ws, cfg.dtype, masks, cfg.k)
+    assert np.array_equal(g.idx_host(), idx)
+    y32 = g.conv_nchw(xs, stride=L.stride, relu=relu, out_dt=wl.F32)
+    pts = _sample_points(np.random.default_rng(seed), xs.shape[0], L.Co, L.Ho, L.Wo, npts)
+    ref = oracle.conv2d_points(xv, wm, pts, stride=L.stride, relu=relu)
+    got = y32[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]].astype(np.float64)
+    err = np.max(np.abs(got - ref))
+    bound = 1e-5 * np.max(np.abs(ref)) if cfg.dtype == wl.F32 else 2e-3 * np.sqrt(np.mean(ref ** 2))
+    assert err <= bound, "max err %.3e > bound %.3e" % (err, bound)
+    assert np.isfinite(y32).all()
+    return g, y32
+
+
+def test_cfg2_full_layers():
+    cfg = wl.get_config(2)
+    rng = wl.make_rng(cfg)
+    masks = B.rtoss_pattern_dict(cfg.k)
+    assert masks.size == 22
+    for i, L in enumerate(cfg.layers):
+        xs, xv = wl.draw_x(rng, cfg, L)
+        ws, wv = wl.draw_w(rng, cfg, L)
+        _check_layer_sampled(cfg, L, xs, xv, ws, wv, masks, False, 4000, seed=i)
+
+
+def test_cfg3_full():
+    cfg = wl.get_config(3)
+    L = cfg.layers[0]
+    rng = wl.make_rng(cfg)
+    masks = B.rtoss_pattern_dict(cfg.k)
+    assert masks.size == 12
+    xs, xv = wl.draw_x(rng, cfg, L)
+    ws, wv = wl.draw_w(rng, cfg, L)
+    _check_layer_sampled(cfg, L, xs, xv, ws, wv, masks, False, 20000, seed=3)
+
+
+def test_cfg4_full_chain():
+    """Four stacked 3x3 layers with ReLU between; each layer is checked against the oracle fed
+    with the GPU's own stored (bf16) output of the previous layer."""
+    cfg = wl.get_config(4)
+    rng = wl.make_rng(cfg)
+    masks = B.rtoss_pattern_dict(cfg.k)
+    xs, xv = wl.draw_x(rng, cfg, cfg.layers[0])
+    weights = [wl.draw_w(rng, cfg, L) for L in cfg.layers]
+    for i, L in enumerate(cfg.layers):
+        ws, wv = weights[i]
+        g, y32 = _check_layer_sampled(cfg, L, xs, xv, ws, wv, masks, L.relu, 3000, seed=40 + i)
+        y16 = g.conv_nchw(xs, stride=1, relu=L.relu)
+        assert np.array_equal(y16, wl.round_to_dtype(y32.astype(np.float64), cfg.dtype))
+        xs, xv = y16, wl.to_f64(y16, cfg.dtype)
+
+
+def test_cfg5_layers_reduced_batch():
+    """Every distinct layer shape of the YOLOv5s-shaped set at full spatial size and batch 2
+    (sampled outputs); the batch-16 launch configuration is covered by test_cfg5_batch16_launch."""
+    cfg = wl.get_config(5)
+    masks = B.rtoss_pattern_dict(cfg.k)
+    seen = set()
+    rng = wl.make_rng(cfg)
+    for i, L in enumerate(cfg.layers):
+        key = (L.Ci, L.Co, L.H, L.ksize, L.stride)
+        if key in seen:
+            continue
+        seen.add(key)
+        xs, xv = wl.draw_x(rng, cfg, L, N=2)
+        ws, wv = wl.draw_w(rng, cfg, L)
+        _check_layer_sampled(cfg, L, xs, xv, ws, wv, masks, False, 1500, seed=500 + i)
+
+
+def test_cfg5_batch16_launch():
+    """Batch 16 (the benchmarked launch shape) on three representative layers."""
+    cfg = wl.get_config(5)
+    masks = B.rtoss_pattern_dict(cfg.k)
+    rng = np.random.default_rng(55)
+    for li in (1, 9, 36):
+        L = cfg.layers[li]
+        xs, xv = wl.draw_x(rng, cfg, L)
+        ws, wv = wl.draw_w(rng, cfg, L)
+        _check_layer_sampled(cfg, L, xs, xv, ws, wv, masks, False, 1500, seed=li)

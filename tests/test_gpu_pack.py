@@ -1,0 +1,32 @@
+"""GPU parity: rtoss_pack's live-weight section vs the oracle's mask step, bit-exact."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2303_02191_amd import binding as B
+from paper_2303_02191_amd import workloads as wl
+
+from gpu_util import GpuLayer, decode_live_section
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("dt", [wl.F32, wl.F16, wl.BF16])
+@pytest.mark.parametrize("Co,Ci,ks,k", [(64, 64, 3, 3), (5, 7, 3, 2), (32, 3, 3, 4), (256, 256, 1, 2), (7, 11, 1, 3),
+                                        (2, 4, 1, 2), (130, 70, 3, 5)])
+def test_pack_live_section(dt, Co, Ci, ks, k):
+    masks = B.rtoss_pattern_dict(k)
+    a = np.random.default_rng(Co * 31 + Ci + k).standard_normal((Co, Ci, ks, ks)) * 0.05
+    store = wl.round_to_dtype(a, dt)
+    vals = wl.to_f64(store, dt)
+    g = GpuLayer(store, dt, masks, k)
+    idx_want = oracle.select(vals, masks)
+    assert np.array_equal(g.idx_host(), idx_want)
+    wm, idx_blob = decode_live_section(g.blob_host(), Co, Ci, ks, k, dt, masks)
+    assert np.array_equal(idx_blob, idx_want)
+    want = oracle.mask(vals, masks, idx_want)
+    got = wl.to_f64(wm, dt)
+    assert np.array_equal(got, want)  # survivors bit-identical, everything else (and the tail) zero
+    tail = (Co * Ci * ks * ks) % 9
+    if tail:
+        assert (got.reshape(-1)[-tail:] == 0).all()

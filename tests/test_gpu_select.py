@@ -1,0 +1,92 @@
+"""GPU parity: rtoss_select_patterns vs the oracle, bit-exact (ties to the lowest index)."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2303_02191_amd import binding as B
+from paper_2303_02191_amd import workloads as wl
+
+from gpu_util import gpu_select
+
+pytestmark = pytest.mark.gpu
+
+
+def _draw(n, dt, seed, std=0.05):
+    a = np.random.default_rng(seed).standard_normal(n) * std
+    s = wl.round_to_dtype(a, dt)
+    return s, wl.to_f64(s, dt)
+
+
+@pytest.mark.parametrize("dt", [wl.F32, wl.F16, wl.BF16])
+@pytest.mark.parametrize("k,rule", [(2, 2), (3, 2), (4, 2), (3, 0), (4, 0), (5, 3), (1, 2), (8, 2)])
+@pytest.mark.parametrize("n", [9, 9 * 63 + 4, 9 * 64, 9 * 1000 + 8, 9 * 4099])
+def test_select_matches_oracle(dt, k, rule, n):
+    masks = B.rtoss_pattern_dict(k, rule)
+    store, vals = _draw(n, dt, seed=n + 17 * k + rule + 1000 * dt)
+    want = oracle.select(vals, masks)
+    got = gpu_select(store, dt, masks)
+    assert got.dtype == np.uint8 and got.shape == want.shape
+    assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("dt", [wl.F16, wl.BF16, wl.F32])
+def test_select_ties_and_specials(dt):
+    masks = B.rtoss_pattern_dict(3)
+    rng = np.random.default_rng(5)
+    # heavily quantised values: ties in almost every group
+    a = np.round(rng.standard_normal(9 * 5000) * 2) / 2
+    # specials: zeros, NaN, +-Inf, subnormals of the storage type, huge values
+    tiny = {wl.F32: 2.0 ** -140, wl.F16: 2.0 ** -20, wl.BF16: 2.0 ** -130}[dt]
+    big = {wl.F32: 3e38, wl.F16: 6e4, wl.BF16: 3e38}[dt]
+    sp = rng.choice(np.array([0.0, np.nan, np.inf, -np.inf, tiny, -tiny, 3 * tiny, big, -big, 1.0]), size=9 * 3000)
+    allnan = np.full(18, np.nan)
+    zeros = np.zeros(27)
+    a = np.concatenate([a, sp, allnan, zeros])
+    store = wl.round_to_dtype(a, dt)
+    vals = wl.to_f64(store, dt)
+    want = oracle.select(vals, masks)
+    got = gpu_select(store, dt, masks)
+    assert np.array_equal(got, want)
+    assert got[-5:].tolist() == [0, 0, 0, 0, 0]
+
+
+def test_select_empty_and_short():
+    masks = B.rtoss_pattern_dict(2)
+    assert gpu_select(np.zeros(0, np.float16), wl.F16, masks).size == 0
+    assert gpu_select(np.ones(8, np.float16), wl.F16, masks).size == 0
+
+
+def test_select_largest_dictionary():
+    # 126 patterns (k = 4 and 5 without the adjacency filter) and a 255-entry dictionary
+    for k in (4, 5):
+        masks = B.rtoss_pattern_dict(k, B.RULE_ALL)
+        store, vals = _draw(9 * 3001, wl.F16, seed=k)
+        assert np.array_equal(gpu_select(store, wl.F16, masks), oracle.select(vals, masks))
+    m4 = B.rtoss_pattern_dict(4, B.RULE_ALL)
+    masks = np.concatenate([m4, m4, m4[:3]])  # duplicates: the first copy must win
+    assert masks.size == 255
+    store, vals = _draw(9 * 777, wl.F32, seed=9)
+    got = gpu_select(store, wl.F32, masks)
+    assert np.array_equal(got, oracle.select(vals, masks))
+    assert got.max() < 126
+
+
+@pytest.mark.parametrize("cfg_i", [1, 2, 3, 4, 5])
+def test_select_full_configs(cfg_i):
+    """Every weight tensor of the five configurations at full size."""
+    cfg = wl.get_config(cfg_i)
+    masks = B.rtoss_pattern_dict(cfg.k)
+    rng = np.random.default_rng(1000 + cfg.seed)  # weights only; activations are not needed here
+    stores3, vals3 = [], []
+    for L in cfg.layers:
+        s, v = wl.draw_w(rng, cfg, L)
+        if L.ksize == 3:
+            stores3.append(s.reshape(-1))
+            vals3.append(v.reshape(-1))
+        else:  # 1x1 tensors carry a per-tensor tail: one call each
+            want = oracle.select(v, masks)
+            assert want.size == L.groups
+            assert np.array_equal(gpu_select(s.reshape(-1), cfg.dtype, masks), want)
+    if stores3:  # all 3x3 kernels of the configuration in one call
+        s, v = np.concatenate(stores3), np.concatenate(vals3)
+        assert np.array_equal(gpu_select(s, cfg.dtype, masks), oracle.select(v, masks))
