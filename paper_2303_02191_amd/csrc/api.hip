@@ -115,7 +115,6 @@ static rtoss_status check_wdesc(const rtoss_wdesc* d)
 
 rtoss_status blob_geometry(const rtoss_wdesc* d, const Dict& dict, BlobGeometry* g)
 {
-    (void)dict;
     std::memset(g, 0, sizeof *g);
     g->n_elems = (int64_t)d->Co * d->Ci * d->ksize * d->ksize;
     g->G = g->n_elems / 9;
@@ -125,6 +124,12 @@ rtoss_status blob_geometry(const rtoss_wdesc* d, const Dict& dict, BlobGeometry*
     g->format = kFormatNone;
     g->mat_off = 0;
     g->mat_bytes = 0;
+    if (sparse3x3_shape_ok(*d) && sparse3x3_dictionary_ok(dict)) {
+        g->format = kFormatSparse24;
+        g->mat_off = end;
+        g->mat_bytes = sparse3x3_section_bytes(*d);
+        end = align_up(end + g->mat_bytes, 256);
+    }
     g->total = std::max<size_t>(end, 256);
     return RTOSS_OK;
 }
@@ -205,7 +210,10 @@ rtoss_status rtoss_pack(const rtoss_wdesc* desc, const void* w_dev, const uint8_
     if (misaligned(w_dev, elem_bytes(desc->dt))) return fail(RTOSS_EINVAL, "w_dev is not aligned to its element size");
     hipStream_t s = (hipStream_t)hip_stream;
     char* blob = (char*)packed_dev;
-    return launch_pack_live(*desc, w_dev, idx_dev, dict, blob + g.live_off, (uint8_t*)(blob + g.idx_off), g.G, s);
+    if (rtoss_status st = launch_pack_live(*desc, w_dev, idx_dev, dict, blob + g.live_off, (uint8_t*)(blob + g.idx_off), g.G, s))
+        return st;
+    if (g.format == kFormatSparse24) return launch_pack_sparse3x3(*desc, w_dev, idx_dev, dict, blob + g.mat_off, s);
+    return RTOSS_OK;
 }
 
 rtoss_status rtoss_conv2d_pattern(const rtoss_wdesc* desc, const rtoss_cdesc* c, const uint16_t* masks_host, int P,
@@ -239,6 +247,8 @@ rtoss_status rtoss_conv2d_pattern(const rtoss_wdesc* desc, const rtoss_cdesc* c,
     BlobGeometry g;
     if (rtoss_status st = blob_geometry(desc, dict, &g)) return st;
     const char* blob = (const char*)packed_dev;
+    if (g.format == kFormatSparse24)
+        return launch_conv3x3_sparse(*desc, *c, blob + g.mat_off, x_dev, y_dev, (hipStream_t)hip_stream);
     return launch_conv_direct(*desc, *c, dict, blob + g.live_off, (const uint8_t*)(blob + g.idx_off), x_dev, y_dev,
                               (hipStream_t)hip_stream);
 }

@@ -62,4 +62,13 @@ rtoss_status launch_pack_live(const rtoss_wdesc& d, const void* w, const uint8_t
 rtoss_status launch_conv_direct(const rtoss_wdesc& d, const rtoss_cdesc& c, const Dict& dict, const void* live_values,
                                 const uint8_t* live_idx, const void* x, void* y, hipStream_t s);
 
+// 3x3 convolution on the sparse matrix instruction (conv3x3_sparse.hip)
+bool sparse3x3_dictionary_ok(const Dict& dict);
+bool sparse3x3_shape_ok(const rtoss_wdesc& d);
+size_t sparse3x3_section_bytes(const rtoss_wdesc& d);
+rtoss_status launch_pack_sparse3x3(const rtoss_wdesc& d, const void* w, const uint8_t* idx, const Dict& dict,
+                                   void* section, hipStream_t s);
+rtoss_status launch_conv3x3_sparse(const rtoss_wdesc& d, const rtoss_cdesc& c, const void* section, const void* x,
+                                   void* y, hipStream_t s);
+
 }  // namespace rtoss

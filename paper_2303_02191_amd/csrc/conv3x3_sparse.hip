@@ -1,0 +1,423 @@
+// 3x3 pattern-sparse convolution on the CDNA4 matrix cores (fp16 / bf16, fp32 accumulate),
+// and the packer that writes the weight fragments it streams.
+//
+// Why 2-of-4 structured sparsity fits pattern pruning (Section IV.B / IV.C): every kernel
+// keeps k taps chosen per kernel, so at matrix-tile granularity the zeros are unstructured
+// and a dense contraction cannot skip them.  The sparse matrix instruction
+// (v_smfmac_f32_16x16x64) accepts a per-row choice of 2 live values in every 4 K-slots.
+// For one input channel the 9 taps are split into the 4 corners {0,2,6,8}, the 4 edge
+// midpoints {1,3,5,7} and the centre {4}.  Whenever every dictionary pattern has at most
+// 2 corners and at most 2 edge midpoints (true for all edge-connected 2- and 3-entry
+// patterns: a connected path alternates between the two classes), the corner slots and
+// the edge slots of a channel are each one legal 2-of-4 group, and the centre tap is a
+// plain dense K-slot.  Per 32 input channels this costs 2+2 sparse steps and 1 dense step
+// instead of 9 dense steps.
+//
+// Instruction operand layout (wave64; r = lane % 16, q = lane / 16):
+//   dense  v_mfma_f32_16x16x32:  A lane holds row r, K = 8q .. 8q+7; B lane holds column r,
+//          K = 8q .. 8q+7; D lane holds column r, rows 4q .. 4q+3.
+//   sparse v_smfmac_f32_16x16x64: A lane holds 8 compressed values of row r in 4 pairs;
+//          pair g refers to the 4 B-values (column = any, B lane group 2*(q&1) + (g>>1),
+//          B elements 8*(q>>1) + 4*(g&1) .. +3); the two 2-bit fields at bits 4g and 4g+2
+//          of the 16-bit index say which of the 4 each compressed value multiplies.
+//          ABID selects the low (0) or high (1) half of the index register.
+//
+// Data flow of one workgroup (256 lanes = 4 waves): output tile = 16*TM output channels x
+// (RT x CT) blocks of 4x4 output positions; every wave owns all 16*TM channels and TN of
+// the position blocks.  K runs over stages of 32 input channels: the stage's weight
+// fragments (one contiguous chunk of the packed blob) and its activation tile with halo
+// (channels-last, 32 channels per position, 80-byte position stride) are prefetched from
+// global memory into registers while the previous stage is multiplied, then parked in
+// LDS.  B operands are read from LDS as 16-byte vectors (8 channels of one tap) and the
+// 4x4 (tap, channel) blocks are transposed in registers with byte permutes so that one
+// lane holds, for 4 channels, the 4 taps of a group.
+#include "common.h"
+#include "dtypes.h"
+
+namespace rtoss {
+
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef _Float16 h16 __attribute__((ext_vector_type(16)));
+typedef __bf16 b8 __attribute__((ext_vector_type(8)));
+typedef __bf16 b16 __attribute__((ext_vector_type(16)));
+
+template <typename T> struct Mat;
+template <> struct Mat<f16_t> {
+    static __device__ __forceinline__ f32x4 dense(u32x4 a, u32x4 b, f32x4 c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, a), __builtin_bit_cast(h8, b), c, 0, 0, 0);
+    }
+    template <int ABID> static __device__ __forceinline__ f32x4 sparse(u32x4 a, u32x8 b, f32x4 c, int idx)
+    {
+        return __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, a), __builtin_bit_cast(h16, b), c, idx, 0, ABID);
+    }
+};
+template <> struct Mat<bf16_t> {
+    static __device__ __forceinline__ f32x4 dense(u32x4 a, u32x4 b, f32x4 c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(b8, a), __builtin_bit_cast(b8, b), c, 0, 0, 0);
+    }
+    template <int ABID> static __device__ __forceinline__ f32x4 sparse(u32x4 a, u32x8 b, f32x4 c, int idx)
+    {
+        return __builtin_amdgcn_smfmac_f32_16x16x64_bf16(__builtin_bit_cast(b8, a), __builtin_bit_cast(b16, b), c, idx, 0, ABID);
+    }
+};
+
+// Packed weight fragments: per (stage of 32 input channels, tile of 16 output channels)
+//   5 operand fragments of 64 lanes x 16 bytes: corner step 0/1, edge step 0/1, centre
+//   then 2 index words per lane: [corner][lane], [edge][lane]; low half = step 0, high = step 1
+constexpr int kFragBytes = 1024;
+constexpr int kTileBytes = 5 * kFragBytes + 2 * 64 * 4;  // 5632
+constexpr int kXPosBytes = 80;                          // 32 channels x 2 B + 16 B pad
+
+__device__ __forceinline__ int tap_of_slot(int group, int f)
+{
+    // group 0: corners {0,2,6,8}; group 1: edge midpoints {1,3,5,7}
+    return group == 0 ? ((f & 1) * 2 + (f >> 1) * 6) : (f == 0 ? 1 : f == 1 ? 3 : f == 2 ? 5 : 7);
+}
+
+// Input channel (within a 32-channel stage) that pair g of lane-quarter q refers to in
+// sparse step `half`.
+__device__ __forceinline__ int stage_channel(int q, int g, int half)
+{
+    return 8 * (2 * (q & 1) + (g >> 1)) + 4 * half + 2 * (q >> 1) + (g & 1);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void pack_sparse3x3_kernel(const T* __restrict__ w, const uint8_t* __restrict__ idx,
+                                                             Dict dict, char* __restrict__ out, int Co, int Ci,
+                                                             int m_tiles, int64_t total_items)
+{
+    __shared__ uint16_t masks[256];
+    masks[threadIdx.x] = dict.mask[threadIdx.x];
+    __syncthreads();
+    const int64_t item = (int64_t)blockIdx.x * 256 + threadIdx.x;  // (stage, m_tile, step 0..4, lane)
+    if (item >= total_items) return;
+    const int lane = (int)(item % 64);
+    const int step = (int)((item / 64) % 5);
+    const int64_t tile = item / 320;  // stage * m_tiles + m_tile
+    const int mt = (int)(tile % m_tiles);
+    const int cb = (int)(tile / m_tiles);
+    const int r = lane % 16, q = lane / 16;
+    const int co = 16 * mt + r;
+    char* tile_out = out + tile * kTileBytes;
+    uint16_t vals[8];
+    if (step == 4) {  // dense centre tap: K = 8q + j
+        for (int j = 0; j < 8; ++j) {
+            const int ci = 32 * cb + 8 * q + j;
+            uint16_t v = 0;
+            if (co < Co && ci < Ci) {
+                const int64_t g9 = (int64_t)co * Ci + ci;
+                if ((masks[idx[g9]] >> 4) & 1u) v = __builtin_bit_cast(uint16_t, w[g9 * 9 + 4]);
+            }
+            vals[j] = v;
+        }
+    } else {
+        const int group = step >> 1, half = step & 1;
+        unsigned fields = 0;
+        for (int g = 0; g < 4; ++g) {
+            const int ci = 32 * cb + stage_channel(q, g, half);
+            uint16_t v[2] = {0, 0};
+            int f[2] = {0, 1};
+            if (co < Co && ci < Ci) {
+                const int64_t g9 = (int64_t)co * Ci + ci;
+                const unsigned m = masks[idx[g9]];
+                int n = 0;
+                for (int s = 0; s < 4; ++s) {
+                    const int t = tap_of_slot(group, s);
+                    if (((m >> t) & 1u) && n < 2) {
+                        v[n] = __builtin_bit_cast(uint16_t, w[g9 * 9 + t]);
+                        f[n] = s;
+                        ++n;
+                    }
+                }
+                if (n == 1) f[1] = (f[0] + 1) & 3;  // padding value 0 may point anywhere
+            }
+            vals[2 * g] = v[0];
+            vals[2 * g + 1] = v[1];
+            fields |= (unsigned)(f[0] | (f[1] << 2)) << (4 * g);
+        }
+        uint16_t* ip = (uint16_t*)(tile_out + 5 * kFragBytes + (group * 64 + lane) * 4 + half * 2);
+        *ip = (uint16_t)fields;
+    }
+    u32x4 pk;
+    pk.x = vals[0] | ((uint32_t)vals[1] << 16);
+    pk.y = vals[2] | ((uint32_t)vals[3] << 16);
+    pk.z = vals[4] | ((uint32_t)vals[5] << 16);
+    pk.w = vals[6] | ((uint32_t)vals[7] << 16);
+    *(u32x4*)(tile_out + step * kFragBytes + lane * 16) = pk;
+}
+
+// Channel tiles per stage in the packed section: padded so that every block of 8 tiles is complete.
+inline int padded_m_tiles(int Co) { return ((Co + 15) / 16 + 7) / 8 * 8; }
+
+template <int S, int RT, int CT> struct Geom {
+    static constexpr int TH = 4 * RT, TW = 4 * CT;                 // output tile
+    static constexpr int IH = (TH - 1) * S + 3, IW = (TW - 1) * S + 3;  // input tile with halo
+    static constexpr int LW = ((IW + 3) / 8) * 8 + 4;              // row pitch in positions, == 4 (mod 8), >= IW
+    static constexpr int x_bytes = IH * LW * kXPosBytes;
+    static constexpr int x_chunks = IH * IW * 4;                   // 16-byte chunks to fetch per stage
+};
+
+template <typename T, typename TO, int S, int TM, int TN, int RT, int CT>
+__global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restrict__ x, TO* __restrict__ y,
+                                                                const char* __restrict__ wfrag, int H, int W, int Ci,
+                                                                int Co, int Ho, int Wo, int m_tiles_total,
+                                                                int tiles_c, int relu)
+{
+    using G = Geom<S, RT, CT>;
+    static_assert(RT * CT == 4 * TN, "four waves share the position blocks of a workgroup");
+    constexpr int A_BYTES = TM * kTileBytes;
+    constexpr int A_CHUNKS = A_BYTES / 16;
+    constexpr int A_PER_THREAD = (A_CHUNKS + 255) / 256;
+    constexpr int X_PER_THREAD = (G::x_chunks + 255) / 256;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    char* lds_a = smem;
+    char* lds_x = smem + A_BYTES;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int tile_r = blockIdx.x / tiles_c, tile_c = blockIdx.x % tiles_c;
+    const int mt0 = blockIdx.y * TM;
+    const int n_img = blockIdx.z;
+    const int oh0 = tile_r * G::TH, ow0 = tile_c * G::TW;
+    const int ih0 = oh0 * S - 1, iw0 = ow0 * S - 1;
+    const int stages = Ci / 32;
+
+    // ---- prefetch bookkeeping: which 16-byte chunks this lane moves every stage ----
+    const char* a_src = wfrag + (int64_t)mt0 * kTileBytes + tid * 16;  // + stage * m_tiles_total * kTileBytes
+    const int64_t a_stage_stride = (int64_t)m_tiles_total * kTileBytes;
+    int x_lds_off[X_PER_THREAD];
+    int64_t x_src_off[X_PER_THREAD];  // element offset into x for stage 0, or -1 for a zero chunk / unused slot
+#pragma unroll
+    for (int i = 0; i < X_PER_THREAD; ++i) {
+        const int item = tid + i * 256;
+        const int pos = item >> 2, qd = item & 3;
+        const int pr = pos / G::IW, pc = pos % G::IW;
+        x_lds_off[i] = item < G::x_chunks ? (pr * G::LW + pc) * kXPosBytes + qd * 16 : -1;
+        const int ih = ih0 + pr, iw = iw0 + pc;
+        const bool inside = item < G::x_chunks && ih >= 0 && ih < H && iw >= 0 && iw < W;
+        x_src_off[i] = inside ? (((int64_t)n_img * H + ih) * W + iw) * Ci + qd * 8 : -1;
+    }
+    u32x4 a_reg[A_PER_THREAD], x_reg[X_PER_THREAD];
+
+    auto fetch = [&](int stage) {
+#pragma unroll
+        for (int i = 0; i < A_PER_THREAD; ++i)
+            if (tid + i * 256 < A_CHUNKS) a_reg[i] = *(const u32x4*)(a_src + stage * a_stage_stride + i * 4096);
+#pragma unroll
+        for (int i = 0; i < X_PER_THREAD; ++i) {
+            u32x4 v = {0, 0, 0, 0};
+            if (x_src_off[i] >= 0) v = *(const u32x4*)(x + x_src_off[i] + stage * 32);
+            x_reg[i] = v;
+        }
+    };
+    auto park = [&]() {
+#pragma unroll
+        for (int i = 0; i < A_PER_THREAD; ++i)
+            if (tid + i * 256 < A_CHUNKS) *(u32x4*)(lds_a + tid * 16 + i * 4096) = a_reg[i];
+#pragma unroll
+        for (int i = 0; i < X_PER_THREAD; ++i)
+            if (x_lds_off[i] >= 0) *(u32x4*)(lds_x + x_lds_off[i]) = x_reg[i];
+    };
+
+    // ---- per-lane read addresses of the B operand ----
+    const int nn = lane & 15, qq = lane >> 4;
+    const int pr = nn >> 2, pc = nn & 3;
+    int xb[TN];  // byte offset in lds_x of this lane's output position for each of its blocks (tap (0,0))
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int blk = wave * TN + j;
+        const int br = blk / CT, bc = blk % CT;
+        xb[j] = (((4 * br + pr) * S) * G::LW + (4 * bc + pc) * S) * kXPosBytes + qq * 16;
+    }
+
+    f32x4 acc[TM][TN];
+#pragma unroll
+    for (int m = 0; m < TM; ++m)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[m][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    fetch(0);
+    for (int stage = 0; stage < stages; ++stage) {
+        __syncthreads();  // every wave is done reading the previous stage
+        park();
+        __syncthreads();
+        if (stage + 1 < stages) fetch(stage + 1);
+
+#pragma unroll
+        for (int group = 0; group < 2; ++group) {
+            // B operands of both sparse steps of this tap group, for all TN position blocks
+            u32x8 bf[2][TN];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                u32x4 rr[4];
+#pragma unroll
+                for (int f = 0; f < 4; ++f) {
+                    const int t = group == 0 ? ((f & 1) * 2 + (f >> 1) * 6) : (2 * f + 1);
+                    rr[f] = *(const u32x4*)(lds_x + xb[j] + ((t / 3) * G::LW + (t % 3)) * kXPosBytes);
+                }
+                // element 4*c + f of a step = channel c (of this lane's 4), tap slot f
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    const uint32_t s0 = half ? rr[0].z : rr[0].x, s1 = half ? rr[1].z : rr[1].x;
+                    const uint32_t s2 = half ? rr[2].z : rr[2].x, s3 = half ? rr[3].z : rr[3].x;
+                    const uint32_t u0 = half ? rr[0].w : rr[0].y, u1 = half ? rr[1].w : rr[1].y;
+                    const uint32_t u2 = half ? rr[2].w : rr[2].y, u3 = half ? rr[3].w : rr[3].y;
+                    u32x8 b;
+                    b[0] = __builtin_amdgcn_perm(s1, s0, 0x05040100u);  // channel 0: taps 0,1
+                    b[1] = __builtin_amdgcn_perm(s3, s2, 0x05040100u);  // channel 0: taps 2,3
+                    b[2] = __builtin_amdgcn_perm(s1, s0, 0x07060302u);  // channel 1
+                    b[3] = __builtin_amdgcn_perm(s3, s2, 0x07060302u);
+                    b[4] = __builtin_amdgcn_perm(u1, u0, 0x05040100u);  // channel 2
+                    b[5] = __builtin_amdgcn_perm(u3, u2, 0x05040100u);
+                    b[6] = __builtin_amdgcn_perm(u1, u0, 0x07060302u);  // channel 3
+                    b[7] = __builtin_amdgcn_perm(u3, u2, 0x07060302u);
+                    bf[half][j] = b;
+                }
+            }
+#pragma unroll
+            for (int m = 0; m < TM; ++m) {
+                const char* at = lds_a + m * kTileBytes;
+                const int iw2 = *(const int*)(at + 5 * kFragBytes + (group * 64 + lane) * 4);
+                const u32x4 a0 = *(const u32x4*)(at + (group * 2 + 0) * kFragBytes + lane * 16);
+                const u32x4 a1 = *(const u32x4*)(at + (group * 2 + 1) * kFragBytes + lane * 16);
+#pragma unroll
+                for (int j = 0; j < TN; ++j) acc[m][j] = Mat<T>::template sparse<0>(a0, bf[0][j], acc[m][j], iw2);
+#pragma unroll
+                for (int j = 0; j < TN; ++j) acc[m][j] = Mat<T>::template sparse<1>(a1, bf[1][j], acc[m][j], iw2);
+            }
+        }
+        {  // centre tap: dense step over the 32 channels of the stage
+            u32x4 bc[TN];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) bc[j] = *(const u32x4*)(lds_x + xb[j] + (G::LW + 1) * kXPosBytes);
+#pragma unroll
+            for (int m = 0; m < TM; ++m) {
+                const u32x4 a = *(const u32x4*)(lds_a + m * kTileBytes + 4 * kFragBytes + lane * 16);
+#pragma unroll
+                for (int j = 0; j < TN; ++j) acc[m][j] = Mat<T>::dense(a, bc[j], acc[m][j]);
+            }
+        }
+    }
+
+    // ---- epilogue: D lane holds column nn (position), rows 4*qq .. 4*qq+3 (output channels) ----
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int blk = wave * TN + j;
+        const int oh = oh0 + 4 * (blk / CT) + pr, ow = ow0 + 4 * (blk % CT) + pc;
+        if (oh >= Ho || ow >= Wo) continue;
+        TO* yp = y + (((int64_t)n_img * Ho + oh) * Wo + ow) * Co;
+#pragma unroll
+        for (int m = 0; m < TM; ++m) {
+            const int co = 16 * (mt0 + m) + 4 * qq;
+            if (co >= Co) continue;
+            f32x4 v = acc[m][j];
+            if (relu) {
+                v.x = v.x > 0.f ? v.x : 0.f;
+                v.y = v.y > 0.f ? v.y : 0.f;
+                v.z = v.z > 0.f ? v.z : 0.f;
+                v.w = v.w > 0.f ? v.w : 0.f;
+            }
+            if constexpr (sizeof(TO) == 4) {
+                *(f32x4*)(yp + co) = v;
+            } else {
+                TO o[4];
+                store_from_f32<TO>(&o[0], v.x);
+                store_from_f32<TO>(&o[1], v.y);
+                store_from_f32<TO>(&o[2], v.z);
+                store_from_f32<TO>(&o[3], v.w);
+                *(uint2*)(yp + co) = *(const uint2*)o;
+            }
+        }
+    }
+}
+
+template <typename T, typename TO, int S, int TM, int TN, int RT, int CT>
+rtoss_status launch_variant(const rtoss_wdesc& d, const rtoss_cdesc& c, const char* wfrag, const void* x, void* y,
+                            hipStream_t s)
+{
+    using G = Geom<S, RT, CT>;
+    const int Ho = (c.H + 2 - 3) / S + 1, Wo = (c.W + 2 - 3) / S + 1;
+    const int tiles_r = (Ho + G::TH - 1) / G::TH, tiles_c = (Wo + G::TW - 1) / G::TW;
+    const int m_tiles_total = padded_m_tiles(d.Co);  // pitch of the packed section
+    const int co_blocks = ((d.Co + 15) / 16 + TM - 1) / TM;
+    const size_t smem = (size_t)TM * kTileBytes + G::x_bytes;
+    auto kern = conv3x3_sparse_kernel<T, TO, S, TM, TN, RT, CT>;
+    static bool attr_set = false;  // per instantiation
+    if (!attr_set) {
+        if (rtoss_status st = check_hip(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem),
+                                        "conv3x3 shared memory attribute"))
+            return st;
+        attr_set = true;
+    }
+    if (c.N > 65535 || co_blocks > 65535) return fail(RTOSS_ESHAPE, "conv: batch or channel count too large");
+    dim3 grid((unsigned)(tiles_r * tiles_c), (unsigned)co_blocks, (unsigned)c.N), block(256);
+    kern<<<grid, block, smem, s>>>((const T*)x, (TO*)y, wfrag, c.H, c.W, d.Ci, d.Co, Ho, Wo, m_tiles_total, tiles_c,
+                                   c.fuse_relu);
+    return check_hip(hipGetLastError(), "conv3x3 sparse launch");
+}
+
+template <typename T, typename TO>
+rtoss_status launch_typed(const rtoss_wdesc& d, const rtoss_cdesc& c, const char* wfrag, const void* x, void* y,
+                          hipStream_t s)
+{
+    // The fragment section is padded to a multiple of 8 channel tiles, so any TM <= 8 may over-read rows
+    // that hold zeros; outputs beyond Co are never stored.
+    if (c.stride == 1) return launch_variant<T, TO, 1, 8, 4, 4, 4>(d, c, wfrag, x, y, s);
+    return launch_variant<T, TO, 2, 8, 4, 4, 4>(d, c, wfrag, x, y, s);
+}
+
+}  // namespace
+
+// ---- host-visible entry points of this file ----
+
+bool sparse3x3_dictionary_ok(const Dict& dict)
+{
+    for (int p = 0; p < dict.P; ++p) {
+        const unsigned m = dict.mask[p];
+        if (__builtin_popcount(m & 0x145u) > 2 || __builtin_popcount(m & 0x0aau) > 2) return false;
+    }
+    return true;
+}
+
+bool sparse3x3_shape_ok(const rtoss_wdesc& d)
+{
+    return d.ksize == 3 && (d.dt == RTOSS_F16 || d.dt == RTOSS_BF16) && d.Ci % 32 == 0 && d.Co % 16 == 0;
+}
+
+size_t sparse3x3_section_bytes(const rtoss_wdesc& d)
+{
+    return (size_t)(d.Ci / 32) * padded_m_tiles(d.Co) * kTileBytes;
+}
+
+rtoss_status launch_pack_sparse3x3(const rtoss_wdesc& d, const void* w, const uint8_t* idx, const Dict& dict,
+                                   void* section, hipStream_t s)
+{
+    const int m_tiles = padded_m_tiles(d.Co);
+    const int64_t items = (int64_t)(d.Ci / 32) * m_tiles * 320;
+    dim3 grid((unsigned)((items + 255) / 256)), block(256);
+    if (d.dt == RTOSS_F16)
+        pack_sparse3x3_kernel<f16_t><<<grid, block, 0, s>>>((const f16_t*)w, idx, dict, (char*)section, d.Co, d.Ci, m_tiles, items);
+    else
+        pack_sparse3x3_kernel<bf16_t><<<grid, block, 0, s>>>((const bf16_t*)w, idx, dict, (char*)section, d.Co, d.Ci, m_tiles, items);
+    return check_hip(hipGetLastError(), "pack sparse3x3 launch");
+}
+
+rtoss_status launch_conv3x3_sparse(const rtoss_wdesc& d, const rtoss_cdesc& c, const void* section, const void* x,
+                                   void* y, hipStream_t s)
+{
+    const char* wf = (const char*)section;
+    const bool f32out = c.out_dt == RTOSS_F32;
+    if (d.dt == RTOSS_F16)
+        return f32out ? launch_typed<f16_t, float>(d, c, wf, x, y, s) : launch_typed<f16_t, f16_t>(d, c, wf, x, y, s);
+    return f32out ? launch_typed<bf16_t, float>(d, c, wf, x, y, s) : launch_typed<bf16_t, bf16_t>(d, c, wf, x, y, s);
+}
+
+}  // namespace rtoss

@@ -69,6 +69,49 @@ def test_conv_small_shapes(dt, case):
     run_case(dt, N, Ci, Co, H, W, ks, stride, k, relu, seed=hash(case) % 10000 + dt)
 
 
+MATRIX_CORE = [
+    # shapes that take the matrix-core path (Ci % 32 == 0, Co % 16 == 0, 16-bit types):
+    # ragged tiles, several channel blocks, odd extents, batch > 1
+    # N, Ci, Co,  H,  W, stride, k, relu
+    (1, 32, 16, 4, 4, 1, 3, False),
+    (1, 32, 16, 5, 7, 1, 2, True),
+    (2, 96, 48, 19, 21, 1, 3, False),
+    (1, 64, 144, 33, 18, 1, 2, False),
+    (1, 32, 272, 16, 16, 1, 3, True),
+    (3, 64, 128, 16, 35, 1, 3, False),
+    (1, 256, 256, 20, 24, 1, 3, False),
+    (1, 32, 16, 7, 9, 2, 3, False),
+    (2, 64, 80, 37, 41, 2, 2, True),
+    (1, 128, 256, 40, 40, 2, 3, False),
+    (1, 32, 32, 1, 1, 1, 3, False),
+    (1, 32, 32, 2, 70, 2, 2, False),
+]
+
+
+@pytest.mark.parametrize("dt", [wl.F16, wl.BF16])
+@pytest.mark.parametrize("case", MATRIX_CORE)
+def test_conv3x3_matrix_core_shapes(dt, case):
+    N, Ci, Co, H, W, stride, k, relu = case
+    run_case(dt, N, Ci, Co, H, W, 3, stride, k, relu, seed=hash(case) % 10000 + dt, w_std=0.02)
+
+
+def test_conv3x3_matrix_core_dictionaries():
+    # every pair of taps (36 patterns): still at most 2 corners and 2 edge midpoints -> sparse path
+    run_case(wl.F16, 1, 64, 64, 12, 12, 3, 1, 2, False, seed=31, rule=B.RULE_ALL)
+    # single-tap patterns
+    run_case(wl.BF16, 1, 32, 32, 9, 9, 3, 1, 1, False, seed=32)
+    # 4-entry connected patterns include a T shape with 3 edge midpoints -> falls back to the direct path
+    run_case(wl.F16, 1, 64, 64, 12, 12, 3, 1, 4, False, seed=33)
+    # identical weights in every kernel: every kernel picks pattern 0 (ties) -> coherent tiles
+    masks = B.rtoss_pattern_dict(3)
+    ws = np.full((32, 32, 3, 3), 0.25, dtype=np.float16)
+    xs = wl.round_to_dtype(np.random.default_rng(34).standard_normal((1, 32, 8, 8)), wl.F16)
+    g = GpuLayer(ws, wl.F16, masks, 3)
+    assert (g.idx_host() == 0).all()
+    ref = oracle.conv2d(wl.to_f64(xs, wl.F16), oracle.mask(wl.to_f64(ws, wl.F16), masks, g.idx_host()))
+    check(g.conv_nchw(xs, out_dt=wl.F32), ref, wl.F16)
+
+
 def test_conv_all_ones_pattern_is_dense():
     # k = 9: one pattern that keeps every tap -> ordinary dense convolution
     run_case(wl.F16, 1, 16, 16, 9, 9, 3, 1, 9, False, seed=1, rule=B.RULE_ALL)
