@@ -46,25 +46,35 @@ typedef _Float16 h16 __attribute__((ext_vector_type(16)));
 typedef __bf16 b8 __attribute__((ext_vector_type(8)));
 typedef __bf16 b16 __attribute__((ext_vector_type(16)));
 
+// Matrix instructions.  The accumulator is pinned to the accumulation register file ("a"
+// constraint) and updated in place, so that the 128 loop-carried accumulator registers of a
+// wave never move; everything else (operands, addresses, prefetch) lives in the vector
+// registers.  Written as asm because the register class of a builtin's accumulator is the
+// allocator's choice and it changes with register pressure.
+// Operand hazards: A/B come from LDS reads (waited on by the compiler) or vector ALU results;
+// an accumulator is touched again by a matrix instruction no sooner than TN instructions later,
+// and is read by other instructions only after the K loop (see the s_nop before the epilogue).
 template <typename T> struct Mat;
 template <> struct Mat<f16_t> {
-    static __device__ __forceinline__ f32x4 dense(u32x4 a, u32x4 b, f32x4 c)
+    static __device__ __forceinline__ void dense(u32x4 a, u32x4 b, f32x4& c)
     {
-        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, a), __builtin_bit_cast(h8, b), c, 0, 0, 0);
+        asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
     }
-    template <int ABID> static __device__ __forceinline__ f32x4 sparse(u32x4 a, u32x8 b, f32x4 c, int idx)
+    template <int ABID> static __device__ __forceinline__ void sparse(u32x4 a, u32x8 b, f32x4& c, int idx)
     {
-        return __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, a), __builtin_bit_cast(h16, b), c, idx, 0, ABID);
+        if (ABID == 0) asm volatile("v_smfmac_f32_16x16x64_f16 %0, %1, %2, %3" : "+a"(c) : "v"(a), "v"(b), "v"(idx));
+        else asm volatile("v_smfmac_f32_16x16x64_f16 %0, %1, %2, %3 abid:1" : "+a"(c) : "v"(a), "v"(b), "v"(idx));
     }
 };
 template <> struct Mat<bf16_t> {
-    static __device__ __forceinline__ f32x4 dense(u32x4 a, u32x4 b, f32x4 c)
+    static __device__ __forceinline__ void dense(u32x4 a, u32x4 b, f32x4& c)
     {
-        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(b8, a), __builtin_bit_cast(b8, b), c, 0, 0, 0);
+        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
     }
-    template <int ABID> static __device__ __forceinline__ f32x4 sparse(u32x4 a, u32x8 b, f32x4 c, int idx)
+    template <int ABID> static __device__ __forceinline__ void sparse(u32x4 a, u32x8 b, f32x4& c, int idx)
     {
-        return __builtin_amdgcn_smfmac_f32_16x16x64_bf16(__builtin_bit_cast(b8, a), __builtin_bit_cast(b16, b), c, idx, 0, ABID);
+        if (ABID == 0) asm volatile("v_smfmac_f32_16x16x64_bf16 %0, %1, %2, %3" : "+a"(c) : "v"(a), "v"(b), "v"(idx));
+        else asm volatile("v_smfmac_f32_16x16x64_bf16 %0, %1, %2, %3 abid:1" : "+a"(c) : "v"(a), "v"(b), "v"(idx));
     }
 };
 
@@ -164,8 +174,10 @@ template <int S, int RT, int CT> struct Geom {
     static constexpr int x_chunks = IH * IW * 4;                   // 16-byte chunks to fetch per stage
 };
 
+// Single-buffered variant (register-staged prefetch, two barriers per stage).  Used for stride 2,
+// whose activation tile is too large to keep twice in LDS.
 template <typename T, typename TO, int S, int TM, int TN, int RT, int CT>
-__global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restrict__ x, TO* __restrict__ y,
+__global__ __launch_bounds__(256, 1) void conv3x3_sparse_sb_kernel(const T* __restrict__ x, TO* __restrict__ y,
                                                                 const char* __restrict__ wfrag, int H, int W, int Ci,
                                                                 int Co, int Ho, int Wo, int m_tiles_total,
                                                                 int tiles_c, int relu)
@@ -289,9 +301,9 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
                 const u32x4 a0 = *(const u32x4*)(at + (group * 2 + 0) * kFragBytes + lane * 16);
                 const u32x4 a1 = *(const u32x4*)(at + (group * 2 + 1) * kFragBytes + lane * 16);
 #pragma unroll
-                for (int j = 0; j < TN; ++j) acc[m][j] = Mat<T>::template sparse<0>(a0, bf[0][j], acc[m][j], iw2);
+                for (int j = 0; j < TN; ++j) Mat<T>::template sparse<0>(a0, bf[0][j], acc[m][j], iw2);
 #pragma unroll
-                for (int j = 0; j < TN; ++j) acc[m][j] = Mat<T>::template sparse<1>(a1, bf[1][j], acc[m][j], iw2);
+                for (int j = 0; j < TN; ++j) Mat<T>::template sparse<1>(a1, bf[1][j], acc[m][j], iw2);
             }
         }
         {  // centre tap: dense step over the 32 channels of the stage
@@ -302,11 +314,13 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
             for (int m = 0; m < TM; ++m) {
                 const u32x4 a = *(const u32x4*)(lds_a + m * kTileBytes + 4 * kFragBytes + lane * 16);
 #pragma unroll
-                for (int j = 0; j < TN; ++j) acc[m][j] = Mat<T>::dense(a, bc[j], acc[m][j]);
+                for (int j = 0; j < TN; ++j) Mat<T>::dense(a, bc[j], acc[m][j]);
             }
         }
     }
 
+    // the last matrix instructions must have written their accumulators before anything reads them
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
     // ---- epilogue: D lane holds column nn (position), rows 4*qq .. 4*qq+3 (output channels) ----
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
@@ -339,6 +353,274 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
     }
 }
 
+// One 16-byte global -> LDS copy per lane without passing through registers: lane i of the
+// wave writes LDS address lds_wave_base + 16 * i (the base must be wave-uniform).
+__device__ __forceinline__ void copy16_to_lds(const void* gsrc, char* lds_wave_base)
+{
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
+                                     (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
+}
+
+template <typename T, typename TO, int S, int TM, int TN, int RT, int CT>
+__global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restrict__ x, TO* __restrict__ y,
+                                                                const char* __restrict__ wfrag, int H, int W, int Ci,
+                                                                int Co, int Ho, int Wo, int m_tiles_total,
+                                                                int tiles_c, int tiles_per_img, int co_blocks,
+                                                                int total_work, int work_per_xcd, int relu)
+{
+    using G = Geom<S, RT, CT>;
+    static_assert(RT * CT == 4 * TN, "four waves share the position blocks of a workgroup");
+    static_assert(TN == 4, "the software pipeline below is written for 4 position blocks per wave");
+    constexpr int A_BYTES = TM * kTileBytes;
+    constexpr int A_WAVE_COPIES = A_BYTES / 1024;              // 64 lanes x 16 B per copy instruction
+    constexpr int A_PER_WAVE = (A_WAVE_COPIES + 3) / 4;
+    constexpr int X_BYTES = G::x_bytes;
+    constexpr int X_CHUNKS = X_BYTES / 16;                     // including the pad chunk of every position
+    constexpr int X_WAVE_COPIES = (X_CHUNKS + 63) / 64;
+    constexpr int X_PER_WAVE = (X_WAVE_COPIES + 3) / 4;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    // [A buffer 0][A buffer 1][X buffer 0][X buffer 1]
+    char* const lds_a = smem;
+    char* const lds_x = smem + 2 * A_BYTES;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2); give every XCD a
+    // contiguous range of work items so that the channel blocks of one spatial tile, and
+    // neighbouring tiles, share an L2.
+    const int work = (blockIdx.x % 8) * work_per_xcd + blockIdx.x / 8;
+    if (work >= total_work) return;
+    const int cblk = work % co_blocks;
+    const int tile = (work / co_blocks) % tiles_per_img;
+    const int n_img = work / (co_blocks * tiles_per_img);
+    const int tile_r = tile / tiles_c, tile_c = tile % tiles_c;
+    const int mt0 = cblk * TM;
+    const int oh0 = tile_r * G::TH, ow0 = tile_c * G::TW;
+    const int ih0 = oh0 * S - 1, iw0 = ow0 * S - 1;
+    const int stages = Ci / 32;
+
+    // ---- copy bookkeeping ----
+    const char* a_src = wfrag + (int64_t)mt0 * kTileBytes + lane * 16;
+    const int64_t a_stage_stride = (int64_t)m_tiles_total * kTileBytes;
+    int x_src16[X_PER_WAVE];  // source offset in 16-byte units for stage 0; -1: this lane copies nothing
+#pragma unroll
+    for (int k = 0; k < X_PER_WAVE; ++k) {
+        const int c = ((k * 4 + wave) * 64 + lane);
+        const int pos = c / 5, q = c % 5;
+        const int pr = pos / G::LW, pc = pos % G::LW;
+        const int ih = ih0 + pr, iw = iw0 + pc;
+        const bool slot = c < X_CHUNKS && q < 4 && pc < G::IW;
+        const bool inside = slot && ih >= 0 && ih < H && iw >= 0 && iw < W;
+        x_src16[k] = inside ? (int)(((((int64_t)n_img * H + ih) * W + iw) * Ci + q * 8) >> 3) : -1;
+        if (slot && !inside) {  // zero padding never changes: write it once into both buffers
+            *(u32x4*)(lds_x + c * 16) = u32x4{0, 0, 0, 0};
+            *(u32x4*)(lds_x + X_BYTES + c * 16) = u32x4{0, 0, 0, 0};
+        }
+    }
+    auto issue_copies = [&](int stage) {
+        const int par = stage & 1;
+        const char* asrc = a_src + stage * a_stage_stride;
+#pragma unroll
+        for (int k = 0; k < A_PER_WAVE; ++k) {
+            const int kk = k * 4 + wave;
+            if (kk < A_WAVE_COPIES) copy16_to_lds(asrc + kk * 1024, lds_a + par * A_BYTES + kk * 1024);
+        }
+        const char* xsrc = (const char*)x + (int64_t)stage * 64;
+#pragma unroll
+        for (int k = 0; k < X_PER_WAVE; ++k) {
+            const int kk = k * 4 + wave;
+            if (x_src16[k] >= 0) copy16_to_lds(xsrc + (int64_t)x_src16[k] * 16, lds_x + par * X_BYTES + kk * 1024);
+        }
+    };
+
+    // ---- per-lane read addresses ----
+    const int nn = lane & 15, qq = lane >> 4;
+    const int pr = nn >> 2, pc = nn & 3;
+    // the 4 position blocks of a wave sit at compile-time offsets from the first one
+    const int blk0 = wave * TN;
+    int xb[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int blk = blk0 + j;
+        xb[j] = (((4 * (blk / CT) + pr) * S) * G::LW + (4 * (blk % CT) + pc) * S) * kXPosBytes + qq * 16;
+    }
+
+    f32x4 acc[TM][TN];
+#pragma unroll
+    for (int m = 0; m < TM; ++m)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[m][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    issue_copies(0);
+    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): own copies have landed
+    __syncthreads();
+
+    for (int stage = 0; stage < stages; ++stage) {
+        if (stage + 1 < stages) issue_copies(stage + 1);
+        const char* A = lds_a + (stage & 1) * A_BYTES + lane * 16;
+        const char* AI = lds_a + (stage & 1) * A_BYTES + 5 * kFragBytes + lane * 4;
+        const char* X = lds_x + (stage & 1) * X_BYTES;
+
+        // One stage = 5 phases (centre, corner step 0/1, edge step 0/1) of TM*TN matrix
+        // instructions = 20 units of 8 (two channel tiles x four position blocks).  LDS reads are
+        // issued one unit ahead of their use, right after the unit's first matrix instruction,
+        // so the wait in front of the next unit's first instruction only covers loads that have
+        // had a whole unit to complete.  B operands of the sparse steps need a 4x4 (tap x
+        // channel) transpose: a "job" reads the 4 taps of one position block (4 x 16 bytes) in
+        // one unit and permutes them, two byte-permutes behind each matrix instruction, in the
+        // next.
+        auto raw_load = [&](u32x4 (&rr)[4], int j, int group) {
+#pragma unroll
+            for (int f = 0; f < 4; ++f) {
+                const int t = group == 0 ? ((f & 1) * 2 + (f >> 1) * 6) : (2 * f + 1);
+                rr[f] = *(const u32x4*)(X + xb[j] + ((t / 3) * G::LW + (t % 3)) * kXPosBytes);
+            }
+        };
+        // output o (0..15) of a job: dword o%8 of step o/8; element 4*c + f of a step's B operand =
+        // channel c (of this lane's 4 in that step), tap slot f
+        auto transposed = [&](const u32x4 (&rr)[4], int o) -> uint32_t {
+            const int d = o & 7, comp = (o >> 3) * 2 + (d >> 2);
+            const uint32_t sel = (d & 2) ? 0x07060302u : 0x05040100u;
+            return (d & 1) ? __builtin_amdgcn_perm(rr[3][comp], rr[2][comp], sel)
+                           : __builtin_amdgcn_perm(rr[1][comp], rr[0][comp], sel);
+        };
+        // job schedule: job -> (group, block, unit in which its 4 reads are issued); permutes run one unit later.
+        // corner operands must be complete before unit 4, edge operands before unit 12.
+        constexpr int kJobs = 8;
+        constexpr int job_group[kJobs] = {0, 0, 0, 0, 1, 1, 1, 1};
+        constexpr int job_block[kJobs] = {0, 1, 2, 3, 0, 1, 2, 3};
+        constexpr int job_load_unit[kJobs] = {-1, 0, 1, 2, 6, 7, 8, 9};  // -1: stage prologue
+
+        u32x4 bc[TN];
+        u32x8 bfc[2][TN], bfe[2][TN];
+        u32x4 rr_cur[4], rr_nxt[4];
+        u32x4 a_cur[2], a_nxt[2];
+        int i_cur[2] = {0, 0}, i_nxt[2] = {0, 0};
+        // stage prologue: operands of unit 0 and the first job's taps
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bc[j] = *(const u32x4*)(X + xb[j] + (G::LW + 1) * kXPosBytes);
+        a_cur[0] = *(const u32x4*)(A + 4 * kFragBytes);
+        a_cur[1] = *(const u32x4*)(A + kTileBytes + 4 * kFragBytes);
+        raw_load(rr_cur, 0, 0);
+
+#pragma unroll
+        for (int u = 0; u < 20; ++u) {
+            const int phase = u / 4, m0 = (u % 4) * 2;
+            // which job (if any) is permuted / read in this unit
+            int job_perm = -1, job_read = -1;
+#pragma unroll
+            for (int q = 0; q < kJobs; ++q) {
+                if (job_load_unit[q] + 1 == u) job_perm = q;
+                if (job_load_unit[q] == u) job_read = q;
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int mi = i >> 2, j = i & 3, m = m0 + mi;
+                if (phase == 0) Mat<T>::dense(a_cur[mi], bc[j], acc[m][j]);
+                if (phase == 1) Mat<T>::template sparse<0>(a_cur[mi], bfc[0][j], acc[m][j], i_cur[mi]);
+                if (phase == 2) Mat<T>::template sparse<1>(a_cur[mi], bfc[1][j], acc[m][j], i_cur[mi]);
+                if (phase == 3) Mat<T>::template sparse<0>(a_cur[mi], bfe[0][j], acc[m][j], i_cur[mi]);
+                if (phase == 4) Mat<T>::template sparse<1>(a_cur[mi], bfe[1][j], acc[m][j], i_cur[mi]);
+                if (i == 0) {  // issue the next unit's LDS reads behind the first matrix instruction
+                    if (u + 1 < 20) {
+                        const int np = (u + 1) / 4, nm0 = ((u + 1) % 4) * 2;
+                        const int nstep = np == 0 ? 4 : np - 1;
+#pragma unroll
+                        for (int t = 0; t < 2; ++t) {
+                            a_nxt[t] = *(const u32x4*)(A + (nm0 + t) * kTileBytes + nstep * kFragBytes);
+                            if (np > 0) i_nxt[t] = *(const int*)(AI + (nm0 + t) * kTileBytes + ((np - 1) >> 1) * 256);
+                        }
+                    }
+                    if (job_read >= 0) raw_load(rr_nxt, job_block[job_read], job_group[job_read]);
+                }
+                if (job_perm >= 0) {
+                    const int jb = job_block[job_perm];
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        const int o = 2 * i + t;
+                        const uint32_t v = transposed(rr_cur, o);
+                        if (job_group[job_perm] == 0) bfc[o >> 3][jb][o & 7] = v;
+                        else bfe[o >> 3][jb][o & 7] = v;
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (u + 1 < 20) {
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    a_cur[t] = a_nxt[t];
+                    i_cur[t] = i_nxt[t];
+                }
+            }
+            if (job_read >= 0) {
+#pragma unroll
+                for (int f = 0; f < 4; ++f) rr_cur[f] = rr_nxt[f];
+            }
+        }
+        __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): the next stage's copies issued by this wave landed
+        __syncthreads();                              // ... and everybody else's; everybody is done reading this stage
+    }
+
+    // the last matrix instructions must have written their accumulators before anything reads them
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+    // ---- epilogue ----
+    // A D fragment has, per lane, 4 consecutive output channels of one position; stored directly
+    // that is 8-byte pieces scattered over 16 positions.  Instead each wave transposes its
+    // 64 positions x 16*TM channels through its own slice of LDS (all K-loop buffers are free
+    // after the final barrier) and writes whole channel rows, 16 bytes per lane.
+    {
+        constexpr int EB = (int)sizeof(TO);
+        constexpr int ROW = TM * 16 * EB + (EB == 2 ? 8 : 16);  // padded row pitch: spreads the banks
+        static_assert(4 * 16 * TN * ROW <= 2 * (A_BYTES + X_BYTES), "epilogue staging must fit in LDS");
+        char* stage_out = smem + wave * (16 * TN * ROW);
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int m = 0; m < TM; ++m) {
+                f32x4 v = acc[m][j];
+                v.x = relu ? __builtin_fmaxf(v.x, 0.f) : v.x;
+                v.y = relu ? __builtin_fmaxf(v.y, 0.f) : v.y;
+                v.z = relu ? __builtin_fmaxf(v.z, 0.f) : v.z;
+                v.w = relu ? __builtin_fmaxf(v.w, 0.f) : v.w;
+                char* dst = stage_out + (j * 16 + nn) * ROW + (16 * m + 4 * qq) * EB;
+                if constexpr (EB == 4) {
+                    *(f32x4*)dst = v;
+                } else {
+                    uint2 o;
+                    o.x = pack2_from_f32<TO>(v.x, v.y);
+                    o.y = pack2_from_f32<TO>(v.z, v.w);
+                    *(uint2*)dst = o;
+                }
+            }
+        // read back: a row of 16*TM channels is CH 16-byte chunks; 64 lanes cover 64/CH positions per pass
+        constexpr int CH = TM * 16 * EB / 16;
+        static_assert(64 % CH == 0 || CH % 64 == 0, "row chunks must tile the wave");
+        constexpr int POS_PER_PASS = CH <= 64 ? 64 / CH : 1;
+        constexpr int PASSES = CH <= 64 ? (16 * TN) / POS_PER_PASS : (16 * TN) * (CH / 64);
+        const int co_first = 16 * mt0;
+#pragma unroll
+        for (int ps = 0; ps < PASSES; ++ps) {
+            int p, chunk;
+            if constexpr (CH <= 64) {
+                p = ps * POS_PER_PASS + lane / CH;
+                chunk = lane % CH;
+            } else {
+                p = ps / (CH / 64);
+                chunk = (ps % (CH / 64)) * 64 + lane;
+            }
+            const int j = p >> 4, n = p & 15;
+            const int blk = blk0 + j;
+            const int oh = oh0 + 4 * (blk / CT) + (n >> 2), ow = ow0 + 4 * (blk % CT) + (n & 3);
+            const int co = co_first + chunk * (16 / EB);
+            const u32x4 v = *(const u32x4*)(stage_out + p * ROW + chunk * 16);
+            if (oh < Ho && ow < Wo && co < Co)  // Co is a multiple of 16, so a chunk is all in or all out
+                *(u32x4*)(y + (((int64_t)n_img * Ho + oh) * Wo + ow) * Co + co) = v;
+        }
+    }
+}
+
 template <typename T, typename TO, int S, int TM, int TN, int RT, int CT>
 rtoss_status launch_variant(const rtoss_wdesc& d, const rtoss_cdesc& c, const char* wfrag, const void* x, void* y,
                             hipStream_t s)
@@ -348,8 +630,36 @@ rtoss_status launch_variant(const rtoss_wdesc& d, const rtoss_cdesc& c, const ch
     const int tiles_r = (Ho + G::TH - 1) / G::TH, tiles_c = (Wo + G::TW - 1) / G::TW;
     const int m_tiles_total = padded_m_tiles(d.Co);  // pitch of the packed section
     const int co_blocks = ((d.Co + 15) / 16 + TM - 1) / TM;
-    const size_t smem = (size_t)TM * kTileBytes + G::x_bytes;
+    const size_t smem = 2 * ((size_t)TM * kTileBytes + G::x_bytes);
     auto kern = conv3x3_sparse_kernel<T, TO, S, TM, TN, RT, CT>;
+    static bool attr_set = false;  // per instantiation
+    if (!attr_set) {
+        if (rtoss_status st = check_hip(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem),
+                                        "conv3x3 shared memory attribute"))
+            return st;
+        attr_set = true;
+    }
+    const int64_t total = (int64_t)tiles_r * tiles_c * co_blocks * c.N;
+    if (total > 0x3fffffff) return fail(RTOSS_ESHAPE, "conv: too many tiles");
+    if ((int64_t)c.N * c.H * c.W * d.Ci / 8 > 0x7fffffff) return fail(RTOSS_ESHAPE, "conv: input too large for 32-bit chunk offsets");
+    const int work_per_xcd = (int)((total + 7) / 8);
+    dim3 grid((unsigned)(work_per_xcd * 8)), block(256);
+    kern<<<grid, block, smem, s>>>((const T*)x, (TO*)y, wfrag, c.H, c.W, d.Ci, d.Co, Ho, Wo, m_tiles_total, tiles_c,
+                                   tiles_r * tiles_c, co_blocks, (int)total, work_per_xcd, c.fuse_relu);
+    return check_hip(hipGetLastError(), "conv3x3 sparse launch");
+}
+
+template <typename T, typename TO, int S, int TM, int TN, int RT, int CT>
+rtoss_status launch_variant_sb(const rtoss_wdesc& d, const rtoss_cdesc& c, const char* wfrag, const void* x, void* y,
+                            hipStream_t s)
+{
+    using G = Geom<S, RT, CT>;
+    const int Ho = (c.H + 2 - 3) / S + 1, Wo = (c.W + 2 - 3) / S + 1;
+    const int tiles_r = (Ho + G::TH - 1) / G::TH, tiles_c = (Wo + G::TW - 1) / G::TW;
+    const int m_tiles_total = padded_m_tiles(d.Co);  // pitch of the packed section
+    const int co_blocks = ((d.Co + 15) / 16 + TM - 1) / TM;
+    const size_t smem = (size_t)TM * kTileBytes + G::x_bytes;
+    auto kern = conv3x3_sparse_sb_kernel<T, TO, S, TM, TN, RT, CT>;
     static bool attr_set = false;  // per instantiation
     if (!attr_set) {
         if (rtoss_status st = check_hip(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem),
@@ -371,7 +681,7 @@ rtoss_status launch_typed(const rtoss_wdesc& d, const rtoss_cdesc& c, const char
     // The fragment section is padded to a multiple of 8 channel tiles, so any TM <= 8 may over-read rows
     // that hold zeros; outputs beyond Co are never stored.
     if (c.stride == 1) return launch_variant<T, TO, 1, 8, 4, 4, 4>(d, c, wfrag, x, y, s);
-    return launch_variant<T, TO, 2, 8, 4, 4, 4>(d, c, wfrag, x, y, s);
+    return launch_variant_sb<T, TO, 2, 8, 4, 4, 4>(d, c, wfrag, x, y, s);
 }
 
 }  // namespace
