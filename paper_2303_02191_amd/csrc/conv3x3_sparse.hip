@@ -31,6 +31,8 @@
 // LDS.  B operands are read from LDS as 16-byte vectors (8 channels of one tap) and the
 // 4x4 (tap, channel) blocks are transposed in registers with byte permutes so that one
 // lane holds, for 4 channels, the 4 taps of a group.
+#include <algorithm>
+
 #include "common.h"
 #include "dtypes.h"
 
@@ -101,13 +103,16 @@ __device__ __forceinline__ int stage_channel(int q, int g, int half)
 template <typename T>
 __global__ __launch_bounds__(256) void pack_sparse3x3_kernel(const T* __restrict__ w, const uint8_t* __restrict__ idx,
                                                              Dict dict, char* __restrict__ out, int Co, int Ci,
-                                                             int m_tiles, int64_t total_items)
+                                                             int m_tiles, int64_t total_items, int zero_items)
 {
     __shared__ uint16_t masks[256];
     masks[threadIdx.x] = dict.mask[threadIdx.x];
     __syncthreads();
     const int64_t item = (int64_t)blockIdx.x * 256 + threadIdx.x;  // (stage, m_tile, step 0..4, lane)
-    if (item >= total_items) return;
+    if (item >= total_items) {  // the items behind the fragments write the block of zeros, 16 bytes each
+        if (item < total_items + zero_items) *(u32x4*)(out + (total_items / 320) * kTileBytes + (item - total_items) * 16) = u32x4{0, 0, 0, 0};
+        return;
+    }
     const int lane = (int)(item % 64);
     const int step = (int)((item / 64) % 5);
     const int64_t tile = item / 320;  // stage * m_tiles + m_tile
@@ -165,6 +170,9 @@ __global__ __launch_bounds__(256) void pack_sparse3x3_kernel(const T* __restrict
 
 // Channel tiles per stage in the packed section: padded so that every block of 8 tiles is complete.
 inline int padded_m_tiles(int Co) { return ((Co + 15) / 16 + 7) / 8 * 8; }
+// The section is [fragments][block of zeros]; the zeros feed the copy lanes that fill padding.
+inline size_t fragment_bytes(const rtoss_wdesc& d) { return (size_t)(d.Ci / 32) * padded_m_tiles(d.Co) * kTileBytes; }
+inline size_t zero_block_bytes(const rtoss_wdesc& d) { return align_up((size_t)2 * d.Ci + 16, 256); }
 
 template <int S, int RT, int CT> struct Geom {
     static constexpr int TH = 4 * RT, TW = 4 * CT;                 // output tile
@@ -363,7 +371,8 @@ __device__ __forceinline__ void copy16_to_lds(const void* gsrc, char* lds_wave_b
 
 template <typename T, typename TO, int S, int TM, int TN, int RT, int CT>
 __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restrict__ x, TO* __restrict__ y,
-                                                                const char* __restrict__ wfrag, int H, int W, int Ci,
+                                                                const char* __restrict__ wfrag,
+                                                                const char* __restrict__ zeros, int H, int W, int Ci,
                                                                 int Co, int Ho, int Wo, int m_tiles_total,
                                                                 int tiles_c, int tiles_per_img, int co_blocks,
                                                                 int total_work, int work_per_xcd, int relu)
@@ -378,60 +387,67 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
     constexpr int X_CHUNKS = X_BYTES / 16;                     // including the pad chunk of every position
     constexpr int X_WAVE_COPIES = (X_CHUNKS + 63) / 64;
     constexpr int X_PER_WAVE = (X_WAVE_COPIES + 3) / 4;
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-    // [A buffer 0][A buffer 1][X buffer 0][X buffer 1]
-    char* const lds_a = smem;
-    char* const lds_x = smem + 2 * A_BYTES;
+    constexpr int X_AREA = X_PER_WAVE * 4 * 1024;              // what the copy instructions cover (>= X_BYTES)
+    constexpr int REGION = A_BYTES + X_AREA;                   // one pipeline buffer: [weights][activations]
+    extern __shared__ __attribute__((aligned(16))) char smem[];  // two regions
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-
-    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2); give every XCD a
-    // contiguous range of work items so that the channel blocks of one spatial tile, and
-    // neighbouring tiles, share an L2.
-    const int work = (blockIdx.x % 8) * work_per_xcd + blockIdx.x / 8;
-    if (work >= total_work) return;
-    const int cblk = work % co_blocks;
-    const int tile = (work / co_blocks) % tiles_per_img;
-    const int n_img = work / (co_blocks * tiles_per_img);
-    const int tile_r = tile / tiles_c, tile_c = tile % tiles_c;
-    const int mt0 = cblk * TM;
-    const int oh0 = tile_r * G::TH, ow0 = tile_c * G::TW;
-    const int ih0 = oh0 * S - 1, iw0 = ow0 * S - 1;
     const int stages = Ci / 32;
-
-    // ---- copy bookkeeping ----
-    const char* a_src = wfrag + (int64_t)mt0 * kTileBytes + lane * 16;
     const int64_t a_stage_stride = (int64_t)m_tiles_total * kTileBytes;
-    int x_src16[X_PER_WAVE];  // source offset in 16-byte units for stage 0; -1: this lane copies nothing
-#pragma unroll
-    for (int k = 0; k < X_PER_WAVE; ++k) {
-        const int c = ((k * 4 + wave) * 64 + lane);
-        const int pos = c / 5, q = c % 5;
-        const int pr = pos / G::LW, pc = pos % G::LW;
-        const int ih = ih0 + pr, iw = iw0 + pc;
-        const bool slot = c < X_CHUNKS && q < 4 && pc < G::IW;
-        const bool inside = slot && ih >= 0 && ih < H && iw >= 0 && iw < W;
-        x_src16[k] = inside ? (int)(((((int64_t)n_img * H + ih) * W + iw) * Ci + q * 8) >> 3) : -1;
-        if (slot && !inside) {  // zero padding never changes: write it once into both buffers
-            *(u32x4*)(lds_x + c * 16) = u32x4{0, 0, 0, 0};
-            *(u32x4*)(lds_x + X_BYTES + c * 16) = u32x4{0, 0, 0, 0};
-        }
-    }
-    auto issue_copies = [&](int stage) {
-        const int par = stage & 1;
-        const char* asrc = a_src + stage * a_stage_stride;
-#pragma unroll
-        for (int k = 0; k < A_PER_WAVE; ++k) {
-            const int kk = k * 4 + wave;
-            if (kk < A_WAVE_COPIES) copy16_to_lds(asrc + kk * 1024, lds_a + par * A_BYTES + kk * 1024);
-        }
-        const char* xsrc = (const char*)x + (int64_t)stage * 64;
+
+    // Persistent workgroups: one per compute unit, each walking a list of output tiles so that
+    // the copies for a tile's first stage overlap the previous tile's last stage and the output
+    // stores overlap the next tile's arithmetic.  Workgroups are dealt round-robin to the 8 XCDs
+    // (each with its own L2); every XCD gets a contiguous range of work items so that the channel
+    // blocks of one spatial tile, and neighbouring tiles, share an L2.
+    const int xcd = blockIdx.x % 8, slot_in_xcd = blockIdx.x / 8, slots_per_xcd = gridDim.x / 8;
+    const int work_end = min((xcd + 1) * work_per_xcd, total_work);
+    int work = xcd * work_per_xcd + slot_in_xcd;
+    if (work >= work_end) return;
+
+    // ---- per-tile state ----
+    // Every lane copies 16 bytes in every copy instruction, so the copy code has no branches: a
+    // lane whose LDS slot is zero padding of the tile (or an unused pad slot) reads from a block
+    // of zeros that the packer appended to the weight fragments (2*Ci + 16 bytes, so that the
+    // per-stage advance of 64 bytes stays inside it).
+    int n_img, mt0, oh0, ow0;
+    const char* x_ptr[X_PER_WAVE];  // per lane and copy slot: source address for stage 0
+    auto setup_tile = [&](int w) {
+        const int cblk = w % co_blocks;
+        const int tile = (w / co_blocks) % tiles_per_img;
+        n_img = w / (co_blocks * tiles_per_img);
+        mt0 = cblk * TM;
+        oh0 = (tile / tiles_c) * G::TH;
+        ow0 = (tile % tiles_c) * G::TW;
+        const int ih0 = oh0 * S - 1, iw0 = ow0 * S - 1;
 #pragma unroll
         for (int k = 0; k < X_PER_WAVE; ++k) {
+            const int c = ((k * 4 + wave) * 64 + lane);
+            const int pos = c / 5, q = c % 5;
+            const int pr = pos / G::LW, pc = pos % G::LW;
+            const int ih = ih0 + pr, iw = iw0 + pc;
+            const bool inside = q < 4 && pr < G::IH && pc < G::IW && ih >= 0 && ih < H && iw >= 0 && iw < W;
+            x_ptr[k] = inside ? (const char*)x + ((((int64_t)n_img * H + ih) * W + iw) * Ci + q * 8) * 2 : zeros;
+        }
+    };
+    // One copy instruction (64 lanes x 16 bytes) of stage `stage` of the current tile into region
+    // `par`: slots 0 .. A_PER_WAVE-1 move weight fragments, the rest move activations.
+    constexpr int COPY_SLOTS = A_PER_WAVE + X_PER_WAVE;
+    static_assert(COPY_SLOTS <= 20, "one copy per pipeline unit");
+    static_assert(A_WAVE_COPIES % 4 == 0, "every wave issues the same number of weight copies");
+    auto issue_copy_slot = [&](int slot, int stage, int par) {
+        char* region = smem + par * REGION;
+        if (slot < A_PER_WAVE) {
+            const int kk = slot * 4 + wave;
+            const char* asrc = wfrag + (int64_t)mt0 * kTileBytes + lane * 16 + stage * a_stage_stride;
+            copy16_to_lds(asrc + kk * 1024, region + kk * 1024);
+        } else {
+            const int k = slot - A_PER_WAVE;
             const int kk = k * 4 + wave;
-            if (x_src16[k] >= 0) copy16_to_lds(xsrc + (int64_t)x_src16[k] * 16, lds_x + par * X_BYTES + kk * 1024);
+            // (the last copy instructions reach past the activation tile into the slack of X_AREA)
+            copy16_to_lds(x_ptr[k] + stage * 64, region + A_BYTES + kk * 1024);
         }
     };
 
@@ -448,20 +464,34 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
     }
 
     f32x4 acc[TM][TN];
+
+    setup_tile(work);
+#pragma unroll
+    for (int slot = 0; slot < COPY_SLOTS; ++slot) issue_copy_slot(slot, 0, 0);
+    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's copies have landed in LDS
+    __syncthreads();                     // ... and everybody's
+    int gpar = 0;     // region that holds the stage about to be multiplied
+
+  for (;;) {  // tiles
+    // output coordinates of the tile being multiplied (the copy state moves on to the next tile early)
+    const int t_n = n_img, t_mt0 = mt0, t_oh0 = oh0, t_ow0 = ow0;
+    const int next_work = work + slots_per_xcd;
+    const bool has_next = next_work < work_end;
 #pragma unroll
     for (int m = 0; m < TM; ++m)
 #pragma unroll
         for (int j = 0; j < TN; ++j) acc[m][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    issue_copies(0);
-    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): own copies have landed
-    __syncthreads();
-
     for (int stage = 0; stage < stages; ++stage) {
-        if (stage + 1 < stages) issue_copies(stage + 1);
-        const char* A = lds_a + (stage & 1) * A_BYTES + lane * 16;
-        const char* AI = lds_a + (stage & 1) * A_BYTES + 5 * kFragBytes + lane * 4;
-        const char* X = lds_x + (stage & 1) * X_BYTES;
+        // the stage copied while this one is multiplied: the tile's next stage, or the next tile's first
+        // (in the very last stage of the last tile there is nothing left to fetch; stage 0 of the
+        // same tile is fetched again into the free region, which keeps this code free of branches)
+        const bool last_stage = stage + 1 == stages;
+        const int copy_stage = last_stage ? 0 : stage + 1;
+        if (last_stage && has_next) setup_tile(next_work);
+        const char* A = smem + gpar * REGION + lane * 16;
+        const char* AI = smem + gpar * REGION + 5 * kFragBytes + lane * 4;
+        const char* X = smem + gpar * REGION + A_BYTES;
 
         // One stage = 5 phases (centre, corner step 0/1, edge step 0/1) of TM*TN matrix
         // instructions = 20 units of 8 (two channel tiles x four position blocks).  LDS reads are
@@ -523,6 +553,7 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
                 if (phase == 2) Mat<T>::template sparse<1>(a_cur[mi], bfc[1][j], acc[m][j], i_cur[mi]);
                 if (phase == 3) Mat<T>::template sparse<0>(a_cur[mi], bfe[0][j], acc[m][j], i_cur[mi]);
                 if (phase == 4) Mat<T>::template sparse<1>(a_cur[mi], bfe[1][j], acc[m][j], i_cur[mi]);
+                if (i == 4 && u < COPY_SLOTS) issue_copy_slot(u, copy_stage, gpar ^ 1);
                 if (i == 0) {  // issue the next unit's LDS reads behind the first matrix instruction
                     if (u + 1 < 20) {
                         const int np = (u + 1) / 4, nm0 = ((u + 1) % 4) * 2;
@@ -560,7 +591,8 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
             }
         }
         __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): the next stage's copies issued by this wave landed
-        __syncthreads();                              // ... and everybody else's; everybody is done reading this stage
+        __syncthreads();                     // ... and everybody's; everybody is done reading this stage
+        gpar ^= 1;
     }
 
     // the last matrix instructions must have written their accumulators before anything reads them
@@ -568,57 +600,67 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
     // ---- epilogue ----
     // A D fragment has, per lane, 4 consecutive output channels of one position; stored directly
     // that is 8-byte pieces scattered over 16 positions.  Instead each wave transposes its
-    // 64 positions x 16*TM channels through its own slice of LDS (all K-loop buffers are free
-    // after the final barrier) and writes whole channel rows, 16 bytes per lane.
+    // 64 positions x 16*TM channels through its own slice of the region that was multiplied last
+    // (free now; the other region is receiving the next tile's first stage) and writes whole
+    // channel rows, 16 bytes per lane.  fp32 output goes in two halves of the channel tiles.
     {
         constexpr int EB = (int)sizeof(TO);
-        constexpr int ROW = TM * 16 * EB + (EB == 2 ? 8 : 16);  // padded row pitch: spreads the banks
-        static_assert(4 * 16 * TN * ROW <= 2 * (A_BYTES + X_BYTES), "epilogue staging must fit in LDS");
-        char* stage_out = smem + wave * (16 * TN * ROW);
+        constexpr int HALVES = EB == 4 ? 2 : 1;
+        constexpr int TMH = TM / HALVES;
+        static_assert(TM % HALVES == 0, "channel tiles must split evenly");
+        constexpr int ROW = TMH * 16 * EB + (EB == 2 ? 8 : 16);  // padded row pitch: spreads the banks
+        static_assert(4 * 16 * TN * ROW <= REGION, "epilogue staging must fit in one region");
+        char* stage_out = smem + (gpar ^ 1) * REGION + wave * (16 * TN * ROW);
+        // lane-derived addresses of the epilogue are recomputed per tile (opaque copy of the lane id)
+        // instead of staying live in registers through the K loop
+        int lane_e = lane;
+        asm volatile("" : "+v"(lane_e));
+        const int nn_e = lane_e & 15, qq_e = lane_e >> 4;
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+        for (int h = 0; h < HALVES; ++h) {
 #pragma unroll
-            for (int m = 0; m < TM; ++m) {
-                f32x4 v = acc[m][j];
-                v.x = relu ? __builtin_fmaxf(v.x, 0.f) : v.x;
-                v.y = relu ? __builtin_fmaxf(v.y, 0.f) : v.y;
-                v.z = relu ? __builtin_fmaxf(v.z, 0.f) : v.z;
-                v.w = relu ? __builtin_fmaxf(v.w, 0.f) : v.w;
-                char* dst = stage_out + (j * 16 + nn) * ROW + (16 * m + 4 * qq) * EB;
-                if constexpr (EB == 4) {
-                    *(f32x4*)dst = v;
-                } else {
-                    uint2 o;
-                    o.x = pack2_from_f32<TO>(v.x, v.y);
-                    o.y = pack2_from_f32<TO>(v.z, v.w);
-                    *(uint2*)dst = o;
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int mm = 0; mm < TMH; ++mm) {
+                    f32x4 v = acc[h * TMH + mm][j];
+                    v.x = relu ? __builtin_fmaxf(v.x, 0.f) : v.x;
+                    v.y = relu ? __builtin_fmaxf(v.y, 0.f) : v.y;
+                    v.z = relu ? __builtin_fmaxf(v.z, 0.f) : v.z;
+                    v.w = relu ? __builtin_fmaxf(v.w, 0.f) : v.w;
+                    char* dst = stage_out + (j * 16 + nn_e) * ROW + (16 * mm + 4 * qq_e) * EB;
+                    if constexpr (EB == 4) {
+                        *(f32x4*)dst = v;
+                    } else {
+                        uint2 o;
+                        o.x = pack2_from_f32<TO>(v.x, v.y);
+                        o.y = pack2_from_f32<TO>(v.z, v.w);
+                        *(uint2*)dst = o;
+                    }
                 }
-            }
-        // read back: a row of 16*TM channels is CH 16-byte chunks; 64 lanes cover 64/CH positions per pass
-        constexpr int CH = TM * 16 * EB / 16;
-        static_assert(64 % CH == 0 || CH % 64 == 0, "row chunks must tile the wave");
-        constexpr int POS_PER_PASS = CH <= 64 ? 64 / CH : 1;
-        constexpr int PASSES = CH <= 64 ? (16 * TN) / POS_PER_PASS : (16 * TN) * (CH / 64);
-        const int co_first = 16 * mt0;
+            // read back: a row of 16*TMH channels is CH 16-byte chunks; 64 lanes cover 64/CH positions per pass
+            constexpr int CH = TMH * 16 * EB / 16;
+            static_assert(64 % CH == 0, "row chunks must tile the wave");
+            constexpr int POS_PER_PASS = 64 / CH;
+            constexpr int PASSES = (16 * TN) / POS_PER_PASS;
+            const int co_first = 16 * (t_mt0 + h * TMH);
 #pragma unroll
-        for (int ps = 0; ps < PASSES; ++ps) {
-            int p, chunk;
-            if constexpr (CH <= 64) {
-                p = ps * POS_PER_PASS + lane / CH;
-                chunk = lane % CH;
-            } else {
-                p = ps / (CH / 64);
-                chunk = (ps % (CH / 64)) * 64 + lane;
+            for (int ps = 0; ps < PASSES; ++ps) {
+                const int p = ps * POS_PER_PASS + lane_e / CH;
+                const int chunk = lane_e % CH;
+                const int j = p >> 4, n = p & 15;
+                const int blk = blk0 + j;
+                const int oh = t_oh0 + 4 * (blk / CT) + (n >> 2), ow = t_ow0 + 4 * (blk % CT) + (n & 3);
+                const int co = co_first + chunk * (16 / EB);
+                const u32x4 v = *(const u32x4*)(stage_out + p * ROW + chunk * 16);
+                if (oh < Ho && ow < Wo && co < Co)  // Co is a multiple of 16, so a chunk is all in or all out
+                    *(u32x4*)(y + (((int64_t)t_n * Ho + oh) * Wo + ow) * Co + co) = v;
             }
-            const int j = p >> 4, n = p & 15;
-            const int blk = blk0 + j;
-            const int oh = oh0 + 4 * (blk / CT) + (n >> 2), ow = ow0 + 4 * (blk % CT) + (n & 3);
-            const int co = co_first + chunk * (16 / EB);
-            const u32x4 v = *(const u32x4*)(stage_out + p * ROW + chunk * 16);
-            if (oh < Ho && ow < Wo && co < Co)  // Co is a multiple of 16, so a chunk is all in or all out
-                *(u32x4*)(y + (((int64_t)n_img * Ho + oh) * Wo + ow) * Co + co) = v;
         }
     }
+    if (!has_next) break;
+    work = next_work;
+    __syncthreads();  // staging slices are read; the region may be overwritten by the next copies
+  }
 }
 
 template <typename T, typename TO, int S, int TM, int TN, int RT, int CT>
@@ -630,7 +672,8 @@ rtoss_status launch_variant(const rtoss_wdesc& d, const rtoss_cdesc& c, const ch
     const int tiles_r = (Ho + G::TH - 1) / G::TH, tiles_c = (Wo + G::TW - 1) / G::TW;
     const int m_tiles_total = padded_m_tiles(d.Co);  // pitch of the packed section
     const int co_blocks = ((d.Co + 15) / 16 + TM - 1) / TM;
-    const size_t smem = 2 * ((size_t)TM * kTileBytes + G::x_bytes);
+    constexpr int x_copies_per_wave = ((G::x_bytes / 16 + 63) / 64 + 3) / 4;
+    const size_t smem = 2 * ((size_t)TM * kTileBytes + (size_t)x_copies_per_wave * 4096);
     auto kern = conv3x3_sparse_kernel<T, TO, S, TM, TN, RT, CT>;
     static bool attr_set = false;  // per instantiation
     if (!attr_set) {
@@ -643,9 +686,19 @@ rtoss_status launch_variant(const rtoss_wdesc& d, const rtoss_cdesc& c, const ch
     if (total > 0x3fffffff) return fail(RTOSS_ESHAPE, "conv: too many tiles");
     if ((int64_t)c.N * c.H * c.W * d.Ci / 8 > 0x7fffffff) return fail(RTOSS_ESHAPE, "conv: input too large for 32-bit chunk offsets");
     const int work_per_xcd = (int)((total + 7) / 8);
-    dim3 grid((unsigned)(work_per_xcd * 8)), block(256);
-    kern<<<grid, block, smem, s>>>((const T*)x, (TO*)y, wfrag, c.H, c.W, d.Ci, d.Co, Ho, Wo, m_tiles_total, tiles_c,
-                                   tiles_r * tiles_c, co_blocks, (int)total, work_per_xcd, c.fuse_relu);
+    // one workgroup per compute unit (a workgroup owns nearly all of a unit's LDS), at most one per work item
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8)
+            n = 256;
+        cus = n;
+    }
+    const int slots_per_xcd = std::max(1, std::min(work_per_xcd, cus / 8));
+    dim3 grid((unsigned)(slots_per_xcd * 8)), block(256);
+    const char* zeros = wfrag + fragment_bytes(d);
+    kern<<<grid, block, smem, s>>>((const T*)x, (TO*)y, wfrag, zeros, c.H, c.W, d.Ci, d.Co, Ho, Wo, m_tiles_total,
+                                   tiles_c, tiles_r * tiles_c, co_blocks, (int)total, work_per_xcd, c.fuse_relu);
     return check_hip(hipGetLastError(), "conv3x3 sparse launch");
 }
 
@@ -704,7 +757,7 @@ bool sparse3x3_shape_ok(const rtoss_wdesc& d)
 
 size_t sparse3x3_section_bytes(const rtoss_wdesc& d)
 {
-    return (size_t)(d.Ci / 32) * padded_m_tiles(d.Co) * kTileBytes;
+    return fragment_bytes(d) + zero_block_bytes(d);
 }
 
 rtoss_status launch_pack_sparse3x3(const rtoss_wdesc& d, const void* w, const uint8_t* idx, const Dict& dict,
@@ -712,11 +765,12 @@ rtoss_status launch_pack_sparse3x3(const rtoss_wdesc& d, const void* w, const ui
 {
     const int m_tiles = padded_m_tiles(d.Co);
     const int64_t items = (int64_t)(d.Ci / 32) * m_tiles * 320;
-    dim3 grid((unsigned)((items + 255) / 256)), block(256);
+    const int zero_items = (int)(zero_block_bytes(d) / 16);
+    dim3 grid((unsigned)((items + zero_items + 255) / 256)), block(256);
     if (d.dt == RTOSS_F16)
-        pack_sparse3x3_kernel<f16_t><<<grid, block, 0, s>>>((const f16_t*)w, idx, dict, (char*)section, d.Co, d.Ci, m_tiles, items);
+        pack_sparse3x3_kernel<f16_t><<<grid, block, 0, s>>>((const f16_t*)w, idx, dict, (char*)section, d.Co, d.Ci, m_tiles, items, zero_items);
     else
-        pack_sparse3x3_kernel<bf16_t><<<grid, block, 0, s>>>((const bf16_t*)w, idx, dict, (char*)section, d.Co, d.Ci, m_tiles, items);
+        pack_sparse3x3_kernel<bf16_t><<<grid, block, 0, s>>>((const bf16_t*)w, idx, dict, (char*)section, d.Co, d.Ci, m_tiles, items, zero_items);
     return check_hip(hipGetLastError(), "pack sparse3x3 launch");
 }
 
