@@ -186,33 +186,33 @@ def main():
             dense_ms = None
             print("dense comparator failed: %r" % (e,), file=sys.stderr)
 
-    # ---- CPU baseline: the oracle on a bounded sample (first layer, batch item 0, a few output channels) ----
+    # ---- CPU baseline: the oracle on a bounded sample: whole (layer, batch item) convolutions, taken in
+    # order until the time budget is used up ----
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
-        L = cfg.layers[0]
-        ws, wv = w_host[0]
-        x0 = pl.to_host(xs[0][:1]).copy()  # [1, H, W, Ci] storage
-        xv = wl.to_f64(wl.nhwc_to_nchw(x0), cfg.dtype)
-        t_a = time.perf_counter()
-        idx = oracle.select(wv, masks)
-        wm = oracle.mask(wv, masks, idx)
-        t_b = time.perf_counter()
-        probe_c = 1
-        t_c = time.perf_counter()
-        oracle.conv2d(xv, wm[:probe_c], stride=L.stride)
-        t_d = time.perf_counter()
-        rate = max(t_d - t_c, 1e-4) / probe_c
-        n_co = int(max(1, min(L.Co, args.cpu_seconds / rate)))
-        t_e = time.perf_counter()
-        oracle.conv2d(xv, wm[:n_co], stride=L.stride)
-        t_f = time.perf_counter()
-        sample_nz_macs = L.Ho * L.Wo * cfg.k * n_co * (L.Ci * L.ksize * L.ksize / 9.0)
-        cpu = {"value": 2.0 * sample_nz_macs / (t_f - t_e) / 1e12, "unit": "TFLOP/s", "cores": oracle.threads(),
+        t_sel = time.perf_counter()
+        masked = []
+        for L, (ws, wv) in zip(cfg.layers, w_host):
+            masked.append(oracle.mask(wv, masks, oracle.select(wv, masks)))
+        t_sel = time.perf_counter() - t_sel
+        done_macs, t_conv, n_done = 0.0, 0.0, 0
+        for li, L in enumerate(cfg.layers):
+            for n in range(cfg.N):
+                if t_conv >= args.cpu_seconds:
+                    break
+                x0 = pl.to_host(xs[li][n:n + 1]).copy()  # [1, H, W, Ci] storage, as the GPU saw it
+                xv = wl.to_f64(wl.nhwc_to_nchw(x0), cfg.dtype)
+                t_a = time.perf_counter()
+                oracle.conv2d(xv, masked[li], stride=L.stride, relu=L.relu)
+                t_conv += time.perf_counter() - t_a
+                done_macs += L.Ho * L.Wo * cfg.k * L.groups
+                n_done += 1
+        cpu = {"value": 2.0 * done_macs / t_conv / 1e12, "unit": "TFLOP/s", "cores": oracle.threads(),
                "kind": "oracle",
-               "sample": "layer 0 of %s, batch item 0, output channels 0..%d, all positions (%.2f s); "
-                         "select+mask of the layer's %d groups took %.3f s" % (cfg.name, n_co - 1, t_f - t_e,
-                                                                              L.groups, t_b - t_a)}
+               "sample": "%d whole (layer, batch item) convolutions of %s in layer-major order, %.2f s of oracle "
+                         "conv time; select+mask of all %d groups took %.3f s" % (
+                             n_done, cfg.name, t_conv, sum(L.groups for L in cfg.layers), t_sel)}
 
     out = {
         "metric": "effective TFLOP/s on non-zero MACs, select+pack+pattern-sparse conv",

@@ -1,0 +1,58 @@
+// Matrix-core instruction wrappers and the global -> LDS copy shared by the convolution kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "dtypes.h"
+
+namespace rtoss {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef _Float16 h16 __attribute__((ext_vector_type(16)));
+typedef __bf16 b8 __attribute__((ext_vector_type(8)));
+typedef __bf16 b16 __attribute__((ext_vector_type(16)));
+
+// Matrix instructions.  The accumulator is pinned to the accumulation register file ("a"
+// constraint) and updated in place, so that the 128 loop-carried accumulator registers of a
+// wave never move; everything else (operands, addresses, prefetch) lives in the vector
+// registers.  Written as asm because the register class of a builtin's accumulator is the
+// allocator's choice and it changes with register pressure.
+// Operand hazards: A/B come from LDS reads (waited on by the compiler) or vector ALU results;
+// an accumulator is touched again by a matrix instruction no sooner than TN instructions later,
+// and is read by other instructions only after the K loop (see the s_nop before the epilogue).
+template <typename T> struct Mat;
+template <> struct Mat<f16_t> {
+    static __device__ __forceinline__ void dense(u32x4 a, u32x4 b, f32x4& c)
+    {
+        asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+    }
+    template <int ABID> static __device__ __forceinline__ void sparse(u32x4 a, u32x8 b, f32x4& c, int idx)
+    {
+        if (ABID == 0) asm volatile("v_smfmac_f32_16x16x64_f16 %0, %1, %2, %3" : "+a"(c) : "v"(a), "v"(b), "v"(idx));
+        else asm volatile("v_smfmac_f32_16x16x64_f16 %0, %1, %2, %3 abid:1" : "+a"(c) : "v"(a), "v"(b), "v"(idx));
+    }
+};
+template <> struct Mat<bf16_t> {
+    static __device__ __forceinline__ void dense(u32x4 a, u32x4 b, f32x4& c)
+    {
+        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+    }
+    template <int ABID> static __device__ __forceinline__ void sparse(u32x4 a, u32x8 b, f32x4& c, int idx)
+    {
+        if (ABID == 0) asm volatile("v_smfmac_f32_16x16x64_bf16 %0, %1, %2, %3" : "+a"(c) : "v"(a), "v"(b), "v"(idx));
+        else asm volatile("v_smfmac_f32_16x16x64_bf16 %0, %1, %2, %3 abid:1" : "+a"(c) : "v"(a), "v"(b), "v"(idx));
+    }
+};
+
+// One 16-byte global -> LDS copy per lane without passing through registers: lane i of the
+// wave writes LDS address lds_wave_base + 16 * i (the base must be wave-uniform).
+__device__ __forceinline__ void copy16_to_lds(const void* gsrc, char* lds_wave_base)
+{
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
+                                     (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
+}
+
+}  // namespace rtoss
