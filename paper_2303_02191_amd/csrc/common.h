@@ -71,4 +71,12 @@ rtoss_status launch_pack_sparse3x3(const rtoss_wdesc& d, const void* w, const ui
 rtoss_status launch_conv3x3_sparse(const rtoss_wdesc& d, const rtoss_cdesc& c, const void* section, const void* x,
                                    void* y, hipStream_t s);
 
+// 1x1 convolution on the dense matrix instruction (conv1x1_mma.hip)
+bool dense1x1_shape_ok(const rtoss_wdesc& d);
+size_t dense1x1_section_bytes(const rtoss_wdesc& d);
+rtoss_status launch_pack_dense1x1(const rtoss_wdesc& d, const void* w, const uint8_t* idx, const Dict& dict, void* section,
+                                  hipStream_t s);
+rtoss_status launch_conv1x1_mma(const rtoss_wdesc& d, const rtoss_cdesc& c, const void* section, const void* x, void* y,
+                                hipStream_t s);
+
 }  // namespace rtoss

@@ -112,6 +112,28 @@ def test_conv3x3_matrix_core_dictionaries():
     check(g.conv_nchw(xs, out_dt=wl.F32), ref, wl.F16)
 
 
+MATRIX_CORE_1X1 = [
+    # 1x1 shapes on the matrix-core path (Ci % 32 == 0, Co % 16 == 0): ragged position tiles,
+    # one / several channel blocks, groups of 9 that straddle rows (Ci % 9 != 0), deep K
+    # N, Ci, Co,  H,  W, k, relu
+    (1, 32, 16, 1, 1, 2, False),
+    (1, 32, 32, 9, 13, 2, True),
+    (2, 64, 48, 11, 12, 3, False),
+    (1, 128, 144, 16, 8, 2, False),
+    (3, 256, 272, 7, 19, 2, True),
+    (1, 1024, 512, 5, 5, 2, False),
+    (2, 512, 128, 20, 20, 2, False),
+    (1, 288, 64, 6, 7, 3, False),  # Ci % 9 == 0: groups never straddle rows
+]
+
+
+@pytest.mark.parametrize("dt", [wl.F16, wl.BF16])
+@pytest.mark.parametrize("case", MATRIX_CORE_1X1)
+def test_conv1x1_matrix_core_shapes(dt, case):
+    N, Ci, Co, H, W, k, relu = case
+    run_case(dt, N, Ci, Co, H, W, 1, 1, k, relu, seed=hash(case) % 10000 + dt, x_dist="uniform", w_std=0.03)
+
+
 def test_conv_all_ones_pattern_is_dense():
     # k = 9: one pattern that keeps every tap -> ordinary dense convolution
     run_case(wl.F16, 1, 16, 16, 9, 9, 3, 1, 9, False, seed=1, rule=B.RULE_ALL)
