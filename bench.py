@@ -37,6 +37,10 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense torch conv2d comparator")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="target wall time of the oracle sample")
+    ap.add_argument("--graph", choices=["auto", "on", "off"], default="auto",
+                    help="replay the step from three captured HIP graphs (select, pack, conv); auto: when the "
+                         "workload has more than 8 layers, where eager launches are bound by host time")
+    ap.add_argument("--per-layer", action="store_true", help="after the timed region, time every layer's conv alone (stderr)")
     return ap.parse_args()
 
 
@@ -103,25 +107,45 @@ def main():
     layers = [pl.PackedLayer(L.Co, L.Ci, L.ksize, cfg.k, cfg.dtype, masks) for L in cfg.layers]
     torch.cuda.synchronize()
 
-    stream = torch.cuda.current_stream().cuda_stream
     ev = lambda: torch.cuda.Event(enable_timing=True)
 
-    def step(events=None):
-        if events:
-            events[0].record()
+    def do_select():
+        stream = torch.cuda.current_stream().cuda_stream
         if n3:
             B.rtoss_select_patterns(w3_all.data_ptr(), cfg.dtype, n3, masks, idx3_all.data_ptr(), stream)
         for L, w, idx in zip(cfg.layers, w_dev, idx_dev):
             if L.ksize == 1:
                 B.rtoss_select_patterns(w.data_ptr(), cfg.dtype, L.n_weights, masks, idx.data_ptr(), stream)
-        if events:
-            events[1].record()
+
+    def do_pack():
         for lay, w, idx in zip(layers, w_dev, idx_dev):
             lay.pack(w, idx)
-        if events:
-            events[2].record()
+
+    def do_conv():
         for L, lay, x, y in zip(cfg.layers, layers, xs, ys):
             lay.conv(x, stride=L.stride, relu=L.relu, y=y)
+
+    phases = [do_select, do_pack, do_conv]
+    use_graph = args.graph == "on" or (args.graph == "auto" and len(cfg.layers) > 8)
+    for f in phases:  # first launches also set kernel attributes: must happen outside capture
+        f()
+    torch.cuda.synchronize()
+    if use_graph:
+        # The library allocates nothing and records no memset, so its launches capture as plain
+        # kernel nodes; three graphs so that the phases can still be timed apart.
+        graphs = []
+        for f in phases:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                f()
+            graphs.append(g)
+        phases = [g.replay for g in graphs]
+
+    def step(events=None):
+        for i, f in enumerate(phases):
+            if events:
+                events[i].record()
+            f()
         if events:
             events[3].record()
 
@@ -163,6 +187,22 @@ def main():
     roofline["kernel"] = "rtoss_conv2d_pattern"
     roofline["avg_launch_us"] = conv_launch_s * 1e6
     roofline["launches_per_step"] = n_conv
+
+    if args.per_layer:
+        print("layer  Ci   Co    H  ks s   conv_us  hbm_ideal_us  mfma_ideal_us(nz)", file=sys.stderr)
+        for i, (L, lay, x, y) in enumerate(zip(cfg.layers, layers, xs, ys)):
+            for _ in range(3):
+                lay.conv(x, stride=L.stride, relu=L.relu, y=y)
+            a, b = ev(), ev()
+            a.record()
+            for _ in range(20):
+                lay.conv(x, stride=L.stride, relu=L.relu, y=y)
+            b.record()
+            torch.cuda.synchronize()
+            byts = cfg.N * (L.Ci * L.H * L.W + L.Co * L.Ho * L.Wo) * eb + L.groups * (cfg.k * eb + 1)
+            nz = 2.0 * cfg.N * L.Ho * L.Wo * cfg.k * L.groups
+            print("%3d %5d %4d %4d  %d %d  %8.1f  %8.2f  %8.2f" % (i, L.Ci, L.Co, L.H, L.ksize, L.stride,
+                  a.elapsed_time(b) / 20 * 1e3, byts / PEAK_HBM_GBS / 1e3, nz / PEAK_MFMA_16BIT_TFLOPS / 1e6), file=sys.stderr)
 
     # ---- dense comparator: torch conv2d (MIOpen / hipBLASLt) on the same shapes, bench only ----
     dense_ms = None
@@ -219,6 +259,7 @@ def main():
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.DTYPE_NAMES[cfg.dtype], "data": "synthetic",
+        "launch": "hip_graph" if use_graph else "eager",
         "config": {"workload": cfg.name, "batch": cfg.N, "layers": len(cfg.layers), "k": cfg.k,
                    "patterns": int(masks.size), "nonzero_gflop_per_step": nz_flops / 1e9,
                    "dense_gflop_per_step": 2.0 * cfg.dense_macs() / 1e9},

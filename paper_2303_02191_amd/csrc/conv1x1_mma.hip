@@ -10,8 +10,11 @@
 // once.  So the weights are expanded to zero-filled dense fragments (they are tiny and stay in
 // L2), and the kernel is built to stream activations: channels-last rows are contiguous, a
 // workgroup owns 128 consecutive positions x up to 128 output channels, and K runs over stages
-// of 32 input channels through a 3-deep ring of LDS buffers filled by global -> LDS copies two
-// stages ahead.
+// of 32 input channels through a 5-deep ring of LDS buffers filled by global -> LDS copies four
+// stages ahead (an HBM-bound kernel lives on bytes in flight: two resident workgroups per CU x
+// four stages x 8 KB of activations).  Activation rows sit in LDS at a 64-byte pitch with their
+// four 16-byte chunks XOR-swizzled by (position / 2) % 4, which makes the 16-byte operand reads
+// of 8 neighbouring positions hit 8 different bank groups without any padding.
 //
 // Operand layout of v_mfma_f32_16x16x32 (wave64; r = lane % 16, q = lane / 16): A lane holds
 // row r, K = 8q..8q+7; B lane holds column r, K = 8q..8q+7; D lane holds column r, rows 4q..4q+3.
@@ -26,9 +29,8 @@ namespace rtoss {
 namespace {
 
 constexpr int kFrag = 1024;      // one A fragment: 64 lanes x 16 bytes = 16 output channels x 32 input channels
-constexpr int kPosBytes = 80;    // 32 channels x 2 B + 16 B pad: conflict-free 16-byte reads across positions
 constexpr int kTilePos = 128;    // positions per workgroup
-constexpr int kRing = 3;
+constexpr int kRing = 5;
 
 inline int padded_tiles(int Co) { return ((Co + 15) / 16 + 7) / 8 * 8; }
 inline size_t frag_bytes(const rtoss_wdesc& d) { return (size_t)(d.Ci / 32) * padded_tiles(d.Co) * kFrag; }
@@ -80,7 +82,7 @@ __global__ __launch_bounds__(256) void conv1x1_mma_kernel(const T* __restrict__ 
     constexpr int TN = 2;                                // 16-position blocks per wave
     constexpr int A_PER_WAVE = (TM + 3) / 4;             // copy instructions per wave and stage (64 lanes x 16 B each)
     constexpr int A_AREA = A_PER_WAVE * 4 * 1024;
-    constexpr int X_PER_WAVE = 3;                        // 128 positions x 5 chunks = 640 chunks = 10 copies, padded to 12
+    constexpr int X_PER_WAVE = 2;                        // 128 positions x 4 chunks = 512 chunks = 8 copies
     constexpr int X_AREA = X_PER_WAVE * 4 * 1024;
     constexpr int STAGE = A_AREA + X_AREA;
     constexpr int CPW = A_PER_WAVE + X_PER_WAVE;         // copies one wave has in flight per stage
@@ -101,9 +103,9 @@ __global__ __launch_bounds__(256) void conv1x1_mma_kernel(const T* __restrict__ 
     const char* x_ptr[X_PER_WAVE];
 #pragma unroll
     for (int k = 0; k < X_PER_WAVE; ++k) {
-        const int c = (k * 4 + wave) * 64 + lane;
-        const int pos = c / 5, q = c % 5;
-        const bool real = q < 4 && pos < kTilePos && p0 + pos < P;
+        const int c = (k * 4 + wave) * 64 + lane;          // LDS chunk this lane fills
+        const int pos = c >> 2, q = (c & 3) ^ ((pos >> 1) & 3);  // ... holds channel chunk q of position pos
+        const bool real = p0 + pos < P;
         x_ptr[k] = real ? (const char*)x + ((p0 + pos) * Ci + q * 8) * 2 : zeros;
     }
     const char* a_ptr[A_PER_WAVE];
@@ -132,27 +134,35 @@ __global__ __launch_bounds__(256) void conv1x1_mma_kernel(const T* __restrict__ 
 #pragma unroll
         for (int j = 0; j < TN; ++j) acc[m][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // Two stages are always in flight behind the one being multiplied.  Past the end the last
-    // stage is fetched again into a free buffer, so that every wave has issued exactly CPW
-    // copies per stage and the wait below can count them.
-    issue_stage(0, 0);
-    issue_stage(min(1, stages - 1), 1);
+    // kRing-1 stages are always in flight or being multiplied.  Past the end the last stage is
+    // fetched again into a free buffer, so that every wave has issued exactly CPW copies per
+    // stage and the wait below can count them.
+    constexpr int AHEAD = kRing - 2;  // stages still in flight when a stage must have landed
+    static_assert(AHEAD * CPW < 64, "outstanding copies must fit the counter");
+#pragma unroll
+    for (int s = 0; s < kRing - 1; ++s) issue_stage(min(s, stages - 1), s);
+    int buf = 0;
     for (int s = 0; s < stages; ++s) {
-        // all but the newest stage's copies of this wave have landed ...
-        __builtin_amdgcn_s_waitcnt(0x0f70 | (CPW & 15) | ((CPW >> 4) << 14));
-        __syncthreads();  // ... and everybody's; everybody is done with the buffer refilled next
-        issue_stage(min(s + 2, stages - 1), (s + 2) % kRing);
-        const char* A = smem + (s % kRing) * STAGE + lane * 16;
-        const char* X = smem + (s % kRing) * STAGE + A_AREA + ((wave * TN * 16 + nn) * kPosBytes + qq * 16);
+        // all but the AHEAD newest stages' copies of this wave have landed ...
+        // (a bare barrier: __syncthreads() would add a fence that waits for ALL outstanding copies)
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(0x0070 | ((AHEAD * CPW) & 15) | (((AHEAD * CPW) >> 4) << 14));  // + lgkmcnt(0)
+        __builtin_amdgcn_s_barrier();  // ... and everybody's; everybody is done with the buffer refilled next
+        asm volatile("" ::: "memory");
+        issue_stage(min(s + kRing - 1, stages - 1), buf == 0 ? kRing - 1 : buf - 1);
+        const char* A = smem + buf * STAGE + lane * 16;
+        // position block j of this wave starts at wave*32 + 16 j; the swizzle depends on n only
+        const char* X = smem + buf * STAGE + A_AREA + (wave * TN * 16 + nn) * 64 + ((qq ^ ((nn >> 1) & 3)) * 16);
         u32x4 b[TN];
 #pragma unroll
-        for (int j = 0; j < TN; ++j) b[j] = *(const u32x4*)(X + j * 16 * kPosBytes);
+        for (int j = 0; j < TN; ++j) b[j] = *(const u32x4*)(X + j * 16 * 64);
 #pragma unroll
         for (int m = 0; m < TM; ++m) {
             const u32x4 a = *(const u32x4*)(A + m * kFrag);
 #pragma unroll
             for (int j = 0; j < TN; ++j) Mat<T>::dense(a, b[j], acc[m][j]);
         }
+        buf = buf + 1 == kRing ? 0 : buf + 1;
     }
     __builtin_amdgcn_s_waitcnt(0x0f70);  // the surplus copies have landed: LDS may be reused
     __syncthreads();
@@ -214,7 +224,7 @@ rtoss_status launch_tm(const rtoss_wdesc& d, const rtoss_cdesc& c, const char* w
     const int64_t total = pos_tiles * co_blocks;
     if (total > 0x3fffffff) return fail(RTOSS_ESHAPE, "conv1x1: too many tiles");
     const int work_per_xcd = (int)((total + 7) / 8);
-    constexpr int stage_bytes = ((TM + 3) / 4) * 4096 + 3 * 4096;
+    constexpr int stage_bytes = ((TM + 3) / 4) * 4096 + 2 * 4096;
     const size_t smem = (size_t)kRing * stage_bytes;
     auto kern = conv1x1_mma_kernel<T, TO, TM>;
     static bool attr_set = false;
