@@ -30,9 +30,10 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // ----- packed blob geometry (host side; the kernels receive section pointers) -----
 enum MatrixFormat {
-    kFormatNone = 0,    // only the live list (section 0): direct kernels
-    kFormatDense = 1,   // zero-filled matrix-core fragments
-    kFormatSparse24 = 2 // 2-of-4 compressed fragments + indices
+    kFormatNone = 0,     // only the live list (section 0): direct kernels
+    kFormatDense = 1,    // 1x1: zero-filled matrix-core fragments
+    kFormatSparse24 = 2, // 3x3: 2-of-4 compressed fragments + indices
+    kFormatStem = 3      // 3x3 with <= 3 input channels: one zero-filled fragment per 16 output channels
 };
 
 struct BlobGeometry {
@@ -78,5 +79,13 @@ rtoss_status launch_pack_dense1x1(const rtoss_wdesc& d, const void* w, const uin
                                   hipStream_t s);
 rtoss_status launch_conv1x1_mma(const rtoss_wdesc& d, const rtoss_cdesc& c, const void* section, const void* x, void* y,
                                 hipStream_t s);
+
+// 3x3 convolution with <= 3 input channels (conv3x3_stem.hip)
+bool stem3x3_shape_ok(const rtoss_wdesc& d);
+size_t stem3x3_section_bytes(const rtoss_wdesc& d);
+rtoss_status launch_pack_stem3x3(const rtoss_wdesc& d, const void* w, const uint8_t* idx, const Dict& dict, void* section,
+                                 hipStream_t s);
+rtoss_status launch_conv3x3_stem(const rtoss_wdesc& d, const rtoss_cdesc& c, const void* section, const void* x, void* y,
+                                 hipStream_t s);
 
 }  // namespace rtoss

@@ -1,0 +1,196 @@
+// 3x3 convolution for very small input channel counts (the 3-channel image stem) on the dense
+// matrix instruction (fp16 / bf16, fp32 accumulate).
+//
+// With Ci <= 3 the whole reduction, K = 9*Ci <= 27, fits one v_mfma_f32_16x16x32 step: a block
+// of 16 output positions x 16 output channels is one instruction, pruned taps are explicit
+// zeros in the weight fragment (there is nothing to skip in a single instruction), and the
+// layer is bound by the output write.  K index k = kh*(3*Ci) + kw*Ci + ci, which is the memory
+// order of a channels-last patch row, so a lane's 8 consecutive K values are short contiguous
+// runs of the input tile staged in LDS.
+//
+// Operand layout (wave64; r = lane % 16, q = lane / 16): A lane holds row r, K = 8q..8q+7; B lane
+// holds column r, K = 8q..8q+7; D lane holds column r, rows 4q..4q+3.
+#include "common.h"
+#include "dtypes.h"
+#include "mma.h"
+
+namespace rtoss {
+
+namespace {
+
+constexpr int kTH = 8, kTW = 32;  // output tile: 8 rows x 32 columns = 16 blocks of 16 positions
+
+template <typename T> struct Dense16;
+template <> struct Dense16<f16_t> {
+    static __device__ __forceinline__ f32x4 mma(u32x4 a, u32x4 b, f32x4 c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, a), __builtin_bit_cast(h8, b), c, 0, 0, 0);
+    }
+};
+template <> struct Dense16<bf16_t> {
+    static __device__ __forceinline__ f32x4 mma(u32x4 a, u32x4 b, f32x4 c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(b8, a), __builtin_bit_cast(b8, b), c, 0, 0, 0);
+    }
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void pack_stem_kernel(const T* __restrict__ w, const uint8_t* __restrict__ idx, Dict dict,
+                                                        char* __restrict__ out, int Co, int Ci, int m_tiles)
+{
+    __shared__ uint16_t masks[256];
+    masks[threadIdx.x] = dict.mask[threadIdx.x];
+    __syncthreads();
+    const int item = blockIdx.x * 256 + threadIdx.x;  // (m_tile, lane)
+    if (item >= m_tiles * 64) return;
+    const int lane = item % 64, mt = item / 64;
+    const int co = 16 * mt + lane % 16, q = lane / 16;
+    uint16_t v[8];
+    for (int j = 0; j < 8; ++j) {
+        const int k = 8 * q + j;
+        v[j] = 0;
+        if (co < Co && k < 9 * Ci) {
+            const int kh = k / (3 * Ci), kw = (k % (3 * Ci)) / Ci, ci = k % Ci;
+            const int t = 3 * kh + kw;
+            const int64_t g9 = (int64_t)co * Ci + ci;
+            if ((masks[idx[g9]] >> t) & 1u) v[j] = __builtin_bit_cast(uint16_t, w[g9 * 9 + t]);
+        }
+    }
+    u32x4 pk;
+    pk.x = v[0] | ((uint32_t)v[1] << 16);
+    pk.y = v[2] | ((uint32_t)v[3] << 16);
+    pk.z = v[4] | ((uint32_t)v[5] << 16);
+    pk.w = v[6] | ((uint32_t)v[7] << 16);
+    *(u32x4*)(out + (size_t)item * 16) = pk;
+}
+
+template <typename T, typename TO, int S, int TM>
+__global__ __launch_bounds__(256) void conv3x3_stem_kernel(const T* __restrict__ x, TO* __restrict__ y,
+                                                           const char* __restrict__ wfrag, int H, int W, int Ci, int Co,
+                                                           int Ho, int Wo, int tiles_c, int relu)
+{
+    constexpr int IH = (kTH - 1) * S + 3, IW = (kTW - 1) * S + 3;
+    constexpr int MAXROW = IW * 3 + 1;  // halves per staged row (Ci <= 3), odd pitch
+    __shared__ uint16_t xs[IH * MAXROW];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int tile_r = blockIdx.x / tiles_c, tile_c = blockIdx.x % tiles_c;
+    const int n_img = blockIdx.y;
+    const int oh0 = tile_r * kTH, ow0 = tile_c * kTW;
+    const int ih0 = oh0 * S - 1, iw0 = ow0 * S - 1;
+    const int rowlen = IW * Ci;  // halves per row actually used
+
+    // ---- stage the input tile (with halo, zero padded): consecutive lanes read consecutive halves ----
+    const uint16_t* xin = (const uint16_t*)x;
+    for (int e = tid; e < IH * rowlen; e += 256) {
+        const int pr = e / rowlen, off = e - pr * rowlen;
+        const int ih = ih0 + pr, iw = iw0 + off / Ci;
+        uint16_t v = 0;
+        if (ih >= 0 && ih < H && iw >= 0 && iw < W) v = xin[(((int64_t)n_img * H + ih) * W + iw0) * Ci + off];
+        xs[pr * MAXROW + off] = v;
+    }
+    // weight fragments stay in registers: TM tiles of 16 output channels
+    u32x4 afrag[TM];
+#pragma unroll
+    for (int m = 0; m < TM; ++m) afrag[m] = *(const u32x4*)(wfrag + (m * 64 + lane) * 16);
+    __syncthreads();
+
+    const int nn = lane & 15, qq = lane >> 4;
+    const int k3 = 3 * Ci, K = 9 * Ci;
+#pragma unroll 1
+    for (int jb = 0; jb < 4; ++jb) {
+        const int blk = wave * 4 + jb;            // 16 blocks: 8 rows x 2 half-rows of 16 columns
+        const int r = blk >> 1, c = (blk & 1) * 16 + nn;
+        uint16_t bv[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int k = 8 * qq + j;
+            const int kh = k / k3, off = k - kh * k3;
+            bv[j] = k < K ? xs[(r * S + kh) * MAXROW + c * S * Ci + off] : (uint16_t)0;
+        }
+        u32x4 b;
+        b.x = bv[0] | ((uint32_t)bv[1] << 16);
+        b.y = bv[2] | ((uint32_t)bv[3] << 16);
+        b.z = bv[4] | ((uint32_t)bv[5] << 16);
+        b.w = bv[6] | ((uint32_t)bv[7] << 16);
+        const int oh = oh0 + r, ow = ow0 + c;
+        const bool inside = oh < Ho && ow < Wo;
+        TO* yp = y + (((int64_t)n_img * Ho + oh) * Wo + ow) * Co;
+#pragma unroll
+        for (int m = 0; m < TM; ++m) {
+            f32x4 v = Dense16<T>::mma(afrag[m], b, f32x4{0.f, 0.f, 0.f, 0.f});
+            v.x = relu ? __builtin_fmaxf(v.x, 0.f) : v.x;
+            v.y = relu ? __builtin_fmaxf(v.y, 0.f) : v.y;
+            v.z = relu ? __builtin_fmaxf(v.z, 0.f) : v.z;
+            v.w = relu ? __builtin_fmaxf(v.w, 0.f) : v.w;
+            const int co = 16 * m + 4 * qq;
+            if (inside && co < Co) {
+                if constexpr (sizeof(TO) == 4) {
+                    *(f32x4*)(yp + co) = v;
+                } else {
+                    uint2 o;
+                    o.x = pack2_from_f32<TO>(v.x, v.y);
+                    o.y = pack2_from_f32<TO>(v.z, v.w);
+                    *(uint2*)(yp + co) = o;
+                }
+            }
+        }
+    }
+}
+
+template <typename T, typename TO, int S, int TM>
+rtoss_status launch_stem(const rtoss_wdesc& d, const rtoss_cdesc& c, const char* wfrag, const void* x, void* y, hipStream_t s)
+{
+    const int Ho = (c.H + 2 - 3) / S + 1, Wo = (c.W + 2 - 3) / S + 1;
+    const int tiles_r = (Ho + kTH - 1) / kTH, tiles_c = (Wo + kTW - 1) / kTW;
+    if (c.N > 65535) return fail(RTOSS_ESHAPE, "conv: batch too large");
+    dim3 grid((unsigned)(tiles_r * tiles_c), (unsigned)c.N), block(256);
+    conv3x3_stem_kernel<T, TO, S, TM><<<grid, block, 0, s>>>((const T*)x, (TO*)y, wfrag, c.H, c.W, d.Ci, d.Co, Ho, Wo, tiles_c,
+                                                             c.fuse_relu);
+    return check_hip(hipGetLastError(), "conv3x3 stem launch");
+}
+
+template <typename T, typename TO>
+rtoss_status launch_typed(const rtoss_wdesc& d, const rtoss_cdesc& c, const char* wfrag, const void* x, void* y, hipStream_t s)
+{
+    const int tiles = (d.Co + 15) / 16;
+    if (c.stride == 1) {
+        if (tiles <= 2) return launch_stem<T, TO, 1, 2>(d, c, wfrag, x, y, s);
+        return launch_stem<T, TO, 1, 4>(d, c, wfrag, x, y, s);
+    }
+    if (tiles <= 2) return launch_stem<T, TO, 2, 2>(d, c, wfrag, x, y, s);
+    return launch_stem<T, TO, 2, 4>(d, c, wfrag, x, y, s);
+}
+
+}  // namespace
+
+bool stem3x3_shape_ok(const rtoss_wdesc& d)
+{
+    return d.ksize == 3 && (d.dt == RTOSS_F16 || d.dt == RTOSS_BF16) && d.Ci <= 3 && d.Co % 16 == 0 && d.Co <= 64;
+}
+
+size_t stem3x3_section_bytes(const rtoss_wdesc& d) { return (size_t)4 * 1024; }  // 4 tiles, unused ones zero
+
+rtoss_status launch_pack_stem3x3(const rtoss_wdesc& d, const void* w, const uint8_t* idx, const Dict& dict, void* section,
+                                 hipStream_t s)
+{
+    dim3 grid(1), block(256);
+    if (d.dt == RTOSS_F16)
+        pack_stem_kernel<f16_t><<<grid, block, 0, s>>>((const f16_t*)w, idx, dict, (char*)section, d.Co, d.Ci, 4);
+    else
+        pack_stem_kernel<bf16_t><<<grid, block, 0, s>>>((const bf16_t*)w, idx, dict, (char*)section, d.Co, d.Ci, 4);
+    return check_hip(hipGetLastError(), "pack stem launch");
+}
+
+rtoss_status launch_conv3x3_stem(const rtoss_wdesc& d, const rtoss_cdesc& c, const void* section, const void* x, void* y,
+                                 hipStream_t s)
+{
+    const char* wf = (const char*)section;
+    const bool f32out = c.out_dt == RTOSS_F32;
+    if (d.dt == RTOSS_F16)
+        return f32out ? launch_typed<f16_t, float>(d, c, wf, x, y, s) : launch_typed<f16_t, f16_t>(d, c, wf, x, y, s);
+    return f32out ? launch_typed<bf16_t, float>(d, c, wf, x, y, s) : launch_typed<bf16_t, bf16_t>(d, c, wf, x, y, s);
+}
+
+}  // namespace rtoss

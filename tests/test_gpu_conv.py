@@ -134,6 +134,24 @@ def test_conv1x1_matrix_core_shapes(dt, case):
     run_case(dt, N, Ci, Co, H, W, 1, 1, k, relu, seed=hash(case) % 10000 + dt, x_dist="uniform", w_std=0.03)
 
 
+STEM = [
+    # <= 3 input channels (image stem): N, Ci, Co, H, W, stride, k, relu
+    (1, 3, 32, 64, 64, 2, 2, False),
+    (2, 3, 16, 37, 45, 2, 3, True),
+    (1, 3, 64, 19, 70, 1, 2, False),
+    (1, 1, 32, 9, 9, 1, 3, False),
+    (2, 2, 48, 33, 17, 2, 2, True),
+    (1, 3, 32, 1, 1, 1, 2, False),
+]
+
+
+@pytest.mark.parametrize("dt", [wl.F16, wl.BF16])
+@pytest.mark.parametrize("case", STEM)
+def test_conv3x3_stem_shapes(dt, case):
+    N, Ci, Co, H, W, stride, k, relu = case
+    run_case(dt, N, Ci, Co, H, W, 3, stride, k, relu, seed=hash(case) % 10000 + dt, w_std=0.1)
+
+
 def test_conv_all_ones_pattern_is_dense():
     # k = 9: one pattern that keeps every tap -> ordinary dense convolution
     run_case(wl.F16, 1, 16, 16, 9, 9, 3, 1, 9, False, seed=1, rule=B.RULE_ALL)
