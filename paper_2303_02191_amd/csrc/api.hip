@@ -220,12 +220,13 @@ rtoss_status rtoss_pack(const rtoss_wdesc* desc, const void* w_dev, const uint8_
     if (misaligned(w_dev, elem_bytes(desc->dt))) return fail(RTOSS_EINVAL, "w_dev is not aligned to its element size");
     hipStream_t s = (hipStream_t)hip_stream;
     char* blob = (char*)packed_dev;
-    if (rtoss_status st = launch_pack_live(*desc, w_dev, idx_dev, dict, blob + g.live_off, (uint8_t*)(blob + g.idx_off), g.G, s))
-        return st;
-    if (g.format == kFormatSparse24) return launch_pack_sparse3x3(*desc, w_dev, idx_dev, dict, blob + g.mat_off, s);
-    if (g.format == kFormatDense) return launch_pack_dense1x1(*desc, w_dev, idx_dev, dict, blob + g.mat_off, s);
-    if (g.format == kFormatStem) return launch_pack_stem3x3(*desc, w_dev, idx_dev, dict, blob + g.mat_off, s);
-    return RTOSS_OK;
+    void* live = blob + g.live_off;
+    uint8_t* live_idx = (uint8_t*)(blob + g.idx_off);
+    // one launch per layer: the fragment packers also write the public section in their first blocks
+    if (g.format == kFormatSparse24) return launch_pack_sparse3x3(*desc, w_dev, idx_dev, dict, blob + g.mat_off, live, live_idx, s);
+    if (g.format == kFormatDense) return launch_pack_dense1x1(*desc, w_dev, idx_dev, dict, blob + g.mat_off, live, live_idx, s);
+    if (g.format == kFormatStem) return launch_pack_stem3x3(*desc, w_dev, idx_dev, dict, blob + g.mat_off, live, live_idx, s);
+    return launch_pack_live(*desc, w_dev, idx_dev, dict, live, live_idx, g.G, s);
 }
 
 rtoss_status rtoss_conv2d_pattern(const rtoss_wdesc* desc, const rtoss_cdesc* c, const uint16_t* masks_host, int P,

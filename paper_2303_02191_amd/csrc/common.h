@@ -68,7 +68,7 @@ bool sparse3x3_dictionary_ok(const Dict& dict);
 bool sparse3x3_shape_ok(const rtoss_wdesc& d);
 size_t sparse3x3_section_bytes(const rtoss_wdesc& d);
 rtoss_status launch_pack_sparse3x3(const rtoss_wdesc& d, const void* w, const uint8_t* idx, const Dict& dict,
-                                   void* section, hipStream_t s);
+                                   void* section, void* live_values, uint8_t* live_idx, hipStream_t s);
 rtoss_status launch_conv3x3_sparse(const rtoss_wdesc& d, const rtoss_cdesc& c, const void* section, const void* x,
                                    void* y, hipStream_t s);
 
@@ -76,7 +76,7 @@ rtoss_status launch_conv3x3_sparse(const rtoss_wdesc& d, const rtoss_cdesc& c, c
 bool dense1x1_shape_ok(const rtoss_wdesc& d);
 size_t dense1x1_section_bytes(const rtoss_wdesc& d);
 rtoss_status launch_pack_dense1x1(const rtoss_wdesc& d, const void* w, const uint8_t* idx, const Dict& dict, void* section,
-                                  hipStream_t s);
+                                  void* live_values, uint8_t* live_idx, hipStream_t s);
 rtoss_status launch_conv1x1_mma(const rtoss_wdesc& d, const rtoss_cdesc& c, const void* section, const void* x, void* y,
                                 hipStream_t s);
 
@@ -84,7 +84,7 @@ rtoss_status launch_conv1x1_mma(const rtoss_wdesc& d, const rtoss_cdesc& c, cons
 bool stem3x3_shape_ok(const rtoss_wdesc& d);
 size_t stem3x3_section_bytes(const rtoss_wdesc& d);
 rtoss_status launch_pack_stem3x3(const rtoss_wdesc& d, const void* w, const uint8_t* idx, const Dict& dict, void* section,
-                                 hipStream_t s);
+                                 void* live_values, uint8_t* live_idx, hipStream_t s);
 rtoss_status launch_conv3x3_stem(const rtoss_wdesc& d, const rtoss_cdesc& c, const void* section, const void* x, void* y,
                                  hipStream_t s);
 

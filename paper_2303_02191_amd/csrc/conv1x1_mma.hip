@@ -23,6 +23,7 @@
 #include "common.h"
 #include "dtypes.h"
 #include "mma.h"
+#include "pack_live.h"
 
 namespace rtoss {
 
@@ -39,12 +40,16 @@ inline size_t zero_bytes(const rtoss_wdesc& d) { return align_up((size_t)2 * d.C
 template <typename T>
 __global__ __launch_bounds__(256) void pack_dense1x1_kernel(const T* __restrict__ w, const uint8_t* __restrict__ idx,
                                                             Dict dict, char* __restrict__ out, int Co, int Ci, int m_tiles,
-                                                            int64_t G, int64_t total_items, int zero_items)
+                                                            int64_t G, int64_t total_items, int zero_items, LiveJob job)
 {
     __shared__ uint16_t masks[256];
     masks[threadIdx.x] = dict.mask[threadIdx.x];
     __syncthreads();
-    const int64_t item = (int64_t)blockIdx.x * 256 + threadIdx.x;  // (stage, m_tile, lane)
+    if ((int)blockIdx.x < job.blocks) {  // the first blocks write the blob's public section
+        pack_live_block<T>(w, idx, masks, dict.k, job, blockIdx.x);
+        return;
+    }
+    const int64_t item = (int64_t)(blockIdx.x - job.blocks) * 256 + threadIdx.x;  // (stage, m_tile, lane)
     if (item >= total_items) {
         if (item < total_items + zero_items) *(u32x4*)(out + total_items * 16 + (item - total_items) * 16) = u32x4{0, 0, 0, 0};
         return;
@@ -260,17 +265,18 @@ bool dense1x1_shape_ok(const rtoss_wdesc& d)
 size_t dense1x1_section_bytes(const rtoss_wdesc& d) { return frag_bytes(d) + zero_bytes(d); }
 
 rtoss_status launch_pack_dense1x1(const rtoss_wdesc& d, const void* w, const uint8_t* idx, const Dict& dict, void* section,
-                                  hipStream_t s)
+                                  void* live_values, uint8_t* live_idx, hipStream_t s)
 {
     const int m_tiles = padded_tiles(d.Co);
     const int64_t items = (int64_t)(d.Ci / 32) * m_tiles * 64;
     const int zero_items = (int)(zero_bytes(d) / 16);
     const int64_t G = (int64_t)d.Co * d.Ci / 9;
-    dim3 grid((unsigned)((items + zero_items + 255) / 256)), block(256);
+    const LiveJob job = make_live_job(live_values, live_idx, G);
+    dim3 grid((unsigned)(job.blocks + (items + zero_items + 255) / 256)), block(256);
     if (d.dt == RTOSS_F16)
-        pack_dense1x1_kernel<f16_t><<<grid, block, 0, s>>>((const f16_t*)w, idx, dict, (char*)section, d.Co, d.Ci, m_tiles, G, items, zero_items);
+        pack_dense1x1_kernel<f16_t><<<grid, block, 0, s>>>((const f16_t*)w, idx, dict, (char*)section, d.Co, d.Ci, m_tiles, G, items, zero_items, job);
     else
-        pack_dense1x1_kernel<bf16_t><<<grid, block, 0, s>>>((const bf16_t*)w, idx, dict, (char*)section, d.Co, d.Ci, m_tiles, G, items, zero_items);
+        pack_dense1x1_kernel<bf16_t><<<grid, block, 0, s>>>((const bf16_t*)w, idx, dict, (char*)section, d.Co, d.Ci, m_tiles, G, items, zero_items, job);
     return check_hip(hipGetLastError(), "pack dense1x1 launch");
 }
 

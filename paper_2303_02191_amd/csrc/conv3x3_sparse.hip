@@ -36,6 +36,7 @@
 #include "common.h"
 #include "dtypes.h"
 #include "mma.h"
+#include "pack_live.h"
 
 namespace rtoss {
 
@@ -64,12 +65,16 @@ __device__ __forceinline__ int stage_channel(int q, int g, int half)
 template <typename T>
 __global__ __launch_bounds__(256) void pack_sparse3x3_kernel(const T* __restrict__ w, const uint8_t* __restrict__ idx,
                                                              Dict dict, char* __restrict__ out, int Co, int Ci,
-                                                             int m_tiles, int64_t total_items, int zero_items)
+                                                             int m_tiles, int64_t total_items, int zero_items, LiveJob job)
 {
     __shared__ uint16_t masks[256];
     masks[threadIdx.x] = dict.mask[threadIdx.x];
     __syncthreads();
-    const int64_t item = (int64_t)blockIdx.x * 256 + threadIdx.x;  // (stage, m_tile, step 0..4, lane)
+    if ((int)blockIdx.x < job.blocks) {  // the first blocks write the blob's public section
+        pack_live_block<T>(w, idx, masks, dict.k, job, blockIdx.x);
+        return;
+    }
+    const int64_t item = (int64_t)(blockIdx.x - job.blocks) * 256 + threadIdx.x;  // (stage, m_tile, step 0..4, lane)
     if (item >= total_items) {  // the items behind the fragments write the block of zeros, 16 bytes each
         if (item < total_items + zero_items) *(u32x4*)(out + (total_items / 320) * kTileBytes + (item - total_items) * 16) = u32x4{0, 0, 0, 0};
         return;
@@ -569,44 +574,57 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
         int lane_e = lane;
         asm volatile("" : "+v"(lane_e));
         const int nn_e = lane_e & 15, qq_e = lane_e >> 4;
+        // 64-bit address of the tile's first output element once; everything per pass is 32-bit
+        TO* const y_tile = y + (((int64_t)t_n * Ho + t_oh0) * Wo + t_ow0) * Co;
+        const float relu_floor = relu ? 0.f : -__builtin_inff();
 #pragma unroll
         for (int h = 0; h < HALVES; ++h) {
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
+            for (int j = 0; j < TN; ++j) {
+                f32x4 vals[TMH];
+#pragma unroll
+                for (int mm = 0; mm < TMH; ++mm) vals[mm] = acc[h * TMH + mm][j];
+                // fused ReLU without a branch: max with 0, or with -inf when ReLU is off (one v_max_f32 per
+                // value, written as asm so that no NaN-quieting pass is put in front of it)
+#pragma unroll
+                for (int mm = 0; mm < TMH; ++mm)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        float r;
+                        asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(vals[mm][e]), "v"(relu_floor));
+                        vals[mm][e] = r;
+                    }
 #pragma unroll
                 for (int mm = 0; mm < TMH; ++mm) {
-                    f32x4 v = acc[h * TMH + mm][j];
-                    v.x = relu ? __builtin_fmaxf(v.x, 0.f) : v.x;
-                    v.y = relu ? __builtin_fmaxf(v.y, 0.f) : v.y;
-                    v.z = relu ? __builtin_fmaxf(v.z, 0.f) : v.z;
-                    v.w = relu ? __builtin_fmaxf(v.w, 0.f) : v.w;
                     char* dst = stage_out + (j * 16 + nn_e) * ROW + (16 * mm + 4 * qq_e) * EB;
                     if constexpr (EB == 4) {
-                        *(f32x4*)dst = v;
+                        *(f32x4*)dst = vals[mm];
                     } else {
                         uint2 o;
-                        o.x = pack2_from_f32<TO>(v.x, v.y);
-                        o.y = pack2_from_f32<TO>(v.z, v.w);
+                        o.x = pack2_from_f32<TO>(vals[mm].x, vals[mm].y);
+                        o.y = pack2_from_f32<TO>(vals[mm].z, vals[mm].w);
                         *(uint2*)dst = o;
                     }
                 }
+            }
             // read back: a row of 16*TMH channels is CH 16-byte chunks; 64 lanes cover 64/CH positions per pass
             constexpr int CH = TMH * 16 * EB / 16;
             static_assert(64 % CH == 0, "row chunks must tile the wave");
             constexpr int POS_PER_PASS = 64 / CH;
+            static_assert(POS_PER_PASS <= 4 || POS_PER_PASS % 4 == 0, "a pass covers whole rows of a 4x4 block");
             constexpr int PASSES = (16 * TN) / POS_PER_PASS;
             const int co_first = 16 * (t_mt0 + h * TMH);
+            const int sub = lane_e / CH, chunk = lane_e % CH;  // position within the pass, chunk within the row
+            const int co = co_first + chunk * (16 / EB);
 #pragma unroll
             for (int ps = 0; ps < PASSES; ++ps) {
-                const int p = ps * POS_PER_PASS + lane_e / CH;
-                const int chunk = lane_e % CH;
+                const int p = ps * POS_PER_PASS + sub;
                 const int j = p >> 4, n = p & 15;
                 const int blk = blk0 + j;
-                const int oh = t_oh0 + 4 * (blk / CT) + (n >> 2), ow = t_ow0 + 4 * (blk % CT) + (n & 3);
-                const int co = co_first + chunk * (16 / EB);
+                const int dr = 4 * (blk / CT) + (n >> 2), dc = 4 * (blk % CT) + (n & 3);
                 const u32x4 v = *(const u32x4*)(stage_out + p * ROW + chunk * 16);
-                if (oh < Ho && ow < Wo && co < Co)  // Co is a multiple of 16, so a chunk is all in or all out
-                    *(u32x4*)(y + (((int64_t)t_n * Ho + oh) * Wo + ow) * Co + co) = v;
+                if (t_oh0 + dr < Ho && t_ow0 + dc < Wo && co < Co)  // Co is a multiple of 16: a chunk is all in or all out
+                    *(u32x4*)(y_tile + (dr * Wo + dc) * Co + co) = v;
             }
         }
     }
@@ -714,16 +732,17 @@ size_t sparse3x3_section_bytes(const rtoss_wdesc& d)
 }
 
 rtoss_status launch_pack_sparse3x3(const rtoss_wdesc& d, const void* w, const uint8_t* idx, const Dict& dict,
-                                   void* section, hipStream_t s)
+                                   void* section, void* live_values, uint8_t* live_idx, hipStream_t s)
 {
+    const LiveJob job = make_live_job(live_values, live_idx, (int64_t)d.Co * d.Ci);
     const int m_tiles = padded_m_tiles(d.Co);
     const int64_t items = (int64_t)(d.Ci / 32) * m_tiles * 320;
     const int zero_items = (int)(zero_block_bytes(d) / 16);
-    dim3 grid((unsigned)((items + zero_items + 255) / 256)), block(256);
+    dim3 grid((unsigned)(job.blocks + (items + zero_items + 255) / 256)), block(256);
     if (d.dt == RTOSS_F16)
-        pack_sparse3x3_kernel<f16_t><<<grid, block, 0, s>>>((const f16_t*)w, idx, dict, (char*)section, d.Co, d.Ci, m_tiles, items, zero_items);
+        pack_sparse3x3_kernel<f16_t><<<grid, block, 0, s>>>((const f16_t*)w, idx, dict, (char*)section, d.Co, d.Ci, m_tiles, items, zero_items, job);
     else
-        pack_sparse3x3_kernel<bf16_t><<<grid, block, 0, s>>>((const bf16_t*)w, idx, dict, (char*)section, d.Co, d.Ci, m_tiles, items, zero_items);
+        pack_sparse3x3_kernel<bf16_t><<<grid, block, 0, s>>>((const bf16_t*)w, idx, dict, (char*)section, d.Co, d.Ci, m_tiles, items, zero_items, job);
     return check_hip(hipGetLastError(), "pack sparse3x3 launch");
 }
 

@@ -13,6 +13,7 @@
 #include "common.h"
 #include "dtypes.h"
 #include "mma.h"
+#include "pack_live.h"
 
 namespace rtoss {
 
@@ -36,12 +37,16 @@ template <> struct Dense16<bf16_t> {
 
 template <typename T>
 __global__ __launch_bounds__(256) void pack_stem_kernel(const T* __restrict__ w, const uint8_t* __restrict__ idx, Dict dict,
-                                                        char* __restrict__ out, int Co, int Ci, int m_tiles)
+                                                        char* __restrict__ out, int Co, int Ci, int m_tiles, LiveJob job)
 {
     __shared__ uint16_t masks[256];
     masks[threadIdx.x] = dict.mask[threadIdx.x];
     __syncthreads();
-    const int item = blockIdx.x * 256 + threadIdx.x;  // (m_tile, lane)
+    if ((int)blockIdx.x < job.blocks) {  // the first blocks write the blob's public section
+        pack_live_block<T>(w, idx, masks, dict.k, job, blockIdx.x);
+        return;
+    }
+    const int item = (blockIdx.x - job.blocks) * 256 + threadIdx.x;  // (m_tile, lane)
     if (item >= m_tiles * 64) return;
     const int lane = item % 64, mt = item / 64;
     const int co = 16 * mt + lane % 16, q = lane / 16;
@@ -173,13 +178,14 @@ bool stem3x3_shape_ok(const rtoss_wdesc& d)
 size_t stem3x3_section_bytes(const rtoss_wdesc& d) { return (size_t)4 * 1024; }  // 4 tiles, unused ones zero
 
 rtoss_status launch_pack_stem3x3(const rtoss_wdesc& d, const void* w, const uint8_t* idx, const Dict& dict, void* section,
-                                 hipStream_t s)
+                                 void* live_values, uint8_t* live_idx, hipStream_t s)
 {
-    dim3 grid(1), block(256);
+    const LiveJob job = make_live_job(live_values, live_idx, (int64_t)d.Co * d.Ci);
+    dim3 grid((unsigned)(job.blocks + 1)), block(256);
     if (d.dt == RTOSS_F16)
-        pack_stem_kernel<f16_t><<<grid, block, 0, s>>>((const f16_t*)w, idx, dict, (char*)section, d.Co, d.Ci, 4);
+        pack_stem_kernel<f16_t><<<grid, block, 0, s>>>((const f16_t*)w, idx, dict, (char*)section, d.Co, d.Ci, 4, job);
     else
-        pack_stem_kernel<bf16_t><<<grid, block, 0, s>>>((const bf16_t*)w, idx, dict, (char*)section, d.Co, d.Ci, 4);
+        pack_stem_kernel<bf16_t><<<grid, block, 0, s>>>((const bf16_t*)w, idx, dict, (char*)section, d.Co, d.Ci, 4, job);
     return check_hip(hipGetLastError(), "pack stem launch");
 }
 
