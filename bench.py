@@ -40,6 +40,9 @@ def parse():
     ap.add_argument("--graph", choices=["auto", "on", "off"], default="auto",
                     help="replay the step from three captured HIP graphs (select, pack, conv); auto: when the "
                          "workload has more than 8 layers, where eager launches are bound by host time")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain 256 MiB device copy (a reference dispatch of known traffic for "
+                         "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--per-layer", action="store_true", help="after the timed region, time every layer's conv alone (stderr)")
     return ap.parse_args()
 
@@ -148,6 +151,13 @@ def main():
             f()
         if events:
             events[3].record()
+
+    if args.copy_probe:
+        src = torch.zeros(64 << 20, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.add(src, 1.0, out=dst)  # one elementwise kernel: reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()

@@ -48,6 +48,7 @@ namespace {
 constexpr int kFragBytes = 1024;
 constexpr int kTileBytes = 5 * kFragBytes + 2 * 64 * 4;  // 5632
 constexpr int kXPosBytes = 80;                          // 32 channels x 2 B + 16 B pad
+constexpr bool kDirectEpilogue = false;                 // store D fragments directly (false: transpose through LDS)
 
 __device__ __forceinline__ int tap_of_slot(int group, int f)
 {
@@ -364,6 +365,19 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
     const int work_end = min((xcd + 1) * work_per_xcd, total_work);
     int work = xcd * work_per_xcd + slot_in_xcd;
     if (work >= work_end) return;
+    // All workgroups run the same code on same-sized tiles, so left alone they reach their
+    // epilogues together and the output stores of the whole chip arrive as one burst that the
+    // memory system drains while every matrix pipe idles.  Workgroups that own fewer tiles than
+    // the busiest one have a tile's worth of slack: they start half a tile late, which moves their
+    // store bursts into the others' K loops at no cost to the makespan.
+    {
+        const int my_tiles = (work_end - work + slots_per_xcd - 1) / slots_per_xcd;
+        const int max_tiles = (work_per_xcd + slots_per_xcd - 1) / slots_per_xcd;
+        if (my_tiles < max_tiles) {
+            const int naps = (stages * 4000 + 8000) / 2 / 8128;  // s_sleep 127 = 127 * 64 cycles
+            for (int i = 0; i < naps; ++i) __builtin_amdgcn_s_sleep(127);
+        }
+    }
 
     // ---- per-tile state ----
     // Every lane copies 16 bytes in every copy instruction, so the copy code has no branches: a
@@ -574,9 +588,40 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
         int lane_e = lane;
         asm volatile("" : "+v"(lane_e));
         const int nn_e = lane_e & 15, qq_e = lane_e >> 4;
-        // 64-bit address of the tile's first output element once; everything per pass is 32-bit
+        // 64-bit address of the tile's first output element once; everything else is 32-bit
         TO* const y_tile = y + (((int64_t)t_n * Ho + t_oh0) * Wo + t_ow0) * Co;
         const float relu_floor = relu ? 0.f : -__builtin_inff();
+        if constexpr (kDirectEpilogue) {
+            // straight from the D fragments: 4 consecutive channels per lane and store
+            const int pr_e = nn_e >> 2, pc_e = nn_e & 3;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int blk = blk0 + j;
+                const int dr = 4 * (blk / CT) + pr_e, dc = 4 * (blk % CT) + pc_e;
+                const bool inside = t_oh0 + dr < Ho && t_ow0 + dc < Wo;
+                TO* yp = y_tile + (dr * Wo + dc) * Co + 16 * t_mt0 + 4 * qq_e;
+#pragma unroll
+                for (int m = 0; m < TM; ++m) {
+                    f32x4 v = acc[m][j];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        float r;
+                        asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(v[e]), "v"(relu_floor));
+                        v[e] = r;
+                    }
+                    if (inside && 16 * (t_mt0 + m) < Co) {
+                        if constexpr (EB == 4) {
+                            *(f32x4*)(yp + 16 * m) = v;
+                        } else {
+                            uint2 o;
+                            o.x = pack2_from_f32<TO>(v.x, v.y);
+                            o.y = pack2_from_f32<TO>(v.z, v.w);
+                            *(uint2*)(yp + 16 * m) = o;
+                        }
+                    }
+                }
+            }
+        } else {
 #pragma unroll
         for (int h = 0; h < HALVES; ++h) {
 #pragma unroll
@@ -627,10 +672,17 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
                     *(u32x4*)(y_tile + (dr * Wo + dc) * Co + co) = v;
             }
         }
+        }
     }
     if (!has_next) break;
     work = next_work;
-    __syncthreads();  // staging slices are read; the region may be overwritten by the next copies
+    // staging slices are read (LDS only): the region may be overwritten by the next copies.  A bare
+    // barrier, because __syncthreads() carries a fence that would wait here for this tile's output
+    // stores to drain; they drain behind the next tile's first stage instead.
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0) only
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
   }
 }
 
