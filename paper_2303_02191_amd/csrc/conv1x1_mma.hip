@@ -181,6 +181,7 @@ __global__ __launch_bounds__(256) void conv1x1_mma_kernel(const T* __restrict__ 
         constexpr int ROW = TMH * 16 * EB + (EB == 2 ? 8 : 16);
         static_assert(4 * 16 * TN * ROW <= kRing * STAGE, "epilogue staging must fit in the ring");
         char* stage_out = smem + wave * (16 * TN * ROW);
+        const float relu_floor = relu ? 0.f : -__builtin_inff();
 #pragma unroll
         for (int h = 0; h < HALVES; ++h) {
 #pragma unroll
@@ -188,10 +189,12 @@ __global__ __launch_bounds__(256) void conv1x1_mma_kernel(const T* __restrict__ 
 #pragma unroll
                 for (int mm = 0; mm < TMH; ++mm) {
                     f32x4 v = acc[h * TMH + mm][j];
-                    v.x = relu ? __builtin_fmaxf(v.x, 0.f) : v.x;
-                    v.y = relu ? __builtin_fmaxf(v.y, 0.f) : v.y;
-                    v.z = relu ? __builtin_fmaxf(v.z, 0.f) : v.z;
-                    v.w = relu ? __builtin_fmaxf(v.w, 0.f) : v.w;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {  // fused ReLU: max with 0, or with -inf when it is off
+                        float r;
+                        asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(v[e]), "v"(relu_floor));
+                        v[e] = r;
+                    }
                     char* dst = stage_out + (j * 16 + nn) * ROW + (16 * mm + 4 * qq) * EB;
                     if constexpr (EB == 4) {
                         *(f32x4*)dst = v;
