@@ -6,20 +6,24 @@
 //
 // Mapping: a workgroup owns an 8x8 tile of output positions (one position per lane) and a
 // block of output channels; each of its 4 wavefronts owns kCoPerWave of those channels, so
-// the weight, its pattern index and its tap offsets are wave-uniform and every lane reads
-// the activation tile in LDS at "own position + uniform tap offset", which is conflict
-// free for stride 1.  The activation tile (with its halo) is staged channel-chunk by
-// channel-chunk from channels-last global memory into LDS as fp32, channel-major.
+// the weight and its tap offset are wave-uniform and every lane reads the activation tile
+// in LDS at "own position + uniform tap offset", which is conflict free for stride 1.
+// Per chunk of input channels the workgroup stages, into LDS, (a) the activation tile with
+// its halo as fp32, channel-major, and (b) for every (output channel, input channel) pair
+// of the block its k live weights as fp32 and the k LDS offsets of their taps.  The inner
+// loop then touches LDS only: one broadcast read of the weights, one of the offsets and k
+// activation reads per pair, with no dependent global loads in flight.
 #include "common.h"
 #include "dtypes.h"
 
 namespace rtoss {
 
 constexpr int kTile = 8;        // output tile is kTile x kTile positions
-constexpr int kCoPerWave = 8;   // accumulators per lane
+constexpr int kCoPerWave = 4;   // accumulators per lane
 constexpr int kWaves = 4;
 constexpr int kCoPerBlock = kCoPerWave * kWaves;
 constexpr int kChunk = 16;      // input channels staged per round
+constexpr int kPairs = kCoPerBlock * kChunk;
 
 template <int KS, int S> struct Halo {
     static constexpr int side = (kTile - 1) * S + KS;
@@ -27,15 +31,20 @@ template <int KS, int S> struct Halo {
     static constexpr int padded = count | 1;  // odd row length: channel-major writes spread over banks
 };
 
-template <typename T, typename TO, int KS, int S>
+// KK = entries per kernel known at compile time (2, 3, 4), or 0: read k at run time.
+// For 1x1 layers every pair carries exactly one weight (zero when pruned) at offset 0.
+template <typename T, typename TO, int KS, int S, int KK>
 __global__ __launch_bounds__(256) void conv_direct_kernel(const T* __restrict__ x, TO* __restrict__ y,
                                                           const T* __restrict__ live, const uint8_t* __restrict__ lidx,
                                                           Dict dict, int N, int H, int W, int Ci, int Co, int Ho, int Wo,
                                                           int tiles_w, int relu, int64_t G)
 {
     using HL = Halo<KS, S>;
+    constexpr int WS = KS == 1 ? 1 : (KK ? KK : 9);  // weights (and offsets) stored per pair
     __shared__ float xs[kChunk * HL::padded];
-    __shared__ int16_t tapoff[256 * 9];  // LDS offset of the j-th live tap of pattern p (3x3 only)
+    __shared__ __align__(16) float wl[kPairs * WS];
+    __shared__ __align__(16) int16_t ol[kPairs * WS];
+    __shared__ int16_t tapoff[KS == 3 ? 256 * 9 : 1];  // LDS offset of the j-th live tap of pattern p
     __shared__ uint16_t masks[256];
 
     const int tid = threadIdx.x;
@@ -44,8 +53,8 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(const T* __restrict__ 
     const int tile = blockIdx.x;
     const int th = tile / tiles_w, tw = tile % tiles_w;
     const int n = blockIdx.z;
-    const int co_base = blockIdx.y * kCoPerBlock + wave * kCoPerWave;
-    const int k = dict.k;
+    const int co_block = blockIdx.y * kCoPerBlock;
+    const int k = KS == 1 ? 1 : (KK ? KK : dict.k);
 
     masks[tid] = dict.mask[tid];
     if (KS == 3) {
@@ -76,33 +85,51 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(const T* __restrict__ 
                 v = to_f32(x[(((int64_t)n * H + ih) * W + iw) * Ci + ci0 + ch]);
             xs[ch * HL::padded + pos] = v;
         }
-        __syncthreads();
-
-        for (int ch = 0; ch < nch; ++ch) {
-            const float* xc = xs + ch * HL::padded + base;
-#pragma unroll
-            for (int i = 0; i < kCoPerWave; ++i) {
-                const int co = co_base + i;
-                if (co >= Co) break;  // wave-uniform
-                if (KS == 3) {
-                    const int64_t g = (int64_t)co * Ci + ci0 + ch;
-                    const int p = lidx[g];
-                    const T* wv = live + g * k;
-                    const int16_t* to = tapoff + p * 9;
-                    for (int j = 0; j < k; ++j) acc[i] += to_f32(wv[j]) * xc[to[j]];
-                } else {
-                    // 1x1: the 9-groups run along the flattened [Co][Ci] matrix and may
-                    // straddle rows; element f belongs to group f/9 at tap f%9.
+        // Weights of this chunk.  Pairs outside the layer (channel tails) get weight 0 at
+        // offset 0, so the inner loop needs no bounds test.
+        for (int e = tid; e < kPairs; e += 256) {
+            const int ch = e % kChunk, col = e / kChunk;
+            const int co = co_block + col;
+            const bool inside = co < Co && ch < nch;
+            if (KS == 3) {
+                const int64_t g = (int64_t)co * Ci + ci0 + ch;
+                const int p = inside ? lidx[g] : 0;
+                for (int j = 0; j < k; ++j) {
+                    wl[e * WS + j] = inside ? to_f32(live[g * k + j]) : 0.f;
+                    ol[e * WS + j] = inside ? tapoff[p * 9 + j] : (int16_t)0;
+                }
+            } else {
+                // 1x1: the 9-groups run along the flattened [Co][Ci] matrix and may
+                // straddle rows; element f belongs to group f/9 at tap f%9.
+                float v = 0.f;
+                if (inside) {
                     const int64_t f = (int64_t)co * Ci + ci0 + ch;
                     const int64_t g = f / 9;
                     const int t = (int)(f - g * 9);
                     if (g < G) {
                         const unsigned m = masks[lidx[g]];
-                        if ((m >> t) & 1u) {
-                            const int j = __builtin_popcount(m & ((1u << t) - 1u));
-                            acc[i] += to_f32(live[g * k + j]) * xc[0];
-                        }
+                        if ((m >> t) & 1u) v = to_f32(live[g * dict.k + __builtin_popcount(m & ((1u << t) - 1u))]);
                     }
+                }
+                wl[e] = v;
+                ol[e] = 0;
+            }
+        }
+        __syncthreads();
+
+        const float* xb = xs + base;
+        for (int ch = 0; ch < kChunk; ++ch) {
+            const float* xc = xb + ch * HL::padded;
+#pragma unroll
+            for (int i = 0; i < kCoPerWave; ++i) {
+                const int e = ((wave * kCoPerWave + i) * kChunk + ch) * WS;
+                if (KS == 1) {
+                    acc[i] += wl[e] * xc[0];
+                } else if (KK) {
+#pragma unroll
+                    for (int j = 0; j < KK; ++j) acc[i] += wl[e + j] * xc[ol[e + j]];
+                } else {
+                    for (int j = 0; j < k; ++j) acc[i] += wl[e + j] * xc[ol[e + j]];
                 }
             }
         }
@@ -113,7 +140,7 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(const T* __restrict__ 
         TO* yp = y + (((int64_t)n * Ho + oh) * Wo + ow) * Co;
 #pragma unroll
         for (int i = 0; i < kCoPerWave; ++i) {
-            const int co = co_base + i;
+            const int co = co_block + wave * kCoPerWave + i;
             if (co < Co) {
                 float v = acc[i];
                 if (relu) v = v > 0.f ? v : 0.f;
@@ -135,13 +162,21 @@ static rtoss_status launch_typed(const rtoss_wdesc& d, const rtoss_cdesc& c, con
         return fail(RTOSS_ESHAPE, "conv: batch or channel count too large for the direct kernel");
     dim3 grid((unsigned)(tiles_h * tiles_w), (unsigned)((d.Co + kCoPerBlock - 1) / kCoPerBlock), (unsigned)c.N);
     dim3 block(256);
-#define RTOSS_LAUNCH(KS, S)                                                                                       \
-    conv_direct_kernel<T, TO, KS, S><<<grid, block, 0, s>>>((const T*)x, (TO*)y, (const T*)live, lidx, dict, c.N, c.H, \
-                                                            c.W, d.Ci, d.Co, Ho, Wo, tiles_w, c.fuse_relu, G)
-    if (d.ksize == 3 && c.stride == 1) RTOSS_LAUNCH(3, 1);
-    else if (d.ksize == 3 && c.stride == 2) RTOSS_LAUNCH(3, 2);
-    else if (d.ksize == 1 && c.stride == 1) RTOSS_LAUNCH(1, 1);
+#define RTOSS_LAUNCH(KS, S, KK)                                                                                  \
+    conv_direct_kernel<T, TO, KS, S, KK><<<grid, block, 0, s>>>((const T*)x, (TO*)y, (const T*)live, lidx, dict, c.N, \
+                                                                c.H, c.W, d.Ci, d.Co, Ho, Wo, tiles_w, c.fuse_relu, G)
+#define RTOSS_LAUNCH3(S)                  \
+    switch (dict.k) {                     \
+    case 2: RTOSS_LAUNCH(3, S, 2); break; \
+    case 3: RTOSS_LAUNCH(3, S, 3); break; \
+    case 4: RTOSS_LAUNCH(3, S, 4); break; \
+    default: RTOSS_LAUNCH(3, S, 0); break; \
+    }
+    if (d.ksize == 3 && c.stride == 1) { RTOSS_LAUNCH3(1) }
+    else if (d.ksize == 3 && c.stride == 2) { RTOSS_LAUNCH3(2) }
+    else if (d.ksize == 1 && c.stride == 1) RTOSS_LAUNCH(1, 1, 0);
     else return fail(RTOSS_ESHAPE, "conv: unsupported ksize/stride %d/%d", d.ksize, c.stride);
+#undef RTOSS_LAUNCH3
 #undef RTOSS_LAUNCH
     return check_hip(hipGetLastError(), "conv launch");
 }
