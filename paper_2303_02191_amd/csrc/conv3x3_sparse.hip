@@ -141,6 +141,31 @@ inline int padded_m_tiles(int Co) { return ((Co + 15) / 16 + 7) / 8 * 8; }
 inline size_t fragment_bytes(const rtoss_wdesc& d) { return (size_t)(d.Ci / 32) * padded_m_tiles(d.Co) * kTileBytes; }
 inline size_t zero_block_bytes(const rtoss_wdesc& d) { return align_up((size_t)2 * d.Ci + 16, 256); }
 
+// When the B operands of the sparse steps are fetched and transposed within a stage of 20 units
+// (see the stage loop of conv3x3_sparse_kernel).
+template <int TN> struct JobSchedule {
+    static constexpr int jobs = 2 * TN;
+    static constexpr int load_unit(int q) { return q < TN ? (q - (TN - 3) < -1 ? -1 : q - (TN - 3)) : 6 + (q - TN); }
+    static constexpr int perm_count(int u)
+    {
+        int n = 0;
+        for (int q = 0; q < jobs; ++q) n += load_unit(q) + 1 == u;
+        return n;
+    }
+    static constexpr int perm_first(int u)
+    {
+        for (int q = 0; q < jobs; ++q)
+            if (load_unit(q) + 1 == u) return q;
+        return 0;
+    }
+    static constexpr int read_job(int u)
+    {
+        for (int q = 0; q < jobs; ++q)
+            if (load_unit(q) == u) return q;
+        return -1;
+    }
+};
+
 template <int S, int RT, int CT> struct Geom {
     static constexpr int TH = 4 * RT, TW = 4 * CT;                 // output tile
     static constexpr int IH = (TH - 1) * S + 3, IW = (TW - 1) * S + 3;  // input tile with halo
@@ -338,7 +363,8 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
 {
     using G = Geom<S, RT, CT>;
     static_assert(RT * CT == 4 * TN, "four waves share the position blocks of a workgroup");
-    static_assert(TN == 4, "the software pipeline below is written for 4 position blocks per wave");
+    static_assert(TN == 4 || TN == 5, "the job schedule below covers 4 or 5 position blocks per wave");
+    static_assert(TM == 8, "a stage is 20 units: 5 phases x 4 pairs of channel tiles");
     constexpr int A_BYTES = TM * kTileBytes;
     constexpr int A_WAVE_COPIES = A_BYTES / 1024;              // 64 lanes x 16 B per copy instruction
     constexpr int A_PER_WAVE = (A_WAVE_COPIES + 3) / 4;
@@ -488,80 +514,75 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
             return (d & 1) ? __builtin_amdgcn_perm(rr[3][comp], rr[2][comp], sel)
                            : __builtin_amdgcn_perm(rr[1][comp], rr[0][comp], sel);
         };
-        // job schedule: job -> (group, block, unit in which its 4 reads are issued); permutes run one unit later.
-        // corner operands must be complete before unit 4, edge operands before unit 12.
-        constexpr int kJobs = 8;
-        constexpr int job_group[kJobs] = {0, 0, 0, 0, 1, 1, 1, 1};
-        constexpr int job_block[kJobs] = {0, 1, 2, 3, 0, 1, 2, 3};
-        constexpr int job_load_unit[kJobs] = {-1, 0, 1, 2, 6, 7, 8, 9};  // -1: stage prologue
+        // job schedule: job q < TN = corner taps of block q, job TN + b = edge taps of block b.  A job's 4
+        // reads are issued in unit Sched::load_unit(q) (-1: stage prologue) and permuted one unit later.
+        // Corner operands must be complete before unit 4 (with 5 blocks two jobs share the prologue
+        // and unit 0), edge operands before unit 12.
+        using Sched = JobSchedule<TN>;
+        constexpr int kJobs = Sched::jobs;
+        constexpr int UNIT = 2 * TN;  // matrix instructions per unit: two channel tiles x TN position blocks
 
         u32x4 bc[TN];
         u32x8 bfc[2][TN], bfe[2][TN];
-        u32x4 rr_cur[4], rr_nxt[4];
+        u32x4 rr[kJobs][4];  // every job has its own name; its registers are live from its reads to its permutes
         u32x4 a_cur[2], a_nxt[2];
         int i_cur[2] = {0, 0}, i_nxt[2] = {0, 0};
-        // stage prologue: operands of unit 0 and the first job's taps
+        // stage prologue: operands of unit 0 and the taps of the jobs permuted in unit 0
 #pragma unroll
         for (int j = 0; j < TN; ++j) bc[j] = *(const u32x4*)(X + xb[j] + (G::LW + 1) * kXPosBytes);
         a_cur[0] = *(const u32x4*)(A + 4 * kFragBytes);
         a_cur[1] = *(const u32x4*)(A + kTileBytes + 4 * kFragBytes);
-        raw_load(rr_cur, 0, 0);
+        static_for<kJobs>([&](auto Q) {
+            constexpr int q = decltype(Q)::value;
+            if constexpr (Sched::load_unit(q) == -1) raw_load(rr[q], q % TN, q / TN);
+        });
 
-#pragma unroll
-        for (int u = 0; u < 20; ++u) {
-            const int phase = u / 4, m0 = (u % 4) * 2;
-            // which job (if any) is permuted / read in this unit
-            int job_perm = -1, job_read = -1;
-#pragma unroll
-            for (int q = 0; q < kJobs; ++q) {
-                if (job_load_unit[q] + 1 == u) job_perm = q;
-                if (job_load_unit[q] == u) job_read = q;
-            }
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int mi = i >> 2, j = i & 3, m = m0 + mi;
-                if (phase == 0) Mat<T>::dense(a_cur[mi], bc[j], acc[m][j]);
-                if (phase == 1) Mat<T>::template sparse<0>(a_cur[mi], bfc[0][j], acc[m][j], i_cur[mi]);
-                if (phase == 2) Mat<T>::template sparse<1>(a_cur[mi], bfc[1][j], acc[m][j], i_cur[mi]);
-                if (phase == 3) Mat<T>::template sparse<0>(a_cur[mi], bfe[0][j], acc[m][j], i_cur[mi]);
-                if (phase == 4) Mat<T>::template sparse<1>(a_cur[mi], bfe[1][j], acc[m][j], i_cur[mi]);
-                if (i == 4 && u < COPY_SLOTS) issue_copy_slot(u, copy_stage, gpar ^ 1);
-                if (i == 0) {  // issue the next unit's LDS reads behind the first matrix instruction
-                    if (u + 1 < 20) {
-                        const int np = (u + 1) / 4, nm0 = ((u + 1) % 4) * 2;
-                        const int nstep = np == 0 ? 4 : np - 1;
+        static_for<20>([&](auto U) {
+            constexpr int u = decltype(U)::value;
+            constexpr int phase = u / 4, m0 = (u % 4) * 2;
+            // jobs permuted in this unit (a contiguous range of job numbers) and the job read in it
+            constexpr int perm_first = Sched::perm_first(u), perm_count = Sched::perm_count(u);
+            constexpr int job_read = Sched::read_job(u);
+            static_for<UNIT>([&](auto I) {
+                constexpr int i = decltype(I)::value;
+                constexpr int mi = i / TN, j = i % TN, m = m0 + mi;
+                if constexpr (phase == 0) Mat<T>::dense(a_cur[mi], bc[j], acc[m][j]);
+                if constexpr (phase == 1) Mat<T>::template sparse<0>(a_cur[mi], bfc[0][j], acc[m][j], i_cur[mi]);
+                if constexpr (phase == 2) Mat<T>::template sparse<1>(a_cur[mi], bfc[1][j], acc[m][j], i_cur[mi]);
+                if constexpr (phase == 3) Mat<T>::template sparse<0>(a_cur[mi], bfe[0][j], acc[m][j], i_cur[mi]);
+                if constexpr (phase == 4) Mat<T>::template sparse<1>(a_cur[mi], bfe[1][j], acc[m][j], i_cur[mi]);
+                if constexpr (i == TN && u < COPY_SLOTS) issue_copy_slot(u, copy_stage, gpar ^ 1);
+                if constexpr (i == 0) {  // issue the next unit's LDS reads behind the first matrix instruction
+                    if constexpr (u + 1 < 20) {
+                        constexpr int np = (u + 1) / 4, nm0 = ((u + 1) % 4) * 2;
+                        constexpr int nstep = np == 0 ? 4 : np - 1;
 #pragma unroll
                         for (int t = 0; t < 2; ++t) {
                             a_nxt[t] = *(const u32x4*)(A + (nm0 + t) * kTileBytes + nstep * kFragBytes);
-                            if (np > 0) i_nxt[t] = *(const int*)(AI + (nm0 + t) * kTileBytes + ((np - 1) >> 1) * 256);
+                            if constexpr (np > 0) i_nxt[t] = *(const int*)(AI + (nm0 + t) * kTileBytes + ((np - 1) >> 1) * 256);
                         }
                     }
-                    if (job_read >= 0) raw_load(rr_nxt, job_block[job_read], job_group[job_read]);
+                    if constexpr (job_read >= 0) raw_load(rr[job_read], job_read % TN, job_read / TN);
                 }
-                if (job_perm >= 0) {
-                    const int jb = job_block[job_perm];
-#pragma unroll
-                    for (int t = 0; t < 2; ++t) {
-                        const int o = 2 * i + t;
-                        const uint32_t v = transposed(rr_cur, o);
-                        if (job_group[job_perm] == 0) bfc[o >> 3][jb][o & 7] = v;
-                        else bfe[o >> 3][jb][o & 7] = v;
-                    }
-                }
+                // this instruction's share of the unit's 16 * perm_count permutes
+                constexpr int o_begin = i * 16 * perm_count / UNIT, o_end = (i + 1) * 16 * perm_count / UNIT;
+                static_for<o_end - o_begin>([&](auto O) {
+                    constexpr int o = o_begin + decltype(O)::value;
+                    constexpr int q = perm_first + o / 16, oo = o % 16;
+                    const uint32_t v = transposed(rr[q], oo);
+                    if constexpr (q < TN) bfc[oo >> 3][q][oo & 7] = v;
+                    else bfe[oo >> 3][q - TN][oo & 7] = v;
+                });
                 __builtin_amdgcn_sched_barrier(0);
-            }
-            if (u + 1 < 20) {
+            });
+            if constexpr (u + 1 < 20) {
 #pragma unroll
                 for (int t = 0; t < 2; ++t) {
                     a_cur[t] = a_nxt[t];
                     i_cur[t] = i_nxt[t];
                 }
             }
-            if (job_read >= 0) {
-#pragma unroll
-                for (int f = 0; f < 4; ++f) rr_cur[f] = rr_nxt[f];
-            }
-        }
+        });
         __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): the next stage's copies issued by this wave landed
         __syncthreads();                     // ... and everybody's; everybody is done reading this stage
         gpar ^= 1;
@@ -581,8 +602,10 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
         constexpr int TMH = TM / HALVES;
         static_assert(TM % HALVES == 0, "channel tiles must split evenly");
         constexpr int ROW = TMH * 16 * EB + (EB == 2 ? 8 : 16);  // padded row pitch: spreads the banks
-        static_assert(4 * 16 * TN * ROW <= REGION, "epilogue staging must fit in one region");
-        char* stage_out = smem + (gpar ^ 1) * REGION + wave * (16 * TN * ROW);
+        // position blocks staged together: as many as fit when the four waves share one region
+        constexpr int JG = (REGION / (4 * 16 * ROW)) < TN ? (REGION / (4 * 16 * ROW)) : TN;
+        static_assert(JG >= 1, "epilogue staging must fit in one region");
+        char* stage_out = smem + (gpar ^ 1) * REGION + wave * (16 * JG * ROW);
         // lane-derived addresses of the epilogue are recomputed per tile (opaque copy of the lane id)
         // instead of staying live in registers through the K loop
         int lane_e = lane;
@@ -625,7 +648,11 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
 #pragma unroll
         for (int h = 0; h < HALVES; ++h) {
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
+          for (int j0 = 0; j0 < TN; j0 += JG) {
+            const int jn = j0 + JG <= TN ? JG : TN - j0;  // blocks in this group
+#pragma unroll
+            for (int jj = 0; jj < jn; ++jj) {
+                const int j = j0 + jj;
                 f32x4 vals[TMH];
 #pragma unroll
                 for (int mm = 0; mm < TMH; ++mm) vals[mm] = acc[h * TMH + mm][j];
@@ -641,7 +668,7 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
                     }
 #pragma unroll
                 for (int mm = 0; mm < TMH; ++mm) {
-                    char* dst = stage_out + (j * 16 + nn_e) * ROW + (16 * mm + 4 * qq_e) * EB;
+                    char* dst = stage_out + (jj * 16 + nn_e) * ROW + (16 * mm + 4 * qq_e) * EB;
                     if constexpr (EB == 4) {
                         *(f32x4*)dst = vals[mm];
                     } else {
@@ -652,25 +679,28 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
                     }
                 }
             }
-            // read back: a row of 16*TMH channels is CH 16-byte chunks; 64 lanes cover 64/CH positions per pass
+            // read back: a row of 16*TMH channels is CH 16-byte chunks; 64 lanes cover 64/CH positions per pass.
+            // (A wave's LDS accesses execute in order, so the next group's writes to this slice cannot pass
+            // these reads.)
             constexpr int CH = TMH * 16 * EB / 16;
             static_assert(64 % CH == 0, "row chunks must tile the wave");
             constexpr int POS_PER_PASS = 64 / CH;
             static_assert(POS_PER_PASS <= 4 || POS_PER_PASS % 4 == 0, "a pass covers whole rows of a 4x4 block");
-            constexpr int PASSES = (16 * TN) / POS_PER_PASS;
+            const int passes = (16 * jn) / POS_PER_PASS;
             const int co_first = 16 * (t_mt0 + h * TMH);
             const int sub = lane_e / CH, chunk = lane_e % CH;  // position within the pass, chunk within the row
             const int co = co_first + chunk * (16 / EB);
 #pragma unroll
-            for (int ps = 0; ps < PASSES; ++ps) {
+            for (int ps = 0; ps < passes; ++ps) {
                 const int p = ps * POS_PER_PASS + sub;
-                const int j = p >> 4, n = p & 15;
-                const int blk = blk0 + j;
+                const int jj = p >> 4, n = p & 15;
+                const int blk = blk0 + j0 + jj;
                 const int dr = 4 * (blk / CT) + (n >> 2), dc = 4 * (blk % CT) + (n & 3);
                 const u32x4 v = *(const u32x4*)(stage_out + p * ROW + chunk * 16);
                 if (t_oh0 + dr < Ho && t_ow0 + dc < Wo && co < Co)  // Co is a multiple of 16: a chunk is all in or all out
                     *(u32x4*)(y_tile + (dr * Wo + dc) * Co + co) = v;
             }
+          }
         }
         }
     }
@@ -756,7 +786,19 @@ rtoss_status launch_typed(const rtoss_wdesc& d, const rtoss_cdesc& c, const char
 {
     // The fragment section is padded to a multiple of 8 channel tiles, so any TM <= 8 may over-read rows
     // that hold zeros; outputs beyond Co are never stored.
-    if (c.stride == 1) return launch_variant<T, TO, 1, 8, 4, 4, 4>(d, c, wfrag, x, y, s);
+    if (c.stride == 1) {
+        // Two tile shapes: 16x16 positions, or 20 rows x 16 columns (5 position blocks per wave: better
+        // reuse of the weight fragments, and for some images fewer rounds over the compute units or less
+        // padding).  Cost model: rounds of the busiest workgroup x relative cost of a tile.
+        const int Ho = c.H, Wo = c.W;
+        const int64_t co_blocks = ((d.Co + 15) / 16 + 7) / 8;
+        const int64_t t4 = (int64_t)((Ho + 15) / 16) * ((Wo + 15) / 16) * co_blocks * c.N;
+        const int64_t t5 = (int64_t)((Ho + 19) / 20) * ((Wo + 15) / 16) * co_blocks * c.N;
+        const int64_t slots = 256;
+        const double cost4 = (double)((t4 + slots - 1) / slots) * 4.0, cost5 = (double)((t5 + slots - 1) / slots) * 4.85;
+        if (cost5 < cost4) return launch_variant<T, TO, 1, 8, 5, 5, 4>(d, c, wfrag, x, y, s);
+        return launch_variant<T, TO, 1, 8, 4, 4, 4>(d, c, wfrag, x, y, s);
+    }
     return launch_variant_sb<T, TO, 2, 8, 4, 4, 4>(d, c, wfrag, x, y, s);
 }
 

@@ -85,6 +85,10 @@ MATRIX_CORE = [
     (1, 128, 256, 40, 40, 2, 3, False),
     (1, 32, 32, 1, 1, 1, 3, False),
     (1, 32, 32, 2, 70, 2, 2, False),
+    # enough 16x16 tiles for two rounds over the compute units but one round of 20x16 tiles: the
+    # launcher takes the tall tile (5 position blocks per wave), here with ragged rows and columns
+    (43, 64, 48, 37, 30, 1, 3, True),
+    (130, 32, 16, 21, 16, 1, 2, False),
 ]
 
 
