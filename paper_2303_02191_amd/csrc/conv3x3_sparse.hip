@@ -433,7 +433,7 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
     // One copy instruction (64 lanes x 16 bytes) of stage `stage` of the current tile into region
     // `par`: slots 0 .. A_PER_WAVE-1 move weight fragments, the rest move activations.
     constexpr int COPY_SLOTS = A_PER_WAVE + X_PER_WAVE;
-    static_assert(COPY_SLOTS <= 20, "one copy per pipeline unit");
+    static_assert(COPY_SLOTS <= 20, "two copies per unit in the first ten units of a stage");
     static_assert(A_WAVE_COPIES % 4 == 0, "every wave issues the same number of weight copies");
     auto issue_copy_slot = [&](int slot, int stage, int par) {
         char* region = smem + par * REGION;
@@ -463,12 +463,44 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
 
     f32x4 acc[TM][TN];
 
+    // B operands of the sparse steps need a 4x4 (tap x channel) transpose: a "job" reads the 4 taps of
+    // one position block (4 x 16 bytes) and permutes them one pipeline unit later.  Job q < TN = corner
+    // taps of block q, job TN + b = edge taps of block b (schedule: JobSchedule).
+    using Sched = JobSchedule<TN>;
+    constexpr int kJobs = Sched::jobs;
+    auto raw_load = [&](const char* X, u32x4 (&rr)[4], int j, int group) {
+#pragma unroll
+        for (int f = 0; f < 4; ++f) {
+            const int t = group == 0 ? ((f & 1) * 2 + (f >> 1) * 6) : (2 * f + 1);
+            rr[f] = *(const u32x4*)(X + xb[j] + ((t / 3) * G::LW + (t % 3)) * kXPosBytes);
+        }
+    };
+    // Operand registers that cross stage boundaries: the reads a stage needs before its first matrix
+    // instruction (centre-tap operands of all blocks, weight fragments of unit 0, taps of the jobs
+    // permuted in unit 0) are issued from inside the previous stage's last unit.
+    u32x4 bc[TN];
+    u32x4 rr[kJobs][4];  // every job has its own name; its registers are live from its reads to its permutes
+    u32x4 a_nxt[2];
+    auto load_stage_prologue = [&](int par) {
+        const char* A = smem + par * REGION + lane * 16;
+        const char* X = smem + par * REGION + A_BYTES;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bc[j] = *(const u32x4*)(X + xb[j] + (G::LW + 1) * kXPosBytes);
+        a_nxt[0] = *(const u32x4*)(A + 4 * kFragBytes);
+        a_nxt[1] = *(const u32x4*)(A + kTileBytes + 4 * kFragBytes);
+        static_for<kJobs>([&](auto Q) {
+            constexpr int q = decltype(Q)::value;
+            if constexpr (Sched::load_unit(q) == -1) raw_load(X, rr[q], q % TN, q / TN);
+        });
+    };
+
     setup_tile(work);
 #pragma unroll
     for (int slot = 0; slot < COPY_SLOTS; ++slot) issue_copy_slot(slot, 0, 0);
     __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's copies have landed in LDS
     __syncthreads();                     // ... and everybody's
     int gpar = 0;     // region that holds the stage about to be multiplied
+    load_stage_prologue(0);
 
   for (;;) {  // tiles
     // output coordinates of the tile being multiplied (the copy state moves on to the next tile early)
@@ -492,20 +524,18 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
         const char* X = smem + gpar * REGION + A_BYTES;
 
         // One stage = 5 phases (centre, corner step 0/1, edge step 0/1) of TM*TN matrix
-        // instructions = 20 units of 8 (two channel tiles x four position blocks).  LDS reads are
+        // instructions = 20 units of 2*TN (two channel tiles x TN position blocks).  LDS reads are
         // issued one unit ahead of their use, right after the unit's first matrix instruction,
         // so the wait in front of the next unit's first instruction only covers loads that have
-        // had a whole unit to complete.  B operands of the sparse steps need a 4x4 (tap x
-        // channel) transpose: a "job" reads the 4 taps of one position block (4 x 16 bytes) in
-        // one unit and permutes them, two byte-permutes behind each matrix instruction, in the
-        // next.
-        auto raw_load = [&](u32x4 (&rr)[4], int j, int group) {
-#pragma unroll
-            for (int f = 0; f < 4; ++f) {
-                const int t = group == 0 ? ((f & 1) * 2 + (f >> 1) * 6) : (2 * f + 1);
-                rr[f] = *(const u32x4*)(X + xb[j] + ((t / 3) * G::LW + (t % 3)) * kXPosBytes);
-            }
-        };
+        // had a whole unit to complete; a job's permutes are spread behind the matrix instructions
+        // of the unit after its reads.
+        //
+        // Stage hand-over without a bubble: all of a stage's copies are issued in its first 10 units,
+        // and the reads of the last unit's operands are issued in unit 18.  Behind the first matrix
+        // instruction of unit 19 the wave therefore waits for its copies and its reads, meets the
+        // others at a barrier (the next stage's data is now complete and nobody reads this stage's
+        // region any more), and issues the next stage's first reads, which complete under the rest of
+        // unit 19.
         // output o (0..15) of a job: dword o%8 of step o/8; element 4*c + f of a step's B operand =
         // channel c (of this lane's 4 in that step), tap slot f
         auto transposed = [&](const u32x4 (&rr)[4], int o) -> uint32_t {
@@ -514,28 +544,10 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
             return (d & 1) ? __builtin_amdgcn_perm(rr[3][comp], rr[2][comp], sel)
                            : __builtin_amdgcn_perm(rr[1][comp], rr[0][comp], sel);
         };
-        // job schedule: job q < TN = corner taps of block q, job TN + b = edge taps of block b.  A job's 4
-        // reads are issued in unit Sched::load_unit(q) (-1: stage prologue) and permuted one unit later.
-        // Corner operands must be complete before unit 4 (with 5 blocks two jobs share the prologue
-        // and unit 0), edge operands before unit 12.
-        using Sched = JobSchedule<TN>;
-        constexpr int kJobs = Sched::jobs;
-        constexpr int UNIT = 2 * TN;  // matrix instructions per unit: two channel tiles x TN position blocks
-
-        u32x4 bc[TN];
+        constexpr int UNIT = 2 * TN;  // matrix instructions per unit
         u32x8 bfc[2][TN], bfe[2][TN];
-        u32x4 rr[kJobs][4];  // every job has its own name; its registers are live from its reads to its permutes
-        u32x4 a_cur[2], a_nxt[2];
+        u32x4 a_cur[2] = {a_nxt[0], a_nxt[1]};
         int i_cur[2] = {0, 0}, i_nxt[2] = {0, 0};
-        // stage prologue: operands of unit 0 and the taps of the jobs permuted in unit 0
-#pragma unroll
-        for (int j = 0; j < TN; ++j) bc[j] = *(const u32x4*)(X + xb[j] + (G::LW + 1) * kXPosBytes);
-        a_cur[0] = *(const u32x4*)(A + 4 * kFragBytes);
-        a_cur[1] = *(const u32x4*)(A + kTileBytes + 4 * kFragBytes);
-        static_for<kJobs>([&](auto Q) {
-            constexpr int q = decltype(Q)::value;
-            if constexpr (Sched::load_unit(q) == -1) raw_load(rr[q], q % TN, q / TN);
-        });
 
         static_for<20>([&](auto U) {
             constexpr int u = decltype(U)::value;
@@ -551,7 +563,8 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
                 if constexpr (phase == 2) Mat<T>::template sparse<1>(a_cur[mi], bfc[1][j], acc[m][j], i_cur[mi]);
                 if constexpr (phase == 3) Mat<T>::template sparse<0>(a_cur[mi], bfe[0][j], acc[m][j], i_cur[mi]);
                 if constexpr (phase == 4) Mat<T>::template sparse<1>(a_cur[mi], bfe[1][j], acc[m][j], i_cur[mi]);
-                if constexpr (i == TN && u < COPY_SLOTS) issue_copy_slot(u, copy_stage, gpar ^ 1);
+                if constexpr (i == 2 && 2 * u < COPY_SLOTS) issue_copy_slot(2 * u, copy_stage, gpar ^ 1);
+                if constexpr (i == 2 + TN && 2 * u + 1 < COPY_SLOTS) issue_copy_slot(2 * u + 1, copy_stage, gpar ^ 1);
                 if constexpr (i == 0) {  // issue the next unit's LDS reads behind the first matrix instruction
                     if constexpr (u + 1 < 20) {
                         constexpr int np = (u + 1) / 4, nm0 = ((u + 1) % 4) * 2;
@@ -562,7 +575,14 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
                             if constexpr (np > 0) i_nxt[t] = *(const int*)(AI + (nm0 + t) * kTileBytes + ((np - 1) >> 1) * 256);
                         }
                     }
-                    if constexpr (job_read >= 0) raw_load(rr[job_read], job_read % TN, job_read / TN);
+                    if constexpr (job_read >= 0) raw_load(X, rr[job_read], job_read % TN, job_read / TN);
+                    if constexpr (u == 19) {
+                        asm volatile("" ::: "memory");
+                        __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0): copies landed, reads of this region done
+                        __builtin_amdgcn_s_barrier();
+                        asm volatile("" ::: "memory");
+                        load_stage_prologue(gpar ^ 1);
+                    }
                 }
                 // this instruction's share of the unit's 16 * perm_count permutes
                 constexpr int o_begin = i * 16 * perm_count / UNIT, o_end = (i + 1) * 16 * perm_count / UNIT;
@@ -583,8 +603,6 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
                 }
             }
         });
-        __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): the next stage's copies issued by this wave landed
-        __syncthreads();                     // ... and everybody's; everybody is done reading this stage
         gpar ^= 1;
     }
 
