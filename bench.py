@@ -27,6 +27,34 @@ PEAK_HBM_GBS = 8000.0             # MI355X HBM3E peak
 WORKLOADS = {"cfg1": 1, "cfg2": 2, "cfg3": 3, "cfg4": 4, "cfg5": 5}
 
 
+def measured_traffic(summary_name):
+    """HBM bytes per launch from the committed counter summary, or None.
+
+    The summary (profiles/) records FETCH_SIZE + WRITE_SIZE of the convolution kernel, scaled by what the same
+    counters read for a copy of known size, and a hash of the kernel's sources at the time of the counter
+    runs; once the sources differ the figure no longer describes this kernel and is dropped.
+    """
+    import hashlib
+    here = os.path.dirname(os.path.abspath(__file__))
+    path = os.path.join(here, "profiles", summary_name)
+    if not os.path.exists(path):
+        return None
+    fields = {}
+    for line in open(path):
+        if ":" in line:
+            k, v = line.split(":", 1)
+            fields[k.strip()] = v.strip()
+    try:
+        h = hashlib.sha256()
+        for f in ("conv3x3_sparse.hip", "mma.h", "dtypes.h", "common.h", "pack_live.h"):
+            h.update(open(os.path.join(here, "paper_2303_02191_amd", "csrc", f), "rb").read())
+        if h.hexdigest() != fields.get("kernel_source_sha256"):
+            return None
+        return int(fields["traffic_bytes_per_launch"])
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -194,6 +222,8 @@ def main():
         achieved = nz_flops / n_conv / conv_launch_s / 1e12
         roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_MFMA_16BIT_TFLOPS, "unit": "TFLOP/s",
                     "frac": achieved / PEAK_MFMA_16BIT_TFLOPS, "traffic": None}
+    if args.workload == "cfg4":
+        roofline["traffic"] = measured_traffic("conv3x3_sparse_cfg4_hbm_traffic.txt")
     roofline["kernel"] = "rtoss_conv2d_pattern"
     roofline["avg_launch_us"] = conv_launch_s * 1e6
     roofline["launches_per_step"] = n_conv

@@ -33,7 +33,8 @@ enum MatrixFormat {
     kFormatNone = 0,     // only the live list (section 0): direct kernels
     kFormatDense = 1,    // 1x1: zero-filled matrix-core fragments
     kFormatSparse24 = 2, // 3x3: 2-of-4 compressed fragments + indices
-    kFormatStem = 3      // 3x3 with <= 3 input channels: one zero-filled fragment per 16 output channels
+    kFormatStem = 3,     // 3x3 with <= 3 input channels: one zero-filled fragment per 16 output channels
+    kFormatDenseStream = 4  // 1x1 with Ci = 32 * 2^n <= 1024: zero-filled fragments in the streaming kernel's order
 };
 
 struct BlobGeometry {
@@ -79,6 +80,14 @@ rtoss_status launch_pack_dense1x1(const rtoss_wdesc& d, const void* w, const uin
                                   void* live_values, uint8_t* live_idx, hipStream_t s);
 rtoss_status launch_conv1x1_mma(const rtoss_wdesc& d, const rtoss_cdesc& c, const void* section, const void* x, void* y,
                                 hipStream_t s);
+
+// 1x1 convolution, streaming kernel with register-resident weights (conv1x1_stream.hip)
+bool stream1x1_shape_ok(const rtoss_wdesc& d);
+size_t stream1x1_section_bytes(const rtoss_wdesc& d);
+rtoss_status launch_pack_stream1x1(const rtoss_wdesc& d, const void* w, const uint8_t* idx, const Dict& dict, void* section,
+                                   void* live_values, uint8_t* live_idx, hipStream_t s);
+rtoss_status launch_conv1x1_stream(const rtoss_wdesc& d, const rtoss_cdesc& c, const void* section, const void* x, void* y,
+                                   hipStream_t s);
 
 // 3x3 convolution with <= 3 input channels (conv3x3_stem.hip)
 bool stem3x3_shape_ok(const rtoss_wdesc& d);

@@ -814,7 +814,8 @@ rtoss_status launch_typed(const rtoss_wdesc& d, const rtoss_cdesc& c, const char
         const int64_t t5 = (int64_t)((Ho + 19) / 20) * ((Wo + 15) / 16) * co_blocks * c.N;
         const int64_t slots = 256;
         const double cost4 = (double)((t4 + slots - 1) / slots) * 4.0, cost5 = (double)((t5 + slots - 1) / slots) * 4.85;
-        if (cost5 < cost4) return launch_variant<T, TO, 1, 8, 5, 5, 4>(d, c, wfrag, x, y, s);
+        // (with few stages per tile the taller tile's longer prologue and epilogue outweigh the saved round)
+        if (cost5 < cost4 && d.Ci >= 128) return launch_variant<T, TO, 1, 8, 5, 5, 4>(d, c, wfrag, x, y, s);
         return launch_variant<T, TO, 1, 8, 4, 4, 4>(d, c, wfrag, x, y, s);
     }
     return launch_variant_sb<T, TO, 2, 8, 4, 4, 4>(d, c, wfrag, x, y, s);

@@ -87,8 +87,8 @@ MATRIX_CORE = [
     (1, 32, 32, 2, 70, 2, 2, False),
     # enough 16x16 tiles for two rounds over the compute units but one round of 20x16 tiles: the
     # launcher takes the tall tile (5 position blocks per wave), here with ragged rows and columns
-    (43, 64, 48, 37, 30, 1, 3, True),
-    (130, 32, 16, 21, 16, 1, 2, False),
+    (43, 128, 48, 37, 30, 1, 3, True),
+    (130, 160, 16, 21, 16, 1, 2, False),
 ]
 
 
@@ -128,6 +128,21 @@ MATRIX_CORE_1X1 = [
     (1, 1024, 512, 5, 5, 2, False),
     (2, 512, 128, 20, 20, 2, False),
     (1, 288, 64, 6, 7, 3, False),  # Ci % 9 == 0: groups never straddle rows
+    (1, 96, 32, 13, 11, 2, True),  # Ci / 32 not a power of two: ring kernel with weights in LDS
+    # streaming kernel (Ci = 32 * 2^n): every (depth, wave split) variant, many buffers per workgroup,
+    # ragged last buffer, channel counts that do not fill the workgroup's channel span
+    (4, 64, 32, 40, 37, 2, False),
+    (2, 32, 64, 50, 33, 2, True),
+    (1, 32, 256, 30, 30, 3, False),
+    (2, 64, 112, 17, 23, 2, False),
+    (2, 128, 128, 33, 31, 2, True),
+    (2, 128, 64, 33, 31, 3, False),
+    (3, 256, 128, 29, 23, 2, False),
+    (2, 256, 256, 31, 33, 2, True),
+    (1, 256, 64, 40, 40, 2, False),
+    (1, 512, 256, 20, 21, 2, False),
+    (1, 512, 48, 9, 9, 2, True),
+    (1, 1024, 80, 7, 9, 2, False),
 ]
 
 
