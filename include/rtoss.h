@@ -12,7 +12,8 @@
  *                                                         (Section II.B cost model)
  *
  * plus the host-side dictionary generator rtoss_pattern_dict (Section IV.B, Eq. 1 and the
- * adjacency criterion).
+ * adjacency criterion) and the usage-based dictionary reduction of the same section
+ * (rtoss_pattern_histogram on the device, rtoss_reduce_dict on the host).
  *
  * Conventions shared by every call
  *   - Pointers named *_dev are device (HBM) pointers, pointers named *_host are host
@@ -110,6 +111,40 @@ rtoss_status rtoss_pattern_dict(int k, rtoss_rule rule, uint16_t* masks_host, in
 rtoss_status rtoss_select_patterns(const void* w_dev, rtoss_dtype dt, int64_t n_elems,
                                    const uint16_t* masks_host, int P,
                                    uint8_t* idx_dev, void* hip_stream);
+
+/*
+ * Section IV.B, second narrowing criterion (keep the patterns that are used most when
+ * the selection runs over random kernels), part 1: how often each pattern was selected.
+ *     hist_dev[p] += #{ g < G : idx_dev[g] == p }      for p < P
+ *
+ *   idx_dev   G pattern indices from rtoss_select_patterns (device); values >= P are ignored
+ *   hist_dev  P counters of type uint32 (device), 4-byte aligned.  The call ADDS to them, so
+ *             that several tensors can be accumulated; the caller clears them before the
+ *             first call.  Counts are integers: the result does not depend on the order in
+ *             which the adds happen.
+ * Errors: RTOSS_EINVAL (NULL, G < 0, P outside 1..255, misaligned hist_dev).
+ */
+rtoss_status rtoss_pattern_histogram(const uint8_t* idx_dev, int64_t G, int P,
+                                     uint32_t* hist_dev, void* hip_stream);
+
+/*
+ * Section IV.B, second narrowing criterion, part 2.  Host only, no GPU needed.  Keeps the M
+ * most used patterns of a dictionary: patterns are ranked by count, higher first, equal
+ * counts by lower index; the M best are written to out_masks_host in their ORIGINAL
+ * relative order, so that ties in a later selection over the reduced dictionary resolve
+ * towards the same pattern as before.
+ *
+ *   masks_host      P masks (as for rtoss_select_patterns)
+ *   hist_host       P counts (host copy of what rtoss_pattern_histogram accumulated)
+ *   M               1..P
+ *   out_masks_host  out: M masks
+ *   kept_host       out, may be NULL: kept_host[i] = index in masks_host of out_masks_host[i]
+ * How many random kernels to draw, and the number 21 the paper arrives at for its mixed
+ * 2- and 3-entry dictionary, are not recoverable from the paper: M is the caller's choice.
+ * Errors: RTOSS_EINVAL (NULL, bad dictionary, M outside 1..P).
+ */
+rtoss_status rtoss_reduce_dict(const uint16_t* masks_host, int P, const uint32_t* hist_host,
+                               int M, uint16_t* out_masks_host, uint8_t* kept_host);
 
 /* One convolution layer's weight tensor: [Co][Ci][ksize][ksize] contiguous, ksize 1 or 3,
  * k = number of survivors per group of 9 (the popcount of the dictionary's masks). */

@@ -13,8 +13,10 @@ from .oracle import (  # noqa: F401
     conv2d,
     conv2d_live3x3,
     conv2d_points,
+    histogram,
     mask,
     pattern_dict,
+    reduce_dict,
     select,
     threads,
 )

@@ -160,3 +160,26 @@ def conv2d_live3x3(x, w, masks, idx, stride=1, relu=False):
     _load().rtoss_oracle_conv2d_live3x3(xp, wp, mp, ip, y.ctypes.data_as(ctypes.POINTER(ctypes.c_double)), N, Ci, H,
                                         W, Co, int(stride), int(bool(relu)))
     return y
+
+
+def histogram(idx, P):
+    """Section IV.B, second narrowing criterion: how often each of the P patterns was selected.
+    Plain count; indices >= P are ignored."""
+    idx = np.asarray(idx).reshape(-1).astype(np.int64)
+    counts = np.zeros(P, dtype=np.int64)
+    for p in range(P):
+        counts[p] = int(np.count_nonzero(idx == p))
+    return counts
+
+
+def reduce_dict(masks, counts, M):
+    """Section IV.B, second narrowing criterion: the M most used patterns.  Ranking: higher count first,
+    lower index first among equal counts; the kept patterns stay in their original order.
+    Returns (masks[kept], kept)."""
+    masks = np.asarray(masks)
+    counts = np.asarray(counts)
+    assert 1 <= M <= len(masks) == len(counts)
+    ranked = sorted(range(len(masks)), key=lambda p: (-int(counts[p]), p))
+    kept = np.array(sorted(ranked[:M]), dtype=np.int64)
+    return masks[kept], kept
+

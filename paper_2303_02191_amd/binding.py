@@ -36,8 +36,8 @@ class CDesc(ctypes.Structure):
                 ("fuse_relu", ctypes.c_int)]
 
 
-EXPORTS = ["rtoss_pattern_dict", "rtoss_select_patterns", "rtoss_pack_size", "rtoss_pack", "rtoss_conv2d_pattern",
-           "rtoss_last_error"]
+EXPORTS = ["rtoss_pattern_dict", "rtoss_select_patterns", "rtoss_pattern_histogram", "rtoss_reduce_dict",
+           "rtoss_pack_size", "rtoss_pack", "rtoss_conv2d_pattern", "rtoss_last_error"]
 
 
 def lib():
@@ -60,6 +60,10 @@ def lib():
         L.rtoss_pattern_dict.argtypes = [i, i, u16p, i, ctypes.POINTER(i)]
         L.rtoss_select_patterns.restype = i
         L.rtoss_select_patterns.argtypes = [vp, i, i64, u16p, i, vp, vp]
+        L.rtoss_pattern_histogram.restype = i
+        L.rtoss_pattern_histogram.argtypes = [vp, i64, i, vp, vp]
+        L.rtoss_reduce_dict.restype = i
+        L.rtoss_reduce_dict.argtypes = [u16p, i, ctypes.POINTER(ctypes.c_uint32), i, u16p, ctypes.POINTER(ctypes.c_uint8)]
         L.rtoss_pack_size.restype = i
         L.rtoss_pack_size.argtypes = [ctypes.POINTER(WDesc), u16p, i, szp, szp]
         L.rtoss_pack.restype = i
@@ -99,6 +103,23 @@ def rtoss_pattern_dict(k, rule=RULE_CONNECTED4):
 def rtoss_select_patterns(w_ptr, dt, n_elems, masks, idx_ptr, stream=0):
     mp, P, _keep = _masks_arg(masks)
     _check(lib().rtoss_select_patterns(w_ptr, int(dt), int(n_elems), mp, P, idx_ptr, stream))
+
+
+def rtoss_pattern_histogram(idx_ptr, G, P, hist_ptr, stream=0):
+    _check(lib().rtoss_pattern_histogram(idx_ptr, int(G), int(P), hist_ptr, stream))
+
+
+def rtoss_reduce_dict(masks, hist, M):
+    """Host only: the M most used patterns in dictionary order, and their original indices."""
+    mp, P, _keep = _masks_arg(masks)
+    h = None if hist is None else np.ascontiguousarray(hist, dtype=np.uint32)
+    n = max(int(M), 1) if M is not None else 1
+    out = np.zeros(n, dtype=np.uint16)
+    kept = np.zeros(n, dtype=np.uint8)
+    _check(lib().rtoss_reduce_dict(mp, P, None if h is None else h.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)), int(M),
+                                   out.ctypes.data_as(ctypes.POINTER(ctypes.c_uint16)),
+                                   kept.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8))))
+    return out, kept
 
 
 def rtoss_pack_size(wdesc, masks):

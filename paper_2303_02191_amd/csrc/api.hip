@@ -190,6 +190,36 @@ rtoss_status rtoss_select_patterns(const void* w_dev, rtoss_dtype dt, int64_t n_
     return launch_select(w_dev, dt, G, dict, idx_dev, (hipStream_t)hip_stream);
 }
 
+rtoss_status rtoss_pattern_histogram(const uint8_t* idx_dev, int64_t G, int P, uint32_t* hist_dev, void* hip_stream)
+{
+    if (G < 0) return fail(RTOSS_EINVAL, "G=%lld is negative", (long long)G);
+    if (P < 1 || P > kMaxPatterns) return fail(RTOSS_EINVAL, "P=%d outside 1..%d", P, kMaxPatterns);
+    if (!hist_dev) return fail(RTOSS_EINVAL, "hist_dev is NULL");
+    if (misaligned(hist_dev, 4)) return fail(RTOSS_EINVAL, "hist_dev is not 4-byte aligned");
+    if (G == 0) return RTOSS_OK;
+    if (!idx_dev) return fail(RTOSS_EINVAL, "idx_dev is NULL");
+    return launch_histogram(idx_dev, G, P, hist_dev, (hipStream_t)hip_stream);
+}
+
+rtoss_status rtoss_reduce_dict(const uint16_t* masks_host, int P, const uint32_t* hist_host, int M, uint16_t* out_masks_host,
+                               uint8_t* kept_host)
+{
+    Dict dict;
+    if (rtoss_status st = load_dict(masks_host, P, &dict)) return st;
+    if (!hist_host || !out_masks_host) return fail(RTOSS_EINVAL, "hist_host or out_masks_host is NULL");
+    if (M < 1 || M > P) return fail(RTOSS_EINVAL, "M=%d outside 1..P=%d", M, P);
+    // rank: count descending, index ascending on equal counts; then restore dictionary order
+    int order[256];
+    for (int p = 0; p < P; ++p) order[p] = p;
+    std::stable_sort(order, order + P, [&](int a, int b) { return hist_host[a] > hist_host[b]; });
+    std::sort(order, order + M);
+    for (int i = 0; i < M; ++i) {
+        out_masks_host[i] = dict.mask[order[i]];
+        if (kept_host) kept_host[i] = (uint8_t)order[i];
+    }
+    return RTOSS_OK;
+}
+
 rtoss_status rtoss_pack_size(const rtoss_wdesc* desc, const uint16_t* masks_host, int P, size_t* packed_bytes,
                              size_t* workspace_bytes)
 {

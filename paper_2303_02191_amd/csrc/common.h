@@ -58,6 +58,9 @@ rtoss_status check_hip(hipError_t e, const char* what);
 // ----- launchers (one per kernel family; defined next to the kernels) -----
 rtoss_status launch_select(const void* w, rtoss_dtype dt, int64_t G, const Dict& dict, uint8_t* idx, hipStream_t s);
 
+// counts of each pattern index (select.hip)
+rtoss_status launch_histogram(const uint8_t* idx, int64_t G, int P, uint32_t* hist, hipStream_t s);
+
 rtoss_status launch_pack_live(const rtoss_wdesc& d, const void* w, const uint8_t* idx, const Dict& dict,
                               void* live_values, uint8_t* live_idx, int64_t G, hipStream_t s);
 

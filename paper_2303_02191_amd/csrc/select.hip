@@ -8,6 +8,8 @@
 // merged with two cross-lane exchanges.  Sums run over the live taps in ascending tap
 // order in fp64, comparisons are strict, and the merge prefers the lower index on equal
 // scores, so the result equals a serial ascending scan bit for bit.
+#include <algorithm>
+
 #include "common.h"
 #include "dtypes.h"
 
@@ -74,6 +76,42 @@ rtoss_status launch_select(const void* w, rtoss_dtype dt, int64_t G, const Dict&
     case RTOSS_BF16: select_kernel<bf16_t><<<grid, block, 0, s>>>((const bf16_t*)w, G, dict, idx); break;
     }
     return check_hip(hipGetLastError(), "select launch");
+}
+
+// Usage count of every pattern (Section IV.B, second narrowing criterion): one byte per group in,
+// P counters out.  Each workgroup counts a slice in LDS (integer atomics; the result is independent
+// of their order) and adds its non-zero bins to the global counters.
+constexpr int kHistBytesPerThread = 16;
+constexpr int kHistBlock = 256;
+constexpr int kHistChunk = kHistBlock * kHistBytesPerThread;  // indices per workgroup and pass
+
+__global__ __launch_bounds__(kHistBlock) void histogram_kernel(const uint8_t* __restrict__ idx, int64_t G, int P,
+                                                               uint32_t* __restrict__ hist)
+{
+    __shared__ uint32_t bins[256];
+    bins[threadIdx.x] = 0;
+    __syncthreads();
+    for (int64_t base = (int64_t)blockIdx.x * kHistChunk; base < G; base += (int64_t)gridDim.x * kHistChunk) {
+        const int64_t g0 = base + (int64_t)threadIdx.x * kHistBytesPerThread;
+        // the index tensor comes from an allocator, but its start need not be 16-byte aligned: byte loads
+        for (int i = 0; i < kHistBytesPerThread; ++i)
+            if (g0 + i < G) {
+                const int p = idx[g0 + i];
+                if (p < P) atomicAdd(&bins[p], 1u);
+            }
+    }
+    __syncthreads();
+    const uint32_t c = bins[threadIdx.x];
+    if ((int)threadIdx.x < P && c != 0) atomicAdd(&hist[threadIdx.x], c);
+}
+
+rtoss_status launch_histogram(const uint8_t* idx, int64_t G, int P, uint32_t* hist, hipStream_t s)
+{
+    if (G == 0) return RTOSS_OK;
+    const int64_t chunks = (G + kHistChunk - 1) / kHistChunk;
+    dim3 grid((unsigned)std::min<int64_t>(chunks, 2048)), block(kHistBlock);
+    histogram_kernel<<<grid, block, 0, s>>>(idx, G, P, hist);
+    return check_hip(hipGetLastError(), "histogram launch");
 }
 
 }  // namespace rtoss

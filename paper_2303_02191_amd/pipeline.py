@@ -38,6 +38,25 @@ def select_patterns(w, dt, masks):
     return idx[: w.numel() // 9]
 
 
+def pattern_histogram(idx, P, hist=None):
+    """Adds the usage counts of idx (uint8 cuda tensor) to hist (uint32 counts as an int32 cuda tensor [P])."""
+    assert idx.is_cuda and idx.dtype == torch.uint8 and idx.is_contiguous()
+    if hist is None:
+        hist = torch.zeros(P, dtype=torch.int32, device=idx.device)
+    B.rtoss_pattern_histogram(idx.data_ptr(), idx.numel(), P, hist.data_ptr(), _stream())
+    return hist
+
+
+def reduce_dictionary(masks, w_random, dt, M):
+    """Section IV.B, second criterion: select over the random kernels in w_random (cuda tensor, numel % 9 == 0),
+    count the winners and keep the M most used patterns.  Returns (reduced masks, kept indices, counts)."""
+    idx = select_patterns(w_random, dt, masks)
+    hist = pattern_histogram(idx, len(masks))
+    counts = hist.cpu().numpy().astype("uint32")
+    out, kept = B.rtoss_reduce_dict(masks, counts, M)
+    return out, kept, counts
+
+
 class PackedLayer:
     """One layer's packed blob plus the descriptors the convolution call needs."""
 

@@ -200,5 +200,13 @@ def draw_w(rng, cfg: Config, L: Layer):
     return s, to_f64(s, cfg.dtype)
 
 
+def draw_random_kernels(seed, n_kernels, dtype):
+    """n_kernels 3x3 kernels with iid U[-1, 1] weights (the random kernels of Section IV.B's usage
+    count), rounded once to dtype: (storage array [n, 9], exact float64 values)."""
+    a = np.random.default_rng(seed).uniform(-1.0, 1.0, (n_kernels, 9))
+    s = round_to_dtype(a, dtype)
+    return s, to_f64(s, dtype)
+
+
 def make_rng(cfg: Config):
     return np.random.default_rng(cfg.seed)

@@ -36,11 +36,12 @@ def decode_live_section(blob, Co, Ci, ksize, k, dt, masks):
 class GpuLayer:
     """select -> pack -> conv for one layer, on storage arrays in the logical layouts."""
 
-    def __init__(self, w_store, dt, masks, k):
+    def __init__(self, w_store, dt, masks, k, idx=None):
+        """idx: pattern indices to prune with (a cuda uint8 tensor, e.g. another layer's) instead of selecting."""
         Co, Ci, ks, _ = w_store.shape
         self.dt, self.masks, self.k = dt, masks, k
         self.w = pl.to_device(np.ascontiguousarray(w_store), dt)
-        self.idx = pl.select_patterns(self.w, dt, masks)
+        self.idx = pl.select_patterns(self.w, dt, masks) if idx is None else idx
         self.layer = pl.PackedLayer(Co, Ci, ks, k, dt, masks).pack(self.w, self.idx)
 
     def idx_host(self):

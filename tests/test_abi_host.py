@@ -112,3 +112,36 @@ def test_conv_argument_errors():
     assert _status(call, d, cd(), B.rtoss_pattern_dict(2), fake_p, fake_x, fake_y) == B.EINVAL  # k mismatch
     d1 = B.WDesc(64, 32, 1, 3, B.F16)
     assert _status(call, d1, cd(stride=2, pad=0), masks, fake_p, fake_x, fake_y) == B.ESHAPE
+
+
+def test_reduce_dict_matches_oracle_and_rejects_bad_arguments():
+    # host-only entry point: ranking by count, ties to the lower index, original order kept
+    rng = np.random.default_rng(5)
+    for k in (2, 3, 4):
+        masks = B.rtoss_pattern_dict(k)
+        for trial in range(5):
+            counts = rng.integers(0, 6, len(masks)).astype(np.uint32)  # small range: many ties
+            for M in (1, 2, len(masks) // 2, len(masks)):
+                out, kept = B.rtoss_reduce_dict(masks, counts, M)
+                want, want_kept = oracle.reduce_dict(masks, counts, M)
+                assert out.tolist() == want.tolist() and kept.tolist() == want_kept.tolist()
+    masks = B.rtoss_pattern_dict(2)
+    counts = np.zeros(len(masks), dtype=np.uint32)
+    for bad_M in (0, -1, len(masks) + 1):
+        with pytest.raises(B.RtossError) as e:
+            B.rtoss_reduce_dict(masks, counts, bad_M)
+        assert e.value.status == B.EINVAL
+    with pytest.raises(B.RtossError):
+        B.rtoss_reduce_dict(masks, None, 3)
+    with pytest.raises(B.RtossError):
+        B.rtoss_reduce_dict(None, counts, 3)
+
+
+def test_histogram_argument_errors():
+    # validated on the host before any GPU call
+    for args in [(0, 10, 12, 0), (256, -1, 12, 256), (256, 10, 0, 256), (256, 10, 256, 256), (256, 10, 12, 258)]:
+        with pytest.raises(B.RtossError) as e:
+            B.rtoss_pattern_histogram(*args)
+        assert e.value.status == B.EINVAL
+    B.rtoss_pattern_histogram(0, 0, 12, 256)  # nothing to count: no launch, no error
+

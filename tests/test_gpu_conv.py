@@ -11,7 +11,7 @@ import oracle
 from paper_2303_02191_amd import binding as B
 from paper_2303_02191_amd import workloads as wl
 
-from gpu_util import GpuLayer
+from gpu_util import GpuLayer, decode_live_section
 
 pytestmark = pytest.mark.gpu
 
@@ -169,6 +169,28 @@ STEM = [
 def test_conv3x3_stem_shapes(dt, case):
     N, Ci, Co, H, W, stride, k, relu = case
     run_case(dt, N, Ci, Co, H, W, 3, stride, k, relu, seed=hash(case) % 10000 + dt, w_std=0.1)
+
+
+@pytest.mark.parametrize("ks,Ci,Co,H", [(3, 64, 32, 12), (1, 64, 48, 9), (3, 8, 8, 7)])
+def test_child_layer_reuses_parent_patterns(ks, Ci, Co, H):
+    # Section IV.A / IV.C: layers of one group share the kernel patterns of the group's parent layer.
+    # The child is pruned and packed with the parent's index tensor (no selection of its own) and its
+    # convolution is compared with the oracle's masked convolution under the same indices.
+    dt, k = wl.F16, 3
+    masks = B.rtoss_pattern_dict(k)
+    rng = np.random.default_rng(900 + ks + Ci)
+    w_parent = wl.round_to_dtype(rng.standard_normal((Co, Ci, ks, ks)) * 0.05, dt)
+    w_child = wl.round_to_dtype(rng.standard_normal((Co, Ci, ks, ks)) * 0.05, dt)
+    xs = wl.round_to_dtype(rng.standard_normal((2, Ci, H, H)), dt)
+    parent = GpuLayer(w_parent, dt, masks, k)
+    child = GpuLayer(w_child, dt, masks, k, idx=parent.idx)
+    idx = parent.idx_host()
+    assert np.array_equal(idx, oracle.select(wl.to_f64(w_parent, dt), masks))
+    pruned_child = oracle.mask(wl.to_f64(w_child, dt), masks, idx)
+    dec, dec_idx = decode_live_section(child.blob_host(), Co, Ci, ks, k, dt, masks)
+    assert np.array_equal(dec_idx, idx)
+    assert np.array_equal(wl.to_f64(dec, dt), pruned_child)
+    check(child.conv_nchw(xs, out_dt=wl.F32), oracle.conv2d(wl.to_f64(xs, dt), pruned_child), dt)
 
 
 def test_conv_all_ones_pattern_is_dense():

@@ -90,3 +90,34 @@ def test_select_full_configs(cfg_i):
     if stores3:  # all 3x3 kernels of the configuration in one call
         s, v = np.concatenate(stores3), np.concatenate(vals3)
         assert np.array_equal(gpu_select(s, cfg.dtype, masks), oracle.select(v, masks))
+
+
+@pytest.mark.parametrize("n", [1, 4095, 4096, 4097, 300001])
+@pytest.mark.parametrize("P", [1, 12, 22, 255])
+def test_histogram_matches_oracle(n, P):
+    import torch
+    from paper_2303_02191_amd import pipeline as pl
+    idx = np.random.default_rng(n + P).integers(0, 256, n).astype(np.uint8)  # includes values >= P
+    d = torch.from_numpy(idx).cuda()
+    h = pl.pattern_histogram(d, P)
+    h = pl.pattern_histogram(d[: n // 2].contiguous(), P, h)  # the call accumulates
+    want = oracle.histogram(idx, P) + oracle.histogram(idx[: n // 2], P)
+    assert h.cpu().numpy().tolist() == want.tolist()
+
+
+@pytest.mark.parametrize("dt", [wl.F32, wl.F16])
+@pytest.mark.parametrize("k,M", [(2, 5), (3, 11)])
+def test_dictionary_reduction_matches_oracle(dt, k, M):
+    # Section IV.B second criterion end to end: random U[-1,1] kernels -> select -> usage count -> top M
+    from paper_2303_02191_amd import pipeline as pl
+    masks = B.rtoss_pattern_dict(k)
+    store, vals = wl.draw_random_kernels(77 + k, 50000, dt)
+    red, kept, counts = pl.reduce_dictionary(masks, pl.to_device(store, dt), dt, M)
+    want_counts = oracle.histogram(oracle.select(vals, masks), len(masks))
+    assert counts.tolist() == want_counts.tolist()
+    want_red, want_kept = oracle.reduce_dict(masks, want_counts, M)
+    assert red.tolist() == want_red.tolist() and kept.tolist() == want_kept.tolist()
+    # the reduced dictionary is a valid dictionary for the rest of the path
+    got = gpu_select(store, dt, red)
+    assert np.array_equal(got, oracle.select(vals, red))
+
