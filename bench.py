@@ -66,11 +66,16 @@ def parse():
     ap.add_argument("--no-dense", action="store_true", help="skip the dense torch conv2d comparator")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="target wall time of the oracle sample")
     ap.add_argument("--graph", choices=["auto", "on", "off"], default="auto",
-                    help="replay the step from three captured HIP graphs (select, pack, conv); auto: when the "
-                         "workload has more than 8 layers, where eager launches are bound by host time")
+                    help="replay the step from three captured HIP graphs (select, pack, conv) instead of enqueueing "
+                         "every call from Python, whose host time per launch exceeds most of these kernels; "
+                         "auto = on")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 256 MiB device copy (a reference dispatch of known traffic for "
                          "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
+    ap.add_argument("--k", type=int, default=0,
+                    help="entries kept per kernel instead of the workload's own (the axis of the sensitivity study, "
+                         "Table 3).  2- and 3-entry connected patterns run on the sparse matrix instruction; 4 and "
+                         "more take the vector-ALU kernel for 3x3 layers")
     ap.add_argument("--per-layer", action="store_true", help="after the timed region, time every layer's conv alone (stderr)")
     return ap.parse_args()
 
@@ -95,6 +100,9 @@ def main():
     torch.cuda.set_device(dev)
 
     cfg = wl.get_config(WORKLOADS[args.workload])
+    if args.k:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, k=args.k, name="%s_k%d" % (cfg.name, args.k))
     masks = B.rtoss_pattern_dict(cfg.k)
     tdt = pl.TORCH_DTYPE[cfg.dtype]
     eb = wl.ELEM_BYTES[cfg.dtype]
@@ -157,7 +165,7 @@ def main():
             lay.conv(x, stride=L.stride, relu=L.relu, y=y)
 
     phases = [do_select, do_pack, do_conv]
-    use_graph = args.graph == "on" or (args.graph == "auto" and len(cfg.layers) > 8)
+    use_graph = args.graph != "off"
     for f in phases:  # first launches also set kernel attributes: must happen outside capture
         f()
     torch.cuda.synchronize()
@@ -222,7 +230,7 @@ def main():
         achieved = nz_flops / n_conv / conv_launch_s / 1e12
         roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_MFMA_16BIT_TFLOPS, "unit": "TFLOP/s",
                     "frac": achieved / PEAK_MFMA_16BIT_TFLOPS, "traffic": None}
-    if args.workload == "cfg4":
+    if args.workload == "cfg4" and not args.k:
         roofline["traffic"] = measured_traffic("conv3x3_sparse_cfg4_hbm_traffic.txt")
     roofline["kernel"] = "rtoss_conv2d_pattern"
     roofline["avg_launch_us"] = conv_launch_s * 1e6
@@ -266,6 +274,32 @@ def main():
             dense_ms = None
             print("dense comparator failed: %r" % (e,), file=sys.stderr)
 
+    # ---- dense comparator 2: this library's own kernels in dense mode (the all-ones pattern keeps every
+    # weight; the matrix-core kernels then run with nothing to skip) on the same tensors ----
+    dense_own_ms = None
+    if not args.no_dense and cfg.dtype != wl.F32:
+        masks9 = B.rtoss_pattern_dict(9)
+        dense_own_ms = 0.0
+        for L, w, x, y in zip(cfg.layers, w_dev, xs, ys):
+            # (a flattened 1x1 tensor's tail of < 9 weights is pruned by definition; the rest is dense)
+            idx9 = torch.zeros(max(L.n_weights // 9, 1), dtype=torch.uint8, device=dev)
+            lay9 = pl.PackedLayer(L.Co, L.Ci, L.ksize, 9, cfg.dtype, masks9).pack(w, idx9)
+            yd = torch.empty_like(y)
+            for _ in range(3):
+                lay9.conv(x, stride=L.stride, relu=L.relu, y=yd)
+            torch.cuda.synchronize()
+            a, b = ev(), ev()
+            a.record()
+            for _ in range(10):
+                lay9.conv(x, stride=L.stride, relu=L.relu, y=yd)
+            b.record()
+            torch.cuda.synchronize()
+            dense_own_ms += a.elapsed_time(b) / 10
+            if args.per_layer:
+                print("dense mode, own kernel: Ci %4d Co %4d H %3d ks %d s %d  %8.1f us" %
+                      (L.Ci, L.Co, L.H, L.ksize, L.stride, a.elapsed_time(b) / 10 * 1e3), file=sys.stderr)
+            del lay9, yd
+
     # ---- CPU baseline: the oracle on a bounded sample: whole (layer, batch item) convolutions, taken in
     # order until the time budget is used up ----
     cpu = None
@@ -304,7 +338,7 @@ def main():
                    "patterns": int(masks.size), "nonzero_gflop_per_step": nz_flops / 1e9,
                    "dense_gflop_per_step": 2.0 * cfg.dense_macs() / 1e9},
         "breakdown_ms": {"select": sel_ms, "pack": pack_ms, "conv": conv_ms,
-                         "dense_torch_conv2d": dense_ms},
+                         "dense_torch_conv2d": dense_ms, "dense_own_kernels": dense_own_ms},
         "roofline": roofline,
         "cpu_baseline": cpu,
     }

@@ -134,6 +134,11 @@ rtoss_status blob_geometry(const rtoss_wdesc* d, const Dict& dict, BlobGeometry*
         g->mat_off = end;
         g->mat_bytes = stem3x3_section_bytes(*d);
         end = align_up(end + g->mat_bytes, 256);
+    } else if (dense3x3_shape_ok(*d)) {
+        g->format = kFormatDense3x3;
+        g->mat_off = end;
+        g->mat_bytes = dense3x3_section_bytes(*d);
+        end = align_up(end + g->mat_bytes, 256);
     } else if (stream1x1_shape_ok(*d)) {
         g->format = kFormatDenseStream;
         g->mat_off = end;
@@ -259,6 +264,7 @@ rtoss_status rtoss_pack(const rtoss_wdesc* desc, const void* w_dev, const uint8_
     uint8_t* live_idx = (uint8_t*)(blob + g.idx_off);
     // one launch per layer: the fragment packers also write the public section in their first blocks
     if (g.format == kFormatSparse24) return launch_pack_sparse3x3(*desc, w_dev, idx_dev, dict, blob + g.mat_off, live, live_idx, s);
+    if (g.format == kFormatDense3x3) return launch_pack_dense3x3(*desc, w_dev, idx_dev, dict, blob + g.mat_off, live, live_idx, s);
     if (g.format == kFormatDenseStream) return launch_pack_stream1x1(*desc, w_dev, idx_dev, dict, blob + g.mat_off, live, live_idx, s);
     if (g.format == kFormatDense) return launch_pack_dense1x1(*desc, w_dev, idx_dev, dict, blob + g.mat_off, live, live_idx, s);
     if (g.format == kFormatStem) return launch_pack_stem3x3(*desc, w_dev, idx_dev, dict, blob + g.mat_off, live, live_idx, s);
@@ -300,6 +306,8 @@ rtoss_status rtoss_conv2d_pattern(const rtoss_wdesc* desc, const rtoss_cdesc* c,
         return launch_conv3x3_sparse(*desc, *c, blob + g.mat_off, x_dev, y_dev, (hipStream_t)hip_stream);
     if (g.format == kFormatStem)
         return launch_conv3x3_stem(*desc, *c, blob + g.mat_off, x_dev, y_dev, (hipStream_t)hip_stream);
+    if (g.format == kFormatDense3x3)
+        return launch_conv3x3_dense(*desc, *c, blob + g.mat_off, x_dev, y_dev, (hipStream_t)hip_stream);
     if (g.format == kFormatDenseStream)
         return launch_conv1x1_stream(*desc, *c, blob + g.mat_off, x_dev, y_dev, (hipStream_t)hip_stream);
     if (g.format == kFormatDense)

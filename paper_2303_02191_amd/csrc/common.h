@@ -34,7 +34,8 @@ enum MatrixFormat {
     kFormatDense = 1,    // 1x1: zero-filled matrix-core fragments
     kFormatSparse24 = 2, // 3x3: 2-of-4 compressed fragments + indices
     kFormatStem = 3,     // 3x3 with <= 3 input channels: one zero-filled fragment per 16 output channels
-    kFormatDenseStream = 4  // 1x1 with Ci = 32 * 2^n <= 1024: zero-filled fragments in the streaming kernel's order
+    kFormatDenseStream = 4,  // 1x1 with Ci = 32 * 2^n <= 1024: zero-filled fragments in the streaming kernel's order
+    kFormatDense3x3 = 5      // 3x3 whose dictionary has no 2-of-4 shape: zero-filled fragments, one per tap
 };
 
 struct BlobGeometry {
@@ -75,6 +76,14 @@ rtoss_status launch_pack_sparse3x3(const rtoss_wdesc& d, const void* w, const ui
                                    void* section, void* live_values, uint8_t* live_idx, hipStream_t s);
 rtoss_status launch_conv3x3_sparse(const rtoss_wdesc& d, const rtoss_cdesc& c, const void* section, const void* x,
                                    void* y, hipStream_t s);
+
+// 3x3 convolution in dense mode on the matrix cores (conv3x3_dense.hip)
+bool dense3x3_shape_ok(const rtoss_wdesc& d);
+size_t dense3x3_section_bytes(const rtoss_wdesc& d);
+rtoss_status launch_pack_dense3x3(const rtoss_wdesc& d, const void* w, const uint8_t* idx, const Dict& dict, void* section,
+                                  void* live_values, uint8_t* live_idx, hipStream_t s);
+rtoss_status launch_conv3x3_dense(const rtoss_wdesc& d, const rtoss_cdesc& c, const void* section, const void* x, void* y,
+                                  hipStream_t s);
 
 // 1x1 convolution on the dense matrix instruction (conv1x1_mma.hip)
 bool dense1x1_shape_ok(const rtoss_wdesc& d);

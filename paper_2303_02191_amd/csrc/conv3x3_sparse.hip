@@ -37,6 +37,7 @@
 #include "dtypes.h"
 #include "mma.h"
 #include "pack_live.h"
+#include "tile3x3.h"
 
 namespace rtoss {
 
@@ -47,7 +48,6 @@ namespace {
 //   then 2 index words per lane: [corner][lane], [edge][lane]; low half = step 0, high = step 1
 constexpr int kFragBytes = 1024;
 constexpr int kTileBytes = 5 * kFragBytes + 2 * 64 * 4;  // 5632
-constexpr int kXPosBytes = 80;                          // 32 channels x 2 B + 16 B pad
 constexpr bool kDirectEpilogue = false;                 // store D fragments directly (false: transpose through LDS)
 
 __device__ __forceinline__ int tap_of_slot(int group, int f)
@@ -166,29 +166,27 @@ template <int TN> struct JobSchedule {
     }
 };
 
-template <int S, int RT, int CT> struct Geom {
-    static constexpr int TH = 4 * RT, TW = 4 * CT;                 // output tile
-    static constexpr int IH = (TH - 1) * S + 3, IW = (TW - 1) * S + 3;  // input tile with halo
-    static constexpr int LW = ((IW + 3) / 8) * 8 + 4;              // row pitch in positions, == 4 (mod 8), >= IW
-    static constexpr int x_bytes = IH * LW * kXPosBytes;
-    static constexpr int x_chunks = IH * IW * 4;                   // 16-byte chunks to fetch per stage
-};
-
-// Single-buffered variant (register-staged prefetch, two barriers per stage).  Used for stride 2,
-// whose activation tile is too large to keep twice in LDS.
+// Single-buffered variant: one LDS buffer, two barriers per stage, plain loop nest scheduled by the
+// compiler.  It needs half the LDS of the pipelined kernel below and few registers, so several
+// workgroups share a compute unit and hide each other's copy latency and epilogue.  Used for stride 2
+// (whose activation tile is too large to keep twice in LDS) and for layers too small for the
+// pipelined kernel's 128-channel, 8-stage appetite: TM = 4 covers 64 output channels per workgroup.
 template <typename T, typename TO, int S, int TM, int TN, int RT, int CT>
-__global__ __launch_bounds__(256, 1) void conv3x3_sparse_sb_kernel(const T* __restrict__ x, TO* __restrict__ y,
-                                                                const char* __restrict__ wfrag, int H, int W, int Ci,
+__global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restrict__ x, TO* __restrict__ y,
+                                                                const char* __restrict__ wfrag,
+                                                                const char* __restrict__ zeros, int H, int W, int Ci,
                                                                 int Co, int Ho, int Wo, int m_tiles_total,
                                                                 int tiles_c, int relu)
 {
     using G = Geom<S, RT, CT>;
     static_assert(RT * CT == 4 * TN, "four waves share the position blocks of a workgroup");
     constexpr int A_BYTES = TM * kTileBytes;
-    constexpr int A_CHUNKS = A_BYTES / 16;
-    constexpr int A_PER_THREAD = (A_CHUNKS + 255) / 256;
-    constexpr int X_PER_THREAD = (G::x_chunks + 255) / 256;
-    extern __shared__ __attribute__((aligned(16))) char smem[];
+    constexpr int A_WAVE_COPIES = A_BYTES / 1024;            // 64 lanes x 16 B per copy instruction
+    constexpr int A_PER_WAVE = (A_WAVE_COPIES + 3) / 4;
+    constexpr int X_CHUNKS = G::x_bytes / 16;                // including the pad chunk of every position
+    constexpr int X_PER_WAVE = ((X_CHUNKS + 63) / 64 + 3) / 4;
+    static_assert(A_BYTES % 1024 == 0, "weight fragments are whole copy instructions");
+    extern __shared__ __attribute__((aligned(16))) char smem[];  // [weights][activations, rounded up to whole copies]
     char* lds_a = smem;
     char* lds_x = smem + A_BYTES;
 
@@ -202,42 +200,20 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_sb_kernel(const T* __re
     const int ih0 = oh0 * S - 1, iw0 = ow0 * S - 1;
     const int stages = Ci / 32;
 
-    // ---- prefetch bookkeeping: which 16-byte chunks this lane moves every stage ----
-    const char* a_src = wfrag + (int64_t)mt0 * kTileBytes + tid * 16;  // + stage * m_tiles_total * kTileBytes
-    const int64_t a_stage_stride = (int64_t)m_tiles_total * kTileBytes;
-    int x_lds_off[X_PER_THREAD];
-    int64_t x_src_off[X_PER_THREAD];  // element offset into x for stage 0, or -1 for a zero chunk / unused slot
+    // Copy sources of stage 0.  Every lane copies 16 bytes in every copy instruction; a lane whose LDS
+    // slot is zero padding of the tile (or a pad chunk) reads the block of zeros behind the fragments.
+    const char* x_ptr[X_PER_WAVE];
 #pragma unroll
-    for (int i = 0; i < X_PER_THREAD; ++i) {
-        const int item = tid + i * 256;
-        const int pos = item >> 2, qd = item & 3;
-        const int pr = pos / G::IW, pc = pos % G::IW;
-        x_lds_off[i] = item < G::x_chunks ? (pr * G::LW + pc) * kXPosBytes + qd * 16 : -1;
-        const int ih = ih0 + pr, iw = iw0 + pc;
-        const bool inside = item < G::x_chunks && ih >= 0 && ih < H && iw >= 0 && iw < W;
-        x_src_off[i] = inside ? (((int64_t)n_img * H + ih) * W + iw) * Ci + qd * 8 : -1;
+    for (int k = 0; k < X_PER_WAVE; ++k) {
+        const int c = (k * 4 + wave) * 64 + lane;
+        const int pos = c / 5, q = c % 5;
+        const int xr = pos / G::LW, xc = pos % G::LW;
+        const int ih = ih0 + xr, iw = iw0 + xc;
+        const bool inside = q < 4 && xr < G::IH && xc < G::IW && ih >= 0 && ih < H && iw >= 0 && iw < W;
+        x_ptr[k] = inside ? (const char*)x + ((((int64_t)n_img * H + ih) * W + iw) * Ci + q * 8) * 2 : zeros;
     }
-    u32x4 a_reg[A_PER_THREAD], x_reg[X_PER_THREAD];
-
-    auto fetch = [&](int stage) {
-#pragma unroll
-        for (int i = 0; i < A_PER_THREAD; ++i)
-            if (tid + i * 256 < A_CHUNKS) a_reg[i] = *(const u32x4*)(a_src + stage * a_stage_stride + i * 4096);
-#pragma unroll
-        for (int i = 0; i < X_PER_THREAD; ++i) {
-            u32x4 v = {0, 0, 0, 0};
-            if (x_src_off[i] >= 0) v = *(const u32x4*)(x + x_src_off[i] + stage * 32);
-            x_reg[i] = v;
-        }
-    };
-    auto park = [&]() {
-#pragma unroll
-        for (int i = 0; i < A_PER_THREAD; ++i)
-            if (tid + i * 256 < A_CHUNKS) *(u32x4*)(lds_a + tid * 16 + i * 4096) = a_reg[i];
-#pragma unroll
-        for (int i = 0; i < X_PER_THREAD; ++i)
-            if (x_lds_off[i] >= 0) *(u32x4*)(lds_x + x_lds_off[i]) = x_reg[i];
-    };
+    const char* a_src = wfrag + (int64_t)mt0 * kTileBytes + lane * 16;
+    const int64_t a_stage_stride = (int64_t)m_tiles_total * kTileBytes;
 
     // ---- per-lane read addresses of the B operand ----
     const int nn = lane & 15, qq = lane >> 4;
@@ -256,12 +232,16 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_sb_kernel(const T* __re
 #pragma unroll
         for (int j = 0; j < TN; ++j) acc[m][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    fetch(0);
     for (int stage = 0; stage < stages; ++stage) {
         __syncthreads();  // every wave is done reading the previous stage
-        park();
-        __syncthreads();
-        if (stage + 1 < stages) fetch(stage + 1);
+#pragma unroll
+        for (int k = 0; k < A_PER_WAVE; ++k)
+            if (k * 4 + wave < A_WAVE_COPIES)  // wave-uniform
+                copy16_to_lds(a_src + stage * a_stage_stride + (k * 4 + wave) * 1024, lds_a + (k * 4 + wave) * 1024);
+#pragma unroll
+        for (int k = 0; k < X_PER_WAVE; ++k) copy16_to_lds(x_ptr[k] + stage * 64, lds_x + (k * 4 + wave) * 1024);
+        __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's copies have landed in LDS
+        __syncthreads();                     // ... and everybody's
 
 #pragma unroll
         for (int group = 0; group < 2; ++group) {
@@ -782,7 +762,8 @@ rtoss_status launch_variant_sb(const rtoss_wdesc& d, const rtoss_cdesc& c, const
     const int tiles_r = (Ho + G::TH - 1) / G::TH, tiles_c = (Wo + G::TW - 1) / G::TW;
     const int m_tiles_total = padded_m_tiles(d.Co);  // pitch of the packed section
     const int co_blocks = ((d.Co + 15) / 16 + TM - 1) / TM;
-    const size_t smem = (size_t)TM * kTileBytes + G::x_bytes;
+    constexpr int x_copies_per_wave = ((G::x_bytes / 16 + 63) / 64 + 3) / 4;
+    const size_t smem = (size_t)TM * kTileBytes + (size_t)x_copies_per_wave * 4096;
     auto kern = conv3x3_sparse_sb_kernel<T, TO, S, TM, TN, RT, CT>;
     static bool attr_set = false;  // per instantiation
     if (!attr_set) {
@@ -793,8 +774,8 @@ rtoss_status launch_variant_sb(const rtoss_wdesc& d, const rtoss_cdesc& c, const
     }
     if (c.N > 65535 || co_blocks > 65535) return fail(RTOSS_ESHAPE, "conv: batch or channel count too large");
     dim3 grid((unsigned)(tiles_r * tiles_c), (unsigned)co_blocks, (unsigned)c.N), block(256);
-    kern<<<grid, block, smem, s>>>((const T*)x, (TO*)y, wfrag, c.H, c.W, d.Ci, d.Co, Ho, Wo, m_tiles_total, tiles_c,
-                                   c.fuse_relu);
+    kern<<<grid, block, smem, s>>>((const T*)x, (TO*)y, wfrag, wfrag + fragment_bytes(d), c.H, c.W, d.Ci, d.Co, Ho, Wo,
+                                   m_tiles_total, tiles_c, c.fuse_relu);
     return check_hip(hipGetLastError(), "conv3x3 sparse launch");
 }
 
@@ -804,7 +785,11 @@ rtoss_status launch_typed(const rtoss_wdesc& d, const rtoss_cdesc& c, const char
 {
     // The fragment section is padded to a multiple of 8 channel tiles, so any TM <= 8 may over-read rows
     // that hold zeros; outputs beyond Co are never stored.
+    // Layers with at most 64 output channels, or too few stages to amortise the pipelined kernel's
+    // prologue, take the single-buffered kernel with 64 channels per workgroup.
+    const bool small = d.Co <= 64 || d.Ci <= 64;
     if (c.stride == 1) {
+        if (small) return launch_variant_sb<T, TO, 1, 4, 4, 4, 4>(d, c, wfrag, x, y, s);
         // Two tile shapes: 16x16 positions, or 20 rows x 16 columns (5 position blocks per wave: better
         // reuse of the weight fragments, and for some images fewer rounds over the compute units or less
         // padding).  Cost model: rounds of the busiest workgroup x relative cost of a tile.
@@ -818,6 +803,7 @@ rtoss_status launch_typed(const rtoss_wdesc& d, const rtoss_cdesc& c, const char
         if (cost5 < cost4 && d.Ci >= 128) return launch_variant<T, TO, 1, 8, 5, 5, 4>(d, c, wfrag, x, y, s);
         return launch_variant<T, TO, 1, 8, 4, 4, 4>(d, c, wfrag, x, y, s);
     }
+    if (d.Co <= 64) return launch_variant_sb<T, TO, 2, 4, 4, 4, 4>(d, c, wfrag, x, y, s);
     return launch_variant_sb<T, TO, 2, 8, 4, 4, 4>(d, c, wfrag, x, y, s);
 }
 

@@ -99,12 +99,35 @@ def test_conv3x3_matrix_core_shapes(dt, case):
     run_case(dt, N, Ci, Co, H, W, 3, stride, k, relu, seed=hash(case) % 10000 + dt, w_std=0.02)
 
 
+DENSE_MODE = [
+    # dictionaries with three corners or three edge midpoints in one pattern: dense mode on the matrix
+    # cores (every tap a dense step, pruned weights explicit zeros)
+    # N, Ci, Co,  H,  W, stride, k, rule, relu
+    (1, 32, 16, 4, 4, 1, 4, B.RULE_CONNECTED4, False),
+    (2, 96, 48, 19, 21, 1, 4, B.RULE_CONNECTED4, True),
+    (1, 64, 144, 33, 18, 1, 5, B.RULE_CONNECTED4, False),
+    (3, 64, 128, 16, 35, 1, 3, B.RULE_ALL, False),
+    (1, 256, 256, 20, 24, 1, 4, B.RULE_CONNECTED8, True),
+    (1, 32, 16, 7, 9, 2, 4, B.RULE_CONNECTED4, False),
+    (2, 64, 80, 37, 41, 2, 5, B.RULE_CONNECTED4, True),
+    (1, 128, 256, 40, 40, 2, 4, B.RULE_CONNECTED4, False),
+    (1, 32, 32, 1, 1, 1, 8, B.RULE_CONNECTED4, False),
+]
+
+
+@pytest.mark.parametrize("dt", [wl.F16, wl.BF16])
+@pytest.mark.parametrize("case", DENSE_MODE)
+def test_conv3x3_dense_mode_shapes(dt, case):
+    N, Ci, Co, H, W, stride, k, rule, relu = case
+    run_case(dt, N, Ci, Co, H, W, 3, stride, k, relu, seed=hash(case) % 10000 + dt, w_std=0.02, rule=rule)
+
+
 def test_conv3x3_matrix_core_dictionaries():
     # every pair of taps (36 patterns): still at most 2 corners and 2 edge midpoints -> sparse path
     run_case(wl.F16, 1, 64, 64, 12, 12, 3, 1, 2, False, seed=31, rule=B.RULE_ALL)
     # single-tap patterns
     run_case(wl.BF16, 1, 32, 32, 9, 9, 3, 1, 1, False, seed=32)
-    # 4-entry connected patterns include a T shape with 3 edge midpoints -> falls back to the direct path
+    # 4-entry connected patterns include a T shape with 3 edge midpoints -> dense mode
     run_case(wl.F16, 1, 64, 64, 12, 12, 3, 1, 4, False, seed=33)
     # identical weights in every kernel: every kernel picks pattern 0 (ties) -> coherent tiles
     masks = B.rtoss_pattern_dict(3)
