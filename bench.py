@@ -67,8 +67,8 @@ def parse():
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="target wall time of the oracle sample")
     ap.add_argument("--graph", choices=["auto", "on", "off"], default="auto",
                     help="replay the step from three captured HIP graphs (select, pack, conv) instead of enqueueing "
-                         "every call from Python, whose host time per launch exceeds most of these kernels; "
-                         "auto = on")
+                         "every call from Python; auto: when the workload has more than 8 layers, where the host "
+                         "time per launch exceeds the kernels' (a graph launch itself costs about 10 us)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 256 MiB device copy (a reference dispatch of known traffic for "
                          "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -148,24 +148,46 @@ def main():
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
 
+    # Selection and packing of different layers are independent (they read weights only), so their
+    # launches are spread over a few streams that fork from and join the current one: in a captured
+    # graph these become parallel branches and the small kernels overlap instead of queueing behind
+    # each other.  The convolutions stay in one stream, in layer order, as a network runs them.
+    side = [torch.cuda.Stream() for _ in range(4)] if len(cfg.layers) > 8 else []
+
+    def fanned_out(calls):
+        """calls: functions taking a raw stream handle; run round-robin over the side streams."""
+        main = torch.cuda.current_stream()
+        if not side:
+            for f in calls:
+                f(main.cuda_stream)
+            return
+        for st in side:
+            st.wait_stream(main)
+        for i, f in enumerate(calls):
+            f(side[i % len(side)].cuda_stream)
+        for st in side:
+            main.wait_stream(st)
+
     def do_select():
-        stream = torch.cuda.current_stream().cuda_stream
+        # one batched call: all 3x3 kernels as one tensor, every 1x1 tensor as an item of its own
+        items = []
         if n3:
-            B.rtoss_select_patterns(w3_all.data_ptr(), cfg.dtype, n3, masks, idx3_all.data_ptr(), stream)
+            items.append((w3_all.data_ptr(), n3, idx3_all.data_ptr()))
         for L, w, idx in zip(cfg.layers, w_dev, idx_dev):
             if L.ksize == 1:
-                B.rtoss_select_patterns(w.data_ptr(), cfg.dtype, L.n_weights, masks, idx.data_ptr(), stream)
+                items.append((w.data_ptr(), L.n_weights, idx.data_ptr()))
+        B.rtoss_select_patterns_batch(items, cfg.dtype, masks, torch.cuda.current_stream().cuda_stream)
 
     def do_pack():
-        for lay, w, idx in zip(layers, w_dev, idx_dev):
-            lay.pack(w, idx)
+        fanned_out([lambda st, lay=lay, w=w, idx=idx: lay.pack(w, idx, stream=st)
+                    for lay, w, idx in zip(layers, w_dev, idx_dev)])
 
     def do_conv():
         for L, lay, x, y in zip(cfg.layers, layers, xs, ys):
             lay.conv(x, stride=L.stride, relu=L.relu, y=y)
 
     phases = [do_select, do_pack, do_conv]
-    use_graph = args.graph != "off"
+    use_graph = args.graph == "on" or (args.graph == "auto" and len(cfg.layers) > 8)
     for f in phases:  # first launches also set kernel attributes: must happen outside capture
         f()
     torch.cuda.synchronize()

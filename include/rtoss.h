@@ -113,6 +113,23 @@ rtoss_status rtoss_select_patterns(const void* w_dev, rtoss_dtype dt, int64_t n_
                                    uint8_t* idx_dev, void* hip_stream);
 
 /*
+ * The same selection for several weight tensors of one dtype with one dictionary (all layers of a
+ * model), in as few launches as possible: each tensor is selected exactly as by
+ * rtoss_select_patterns (its own groups of 9, its own tail).
+ *
+ *   items_host  n_items entries {w_dev, n_elems, idx_dev} with the meaning and alignment of
+ *               rtoss_select_patterns' arguments; the array is read before the call returns
+ * Errors: as rtoss_select_patterns; RTOSS_EINVAL also for n_items < 0 or items_host NULL.
+ */
+typedef struct {
+    const void* w_dev;
+    int64_t n_elems;
+    uint8_t* idx_dev;
+} rtoss_select_item;
+rtoss_status rtoss_select_patterns_batch(const rtoss_select_item* items_host, int n_items, rtoss_dtype dt,
+                                         const uint16_t* masks_host, int P, void* hip_stream);
+
+/*
  * Section IV.B, second narrowing criterion (keep the patterns that are used most when
  * the selection runs over random kernels), part 1: how often each pattern was selected.
  *     hist_dev[p] += #{ g < G : idx_dev[g] == p }      for p < P

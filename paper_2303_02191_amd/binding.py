@@ -36,7 +36,11 @@ class CDesc(ctypes.Structure):
                 ("fuse_relu", ctypes.c_int)]
 
 
-EXPORTS = ["rtoss_pattern_dict", "rtoss_select_patterns", "rtoss_pattern_histogram", "rtoss_reduce_dict",
+class SelectItem(ctypes.Structure):
+    _fields_ = [("w_dev", ctypes.c_void_p), ("n_elems", ctypes.c_int64), ("idx_dev", ctypes.c_void_p)]
+
+
+EXPORTS = ["rtoss_pattern_dict", "rtoss_select_patterns", "rtoss_select_patterns_batch", "rtoss_pattern_histogram", "rtoss_reduce_dict",
            "rtoss_pack_size", "rtoss_pack", "rtoss_conv2d_pattern", "rtoss_last_error"]
 
 
@@ -60,6 +64,8 @@ def lib():
         L.rtoss_pattern_dict.argtypes = [i, i, u16p, i, ctypes.POINTER(i)]
         L.rtoss_select_patterns.restype = i
         L.rtoss_select_patterns.argtypes = [vp, i, i64, u16p, i, vp, vp]
+        L.rtoss_select_patterns_batch.restype = i
+        L.rtoss_select_patterns_batch.argtypes = [ctypes.POINTER(SelectItem), i, i, u16p, i, vp]
         L.rtoss_pattern_histogram.restype = i
         L.rtoss_pattern_histogram.argtypes = [vp, i64, i, vp, vp]
         L.rtoss_reduce_dict.restype = i
@@ -103,6 +109,18 @@ def rtoss_pattern_dict(k, rule=RULE_CONNECTED4):
 def rtoss_select_patterns(w_ptr, dt, n_elems, masks, idx_ptr, stream=0):
     mp, P, _keep = _masks_arg(masks)
     _check(lib().rtoss_select_patterns(w_ptr, int(dt), int(n_elems), mp, P, idx_ptr, stream))
+
+
+def rtoss_select_patterns_batch(items, dt, masks, stream=0):
+    """items: sequence of (w_ptr, n_elems, idx_ptr)."""
+    mp, P, _keep = _masks_arg(masks)
+    if items is None:
+        _check(lib().rtoss_select_patterns_batch(None, 1, int(dt), mp, P, stream))
+        return
+    arr = (SelectItem * max(len(items), 1))()
+    for i, (w_ptr, n, idx_ptr) in enumerate(items):
+        arr[i] = SelectItem(w_ptr, int(n), idx_ptr)
+    _check(lib().rtoss_select_patterns_batch(arr, len(items), int(dt), mp, P, stream))
 
 
 def rtoss_pattern_histogram(idx_ptr, G, P, hist_ptr, stream=0):

@@ -195,6 +195,25 @@ rtoss_status rtoss_select_patterns(const void* w_dev, rtoss_dtype dt, int64_t n_
     return launch_select(w_dev, dt, G, dict, idx_dev, (hipStream_t)hip_stream);
 }
 
+rtoss_status rtoss_select_patterns_batch(const rtoss_select_item* items_host, int n_items, rtoss_dtype dt,
+                                         const uint16_t* masks_host, int P, void* hip_stream)
+{
+    if (dt != RTOSS_F32 && dt != RTOSS_F16 && dt != RTOSS_BF16) return fail(RTOSS_EDTYPE, "bad dtype %d", (int)dt);
+    if (n_items < 0) return fail(RTOSS_EINVAL, "n_items=%d is negative", n_items);
+    Dict dict;
+    if (rtoss_status st = load_dict(masks_host, P, &dict)) return st;
+    if (n_items == 0) return RTOSS_OK;
+    if (!items_host) return fail(RTOSS_EINVAL, "items_host is NULL");
+    for (int i = 0; i < n_items; ++i) {
+        const rtoss_select_item& it = items_host[i];
+        if (it.n_elems < 0) return fail(RTOSS_EINVAL, "item %d: n_elems=%lld is negative", i, (long long)it.n_elems);
+        if (it.n_elems / 9 == 0) continue;
+        if (!it.w_dev || !it.idx_dev) return fail(RTOSS_EINVAL, "item %d: w_dev or idx_dev is NULL", i);
+        if (misaligned(it.w_dev, elem_bytes(dt))) return fail(RTOSS_EINVAL, "item %d: w_dev is not aligned to its element size", i);
+    }
+    return launch_select_batch(items_host, n_items, dt, dict, (hipStream_t)hip_stream);
+}
+
 rtoss_status rtoss_pattern_histogram(const uint8_t* idx_dev, int64_t G, int P, uint32_t* hist_dev, void* hip_stream)
 {
     if (G < 0) return fail(RTOSS_EINVAL, "G=%lld is negative", (long long)G);

@@ -59,6 +59,9 @@ rtoss_status check_hip(hipError_t e, const char* what);
 // ----- launchers (one per kernel family; defined next to the kernels) -----
 rtoss_status launch_select(const void* w, rtoss_dtype dt, int64_t G, const Dict& dict, uint8_t* idx, hipStream_t s);
 
+constexpr int kSelectBatchMax = 64;  // tensors per batched selection launch
+rtoss_status launch_select_batch(const rtoss_select_item* items, int n, rtoss_dtype dt, const Dict& dict, hipStream_t s);
+
 // counts of each pattern index (select.hip)
 rtoss_status launch_histogram(const uint8_t* idx, int64_t G, int P, uint32_t* hist, hipStream_t s);
 

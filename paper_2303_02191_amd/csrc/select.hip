@@ -19,15 +19,15 @@ constexpr int kSelLanesPerGroup = 4;
 constexpr int kSelBlock = 256;
 constexpr int kSelGroupsPerBlock = kSelBlock / kSelLanesPerGroup;
 
+// One workgroup's share: 64 groups of tensor `w` starting at group g0.
 template <typename T>
-__global__ __launch_bounds__(kSelBlock) void select_kernel(const T* __restrict__ w, int64_t G, Dict dict,
-                                                           uint8_t* __restrict__ idx)
+__device__ __forceinline__ void select_block(const T* __restrict__ w, int64_t G, const Dict& dict, uint8_t* __restrict__ idx,
+                                             int64_t g0)
 {
     __shared__ double sq[kSelGroupsPerBlock * 9];
     __shared__ uint16_t masks[256];
 
     const int tid = threadIdx.x;
-    const int64_t g0 = (int64_t)blockIdx.x * kSelGroupsPerBlock;
     const int64_t remaining = G - g0;
     const int ngroups = remaining < kSelGroupsPerBlock ? (int)remaining : kSelGroupsPerBlock;
 
@@ -62,6 +62,63 @@ __global__ __launch_bounds__(kSelBlock) void select_kernel(const T* __restrict__
         if (o_s > best_s || (o_s == best_s && o_p < best_p)) { best_s = o_s; best_p = o_p; }
     }
     if (gl < ngroups && q == 0) idx[g0 + gl] = (uint8_t)(best_p == 0xffff ? 0 : best_p);
+}
+
+template <typename T>
+__global__ __launch_bounds__(kSelBlock) void select_kernel(const T* __restrict__ w, int64_t G, Dict dict,
+                                                           uint8_t* __restrict__ idx)
+{
+    select_block<T>(w, G, dict, idx, (int64_t)blockIdx.x * kSelGroupsPerBlock);
+}
+
+// Several tensors in one launch (every layer of a model: the selection of a 1x1 tensor is over its own
+// flattening, Section IV.D, so tensors cannot simply be concatenated).  The table travels in the
+// launch arguments; a workgroup finds its tensor by scanning the table's first-block numbers.
+struct SelectBatch {
+    const void* w[kSelectBatchMax];
+    uint8_t* idx[kSelectBatchMax];
+    int64_t G[kSelectBatchMax];
+    int first_block[kSelectBatchMax + 1];
+    int n;
+};
+
+template <typename T>
+__global__ __launch_bounds__(kSelBlock) void select_batch_kernel(SelectBatch batch, Dict dict)
+{
+    int t = 0;
+    while (t + 1 < batch.n && (int)blockIdx.x >= batch.first_block[t + 1]) ++t;  // block-uniform
+    select_block<T>((const T*)batch.w[t], batch.G[t], dict, batch.idx[t],
+                    (int64_t)((int)blockIdx.x - batch.first_block[t]) * kSelGroupsPerBlock);
+}
+
+rtoss_status launch_select_batch(const rtoss_select_item* items, int n, rtoss_dtype dt, const Dict& dict, hipStream_t s)
+{
+    for (int base = 0; base < n; base += kSelectBatchMax) {
+        SelectBatch b;
+        b.n = 0;
+        int64_t blocks = 0;
+        for (int i = base; i < n && b.n < kSelectBatchMax; ++i) {
+            const int64_t G = items[i].n_elems / 9;
+            if (G == 0) continue;
+            b.w[b.n] = items[i].w_dev;
+            b.idx[b.n] = items[i].idx_dev;
+            b.G[b.n] = G;
+            b.first_block[b.n] = (int)blocks;
+            blocks += (G + kSelGroupsPerBlock - 1) / kSelGroupsPerBlock;
+            if (blocks > 0x7fffffffLL) return fail(RTOSS_ESHAPE, "select: too many groups in one batch");
+            ++b.n;
+        }
+        if (b.n == 0) continue;
+        b.first_block[b.n] = (int)blocks;
+        dim3 grid((unsigned)blocks), block(kSelBlock);
+        switch (dt) {
+        case RTOSS_F32: select_batch_kernel<float><<<grid, block, 0, s>>>(b, dict); break;
+        case RTOSS_F16: select_batch_kernel<f16_t><<<grid, block, 0, s>>>(b, dict); break;
+        case RTOSS_BF16: select_batch_kernel<bf16_t><<<grid, block, 0, s>>>(b, dict); break;
+        }
+        if (rtoss_status st = check_hip(hipGetLastError(), "select batch launch")) return st;
+    }
+    return RTOSS_OK;
 }
 
 rtoss_status launch_select(const void* w, rtoss_dtype dt, int64_t G, const Dict& dict, uint8_t* idx, hipStream_t s)

@@ -38,6 +38,19 @@ def select_patterns(w, dt, masks):
     return idx[: w.numel() // 9]
 
 
+def select_patterns_batch(ws, dt, masks, idxs=None, stream=None):
+    """Selection for several weight tensors (contiguous cuda tensors of one dtype) in one call.
+    Returns the list of uint8 index tensors (idxs, if given, are filled in place)."""
+    if idxs is None:
+        idxs = [torch.empty(max(w.numel() // 9, 1), dtype=torch.uint8, device=w.device) for w in ws]
+    items = []
+    for w, idx in zip(ws, idxs):
+        assert w.is_cuda and w.is_contiguous() and idx.is_cuda and idx.numel() >= w.numel() // 9
+        items.append((w.data_ptr(), w.numel(), idx.data_ptr()))
+    B.rtoss_select_patterns_batch(items, dt, masks, _stream() if stream is None else stream)
+    return [idx[: w.numel() // 9] for w, idx in zip(ws, idxs)]
+
+
 def pattern_histogram(idx, P, hist=None):
     """Adds the usage counts of idx (uint8 cuda tensor) to hist (uint32 counts as an int32 cuda tensor [P])."""
     assert idx.is_cuda and idx.dtype == torch.uint8 and idx.is_contiguous()
@@ -69,10 +82,11 @@ class PackedLayer:
         self.blob = torch.empty(self.packed_bytes, dtype=torch.uint8, device=device)
         self.workspace = torch.empty(max(self.workspace_bytes, 1), dtype=torch.uint8, device=device)
 
-    def pack(self, w, idx):
+    def pack(self, w, idx, stream=None):
+        """stream: raw HIP stream handle (default: torch's current stream)."""
         assert w.is_cuda and w.is_contiguous() and idx.is_cuda
         B.rtoss_pack(self.wdesc, w.data_ptr(), idx.data_ptr(), self.masks, self.blob.data_ptr(), self.packed_bytes,
-                     self.workspace.data_ptr(), self.workspace_bytes, _stream())
+                     self.workspace.data_ptr(), self.workspace_bytes, _stream() if stream is None else stream)
         return self
 
     def out_shape(self, x_shape, stride):

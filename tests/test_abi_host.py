@@ -145,3 +145,24 @@ def test_histogram_argument_errors():
         assert e.value.status == B.EINVAL
     B.rtoss_pattern_histogram(0, 0, 12, 256)  # nothing to count: no launch, no error
 
+
+def test_batched_select_argument_errors():
+    masks = B.rtoss_pattern_dict(2)
+    with pytest.raises(B.RtossError) as e:
+        B.rtoss_select_patterns_batch(None, B.F16, masks)  # NULL table with a non-zero count
+    assert e.value.status == B.EINVAL
+    with pytest.raises(B.RtossError) as e:
+        B.rtoss_select_patterns_batch([(0, 900, 256)], B.F16, masks)  # NULL weights
+    assert e.value.status == B.EINVAL
+    with pytest.raises(B.RtossError) as e:
+        B.rtoss_select_patterns_batch([(257, 900, 256)], B.F16, masks)  # misaligned weights
+    assert e.value.status == B.EINVAL
+    with pytest.raises(B.RtossError) as e:
+        B.rtoss_select_patterns_batch([(256, -9, 256)], B.F16, masks)
+    assert e.value.status == B.EINVAL
+    with pytest.raises(B.RtossError) as e:
+        B.rtoss_select_patterns_batch([(256, 900, 256)], 7, masks)
+    assert e.value.status == B.EDTYPE
+    B.rtoss_select_patterns_batch([], B.F16, masks)             # nothing to do
+    B.rtoss_select_patterns_batch([(0, 8, 0)], B.F16, masks)    # fewer than 9 weights: no group, no launch
+

@@ -121,3 +121,20 @@ def test_dictionary_reduction_matches_oracle(dt, k, M):
     got = gpu_select(store, dt, red)
     assert np.array_equal(got, oracle.select(vals, red))
 
+
+@pytest.mark.parametrize("dt", [wl.F32, wl.F16, wl.BF16])
+def test_batched_select_matches_oracle_per_tensor(dt):
+    # more tensors than one launch's table holds, with empty and tail-only tensors in between
+    from paper_2303_02191_amd import pipeline as pl
+    masks = B.rtoss_pattern_dict(3)
+    rng = np.random.default_rng(321 + dt)
+    sizes = [int(v) for v in rng.integers(0, 4000, 150)] + [0, 8, 9, 9 * 64, 9 * 64 + 1, 9 * 5000 + 7]
+    stores, vals = zip(*[_draw(n, dt, seed=1000 + i) for i, n in enumerate(sizes)])
+    ws = [pl.to_device(np.ascontiguousarray(s_), dt) for s_ in stores]
+    got = pl.select_patterns_batch(ws, dt, masks)
+    import torch
+    torch.cuda.synchronize()
+    for n, v, g in zip(sizes, vals, got):
+        want = oracle.select(v, masks) if n >= 9 else np.zeros(0, dtype=np.uint8)
+        assert np.array_equal(g.cpu().numpy(), want), n
+
