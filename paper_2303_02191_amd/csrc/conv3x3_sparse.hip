@@ -803,8 +803,10 @@ rtoss_status launch_typed(const rtoss_wdesc& d, const rtoss_cdesc& c, const char
         if (cost5 < cost4 && d.Ci >= 128) return launch_variant<T, TO, 1, 8, 5, 5, 4>(d, c, wfrag, x, y, s);
         return launch_variant<T, TO, 1, 8, 4, 4, 4>(d, c, wfrag, x, y, s);
     }
-    if (d.Co <= 64) return launch_variant_sb<T, TO, 2, 4, 4, 4, 4>(d, c, wfrag, x, y, s);
-    return launch_variant_sb<T, TO, 2, 8, 4, 4, 4>(d, c, wfrag, x, y, s);
+    // Stride 2: the input tile of a 16x16 output tile (33x33 positions) nearly fills the LDS by itself.
+    // Half-height tiles (8x16 outputs, 17x33 inputs) with 64 channels per workgroup need 72 KB, so two
+    // workgroups share a compute unit and overlap each other's copies, and small images pad less.
+    return launch_variant_sb<T, TO, 2, 4, 2, 2, 4>(d, c, wfrag, x, y, s);
 }
 
 }  // namespace
