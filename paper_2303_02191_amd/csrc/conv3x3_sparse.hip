@@ -789,7 +789,12 @@ rtoss_status launch_typed(const rtoss_wdesc& d, const rtoss_cdesc& c, const char
     // prologue, take the single-buffered kernel with 64 channels per workgroup.
     const bool small = d.Co <= 64 || d.Ci <= 64;
     if (c.stride == 1) {
-        if (small) return launch_variant_sb<T, TO, 1, 4, 4, 4, 4>(d, c, wfrag, x, y, s);
+        // 8x16-position tiles for these: 38 KB of LDS, four workgroups per compute unit.  (Measured: more
+        // resident workgroups beat double-buffering inside one, and beat 16x16 tiles, on every such layer.)
+        if (small) return launch_variant_sb<T, TO, 1, 4, 2, 2, 4>(d, c, wfrag, x, y, s);
+        // ... and so do launches that would leave compute units idle with 128 channels per workgroup
+        const int64_t tiles8 = (int64_t)((c.H + 15) / 16) * ((c.W + 15) / 16) * c.N * (((d.Co + 15) / 16 + 7) / 8);
+        if (tiles8 < 200) return launch_variant_sb<T, TO, 1, 4, 2, 2, 4>(d, c, wfrag, x, y, s);
         // Two tile shapes: 16x16 positions, or 20 rows x 16 columns (5 position blocks per wave: better
         // reuse of the weight fragments, and for some images fewer rounds over the compute units or less
         // padding).  Cost model: rounds of the busiest workgroup x relative cost of a tile.
