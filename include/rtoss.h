@@ -238,6 +238,33 @@ rtoss_status rtoss_conv2d_pattern(const rtoss_wdesc* desc, const rtoss_cdesc* cd
                                   const void* packed_dev, const void* x_dev, void* y_dev,
                                   void* hip_stream);
 
+/*
+ * The same convolution with a fused output stage (the operations that follow a convolution in the
+ * detector blocks whose inference time Section V reports: folded batch normalisation, activation,
+ * shortcut connection):
+ *     y = act(scale[co] * conv + bias[co]) + residual
+ * evaluated in fp32 on the accumulator and rounded once on store.
+ *
+ *   scale_dev, bias_dev  Co floats each (device, 16-byte aligned), or NULL for 1 / 0
+ *   act                  RTOSS_ACT_NONE, RTOSS_ACT_RELU (max(v, 0)) or RTOSS_ACT_SILU (v / (1 + exp(-v)))
+ *   residual_dev         tensor of y's type and shape (device, 16-byte aligned), or NULL; may not
+ *                        overlap y_dev
+ * cdesc->fuse_relu must be 0 (use act).  All other arguments and errors as rtoss_conv2d_pattern;
+ * RTOSS_EINVAL also for a bad act, misaligned pointers or fuse_relu != 0.
+ */
+typedef enum { RTOSS_ACT_NONE = 0, RTOSS_ACT_RELU = 1, RTOSS_ACT_SILU = 2 } rtoss_act;
+typedef struct {
+    const float* scale_dev;
+    const float* bias_dev;
+    rtoss_act act;
+    const void* residual_dev;
+} rtoss_epilogue;
+rtoss_status rtoss_conv2d_pattern_fused(const rtoss_wdesc* desc, const rtoss_cdesc* cdesc,
+                                        const rtoss_epilogue* epilogue,
+                                        const uint16_t* masks_host, int P,
+                                        const void* packed_dev, const void* x_dev, void* y_dev,
+                                        void* hip_stream);
+
 /* Message for the last error on the calling thread ("" if none).  Static storage. */
 const char* rtoss_last_error(void);
 

@@ -10,7 +10,11 @@ from .oracle import (  # noqa: F401
     RULE_CONNECTED4,
     RULE_CONNECTED8,
     build,
+    ACT_NONE,
+    ACT_RELU,
+    ACT_SILU,
     conv2d,
+    conv2d_fused,
     conv2d_live3x3,
     conv2d_points,
     histogram,

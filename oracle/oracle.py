@@ -183,3 +183,27 @@ def reduce_dict(masks, counts, M):
     kept = np.array(sorted(ranked[:M]), dtype=np.int64)
     return masks[kept], kept
 
+
+ACT_NONE, ACT_RELU, ACT_SILU = 0, 1, 2
+
+
+def conv2d_fused(x, w, stride=1, pad=None, scale=None, bias=None, act=ACT_NONE, residual=None):
+    """Convolution followed by the output stage of a detector block, written out term by term:
+        y = act(scale[co] * conv(x, w) + bias[co]) + residual
+    act: none, ReLU max(v, 0), or SiLU v * sigmoid(v) = v / (1 + exp(-v)).  All in float64."""
+    y = conv2d(x, w, stride=stride, pad=pad, relu=False)
+    Co = y.shape[1]
+    if scale is not None:
+        y = y * np.asarray(scale, dtype=np.float64).reshape(1, Co, 1, 1)
+    if bias is not None:
+        y = y + np.asarray(bias, dtype=np.float64).reshape(1, Co, 1, 1)
+    if act == ACT_RELU:
+        y = np.maximum(y, 0.0)
+    elif act == ACT_SILU:
+        y = y / (1.0 + np.exp(-y))
+    elif act != ACT_NONE:
+        raise ValueError("unknown activation")
+    if residual is not None:
+        y = y + np.asarray(residual, dtype=np.float64)
+    return y
+

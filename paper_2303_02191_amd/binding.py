@@ -36,12 +36,20 @@ class CDesc(ctypes.Structure):
                 ("fuse_relu", ctypes.c_int)]
 
 
+ACT_NONE, ACT_RELU, ACT_SILU = 0, 1, 2
+
+
+class EpilogueDesc(ctypes.Structure):
+    _fields_ = [("scale_dev", ctypes.c_void_p), ("bias_dev", ctypes.c_void_p), ("act", ctypes.c_int),
+                ("residual_dev", ctypes.c_void_p)]
+
+
 class SelectItem(ctypes.Structure):
     _fields_ = [("w_dev", ctypes.c_void_p), ("n_elems", ctypes.c_int64), ("idx_dev", ctypes.c_void_p)]
 
 
 EXPORTS = ["rtoss_pattern_dict", "rtoss_select_patterns", "rtoss_select_patterns_batch", "rtoss_pattern_histogram", "rtoss_reduce_dict",
-           "rtoss_pack_size", "rtoss_pack", "rtoss_conv2d_pattern", "rtoss_last_error"]
+           "rtoss_pack_size", "rtoss_pack", "rtoss_conv2d_pattern", "rtoss_conv2d_pattern_fused", "rtoss_last_error"]
 
 
 def lib():
@@ -76,6 +84,9 @@ def lib():
         L.rtoss_pack.argtypes = [ctypes.POINTER(WDesc), vp, vp, u16p, i, vp, ctypes.c_size_t, vp, ctypes.c_size_t, vp]
         L.rtoss_conv2d_pattern.restype = i
         L.rtoss_conv2d_pattern.argtypes = [ctypes.POINTER(WDesc), ctypes.POINTER(CDesc), u16p, i, vp, vp, vp, vp]
+        L.rtoss_conv2d_pattern_fused.restype = i
+        L.rtoss_conv2d_pattern_fused.argtypes = [ctypes.POINTER(WDesc), ctypes.POINTER(CDesc), ctypes.POINTER(EpilogueDesc),
+                                                 u16p, i, vp, vp, vp, vp]
         _lib = L
     return _lib
 
@@ -159,3 +170,13 @@ def rtoss_conv2d_pattern(wdesc, cdesc, masks, packed_ptr, x_ptr, y_ptr, stream=0
     _check(lib().rtoss_conv2d_pattern(ctypes.byref(wdesc) if wdesc is not None else None,
                                       ctypes.byref(cdesc) if cdesc is not None else None, mp, P, packed_ptr, x_ptr,
                                       y_ptr, stream))
+
+
+def rtoss_conv2d_pattern_fused(wdesc, cdesc, epilogue, masks, packed_ptr, x_ptr, y_ptr, stream=0):
+    """epilogue: EpilogueDesc (scale, bias, activation, residual)."""
+    mp, P, _keep = _masks_arg(masks)
+    _check(lib().rtoss_conv2d_pattern_fused(ctypes.byref(wdesc) if wdesc is not None else None,
+                                            ctypes.byref(cdesc) if cdesc is not None else None,
+                                            ctypes.byref(epilogue) if epilogue is not None else None, mp, P,
+                                            packed_ptr, x_ptr, y_ptr, stream))
+

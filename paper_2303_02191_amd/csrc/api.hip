@@ -8,6 +8,7 @@
 #include <vector>
 
 #include "common.h"
+#include "epilogue.h"
 
 namespace rtoss {
 
@@ -290,8 +291,9 @@ rtoss_status rtoss_pack(const rtoss_wdesc* desc, const void* w_dev, const uint8_
     return launch_pack_live(*desc, w_dev, idx_dev, dict, live, live_idx, g.G, s);
 }
 
-rtoss_status rtoss_conv2d_pattern(const rtoss_wdesc* desc, const rtoss_cdesc* c, const uint16_t* masks_host, int P,
-                                  const void* packed_dev, const void* x_dev, void* y_dev, void* hip_stream)
+static rtoss_status conv_impl(const rtoss_wdesc* desc, const rtoss_cdesc* c, const rtoss_epilogue* e,
+                              const uint16_t* masks_host, int P, const void* packed_dev, const void* x_dev, void* y_dev,
+                              void* hip_stream)
 {
     if (rtoss_status st = check_wdesc(desc)) return st;
     if (!c) return fail(RTOSS_EINVAL, "conv descriptor is NULL");
@@ -318,21 +320,49 @@ rtoss_status rtoss_conv2d_pattern(const rtoss_wdesc* desc, const rtoss_cdesc* c,
     const size_t yb = (size_t)c->N * Ho * Wo * desc->Co * elem_bytes(c->out_dt);
     const char *xa = (const char*)x_dev, *ya = (const char*)y_dev;
     if (xa < ya + yb && ya < xa + xb) return fail(RTOSS_EINVAL, "x and y overlap");
+    ConvParams cp;
+    static_cast<rtoss_cdesc&>(cp) = *c;
+    cp.ep = Epilogue{nullptr, nullptr, nullptr, c->fuse_relu ? 1 : 0};
+    if (e) {
+        if (c->fuse_relu) return fail(RTOSS_EINVAL, "fuse_relu must be 0 when an epilogue is given (use its act)");
+        if (e->act != RTOSS_ACT_NONE && e->act != RTOSS_ACT_RELU && e->act != RTOSS_ACT_SILU)
+            return fail(RTOSS_EINVAL, "unknown activation %d", (int)e->act);
+        if (misaligned(e->scale_dev, 16) || misaligned(e->bias_dev, 16) || misaligned(e->residual_dev, 16))
+            return fail(RTOSS_EINVAL, "scale_dev, bias_dev and residual_dev must be 16-byte aligned");
+        const char* ra = (const char*)e->residual_dev;
+        if (ra && ra < ya + yb && ya < ra + yb) return fail(RTOSS_EINVAL, "residual and y overlap");
+        cp.ep = Epilogue{e->scale_dev, e->bias_dev, e->residual_dev, (int)e->act};
+    }
     BlobGeometry g;
     if (rtoss_status st = blob_geometry(desc, dict, &g)) return st;
     const char* blob = (const char*)packed_dev;
     if (g.format == kFormatSparse24)
-        return launch_conv3x3_sparse(*desc, *c, blob + g.mat_off, x_dev, y_dev, (hipStream_t)hip_stream);
+        return launch_conv3x3_sparse(*desc, cp, blob + g.mat_off, x_dev, y_dev, (hipStream_t)hip_stream);
     if (g.format == kFormatStem)
-        return launch_conv3x3_stem(*desc, *c, blob + g.mat_off, x_dev, y_dev, (hipStream_t)hip_stream);
+        return launch_conv3x3_stem(*desc, cp, blob + g.mat_off, x_dev, y_dev, (hipStream_t)hip_stream);
     if (g.format == kFormatDense3x3)
-        return launch_conv3x3_dense(*desc, *c, blob + g.mat_off, x_dev, y_dev, (hipStream_t)hip_stream);
+        return launch_conv3x3_dense(*desc, cp, blob + g.mat_off, x_dev, y_dev, (hipStream_t)hip_stream);
     if (g.format == kFormatDenseStream)
-        return launch_conv1x1_stream(*desc, *c, blob + g.mat_off, x_dev, y_dev, (hipStream_t)hip_stream);
+        return launch_conv1x1_stream(*desc, cp, blob + g.mat_off, x_dev, y_dev, (hipStream_t)hip_stream);
     if (g.format == kFormatDense)
-        return launch_conv1x1_mma(*desc, *c, blob + g.mat_off, x_dev, y_dev, (hipStream_t)hip_stream);
-    return launch_conv_direct(*desc, *c, dict, blob + g.live_off, (const uint8_t*)(blob + g.idx_off), x_dev, y_dev,
+        return launch_conv1x1_mma(*desc, cp, blob + g.mat_off, x_dev, y_dev, (hipStream_t)hip_stream);
+    return launch_conv_direct(*desc, cp, dict, blob + g.live_off, (const uint8_t*)(blob + g.idx_off), x_dev, y_dev,
                               (hipStream_t)hip_stream);
+}
+
+
+rtoss_status rtoss_conv2d_pattern(const rtoss_wdesc* desc, const rtoss_cdesc* c, const uint16_t* masks_host, int P,
+                                  const void* packed_dev, const void* x_dev, void* y_dev, void* hip_stream)
+{
+    return conv_impl(desc, c, nullptr, masks_host, P, packed_dev, x_dev, y_dev, hip_stream);
+}
+
+rtoss_status rtoss_conv2d_pattern_fused(const rtoss_wdesc* desc, const rtoss_cdesc* c, const rtoss_epilogue* epilogue,
+                                        const uint16_t* masks_host, int P, const void* packed_dev, const void* x_dev,
+                                        void* y_dev, void* hip_stream)
+{
+    if (!epilogue) return fail(RTOSS_EINVAL, "epilogue is NULL");
+    return conv_impl(desc, c, epilogue, masks_host, P, packed_dev, x_dev, y_dev, hip_stream);
 }
 
 }  // extern "C"

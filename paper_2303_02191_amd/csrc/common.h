@@ -9,6 +9,8 @@
 
 namespace rtoss {
 
+struct ConvParams;  // rtoss_cdesc + the fused output stage (epilogue.h)
+
 constexpr int kMaxPatterns = 255;
 
 // A dictionary travels to every kernel by value in the launch arguments, so the host
@@ -68,7 +70,7 @@ rtoss_status launch_histogram(const uint8_t* idx, int64_t G, int P, uint32_t* hi
 rtoss_status launch_pack_live(const rtoss_wdesc& d, const void* w, const uint8_t* idx, const Dict& dict,
                               void* live_values, uint8_t* live_idx, int64_t G, hipStream_t s);
 
-rtoss_status launch_conv_direct(const rtoss_wdesc& d, const rtoss_cdesc& c, const Dict& dict, const void* live_values,
+rtoss_status launch_conv_direct(const rtoss_wdesc& d, const ConvParams& c, const Dict& dict, const void* live_values,
                                 const uint8_t* live_idx, const void* x, void* y, hipStream_t s);
 
 // 3x3 convolution on the sparse matrix instruction (conv3x3_sparse.hip)
@@ -77,7 +79,7 @@ bool sparse3x3_shape_ok(const rtoss_wdesc& d);
 size_t sparse3x3_section_bytes(const rtoss_wdesc& d);
 rtoss_status launch_pack_sparse3x3(const rtoss_wdesc& d, const void* w, const uint8_t* idx, const Dict& dict,
                                    void* section, void* live_values, uint8_t* live_idx, hipStream_t s);
-rtoss_status launch_conv3x3_sparse(const rtoss_wdesc& d, const rtoss_cdesc& c, const void* section, const void* x,
+rtoss_status launch_conv3x3_sparse(const rtoss_wdesc& d, const ConvParams& c, const void* section, const void* x,
                                    void* y, hipStream_t s);
 
 // 3x3 convolution in dense mode on the matrix cores (conv3x3_dense.hip)
@@ -85,7 +87,7 @@ bool dense3x3_shape_ok(const rtoss_wdesc& d);
 size_t dense3x3_section_bytes(const rtoss_wdesc& d);
 rtoss_status launch_pack_dense3x3(const rtoss_wdesc& d, const void* w, const uint8_t* idx, const Dict& dict, void* section,
                                   void* live_values, uint8_t* live_idx, hipStream_t s);
-rtoss_status launch_conv3x3_dense(const rtoss_wdesc& d, const rtoss_cdesc& c, const void* section, const void* x, void* y,
+rtoss_status launch_conv3x3_dense(const rtoss_wdesc& d, const ConvParams& c, const void* section, const void* x, void* y,
                                   hipStream_t s);
 
 // 1x1 convolution on the dense matrix instruction (conv1x1_mma.hip)
@@ -93,7 +95,7 @@ bool dense1x1_shape_ok(const rtoss_wdesc& d);
 size_t dense1x1_section_bytes(const rtoss_wdesc& d);
 rtoss_status launch_pack_dense1x1(const rtoss_wdesc& d, const void* w, const uint8_t* idx, const Dict& dict, void* section,
                                   void* live_values, uint8_t* live_idx, hipStream_t s);
-rtoss_status launch_conv1x1_mma(const rtoss_wdesc& d, const rtoss_cdesc& c, const void* section, const void* x, void* y,
+rtoss_status launch_conv1x1_mma(const rtoss_wdesc& d, const ConvParams& c, const void* section, const void* x, void* y,
                                 hipStream_t s);
 
 // 1x1 convolution, streaming kernel with register-resident weights (conv1x1_stream.hip)
@@ -101,7 +103,7 @@ bool stream1x1_shape_ok(const rtoss_wdesc& d);
 size_t stream1x1_section_bytes(const rtoss_wdesc& d);
 rtoss_status launch_pack_stream1x1(const rtoss_wdesc& d, const void* w, const uint8_t* idx, const Dict& dict, void* section,
                                    void* live_values, uint8_t* live_idx, hipStream_t s);
-rtoss_status launch_conv1x1_stream(const rtoss_wdesc& d, const rtoss_cdesc& c, const void* section, const void* x, void* y,
+rtoss_status launch_conv1x1_stream(const rtoss_wdesc& d, const ConvParams& c, const void* section, const void* x, void* y,
                                    hipStream_t s);
 
 // 3x3 convolution with <= 3 input channels (conv3x3_stem.hip)
@@ -109,7 +111,7 @@ bool stem3x3_shape_ok(const rtoss_wdesc& d);
 size_t stem3x3_section_bytes(const rtoss_wdesc& d);
 rtoss_status launch_pack_stem3x3(const rtoss_wdesc& d, const void* w, const uint8_t* idx, const Dict& dict, void* section,
                                  void* live_values, uint8_t* live_idx, hipStream_t s);
-rtoss_status launch_conv3x3_stem(const rtoss_wdesc& d, const rtoss_cdesc& c, const void* section, const void* x, void* y,
+rtoss_status launch_conv3x3_stem(const rtoss_wdesc& d, const ConvParams& c, const void* section, const void* x, void* y,
                                  hipStream_t s);
 
 }  // namespace rtoss

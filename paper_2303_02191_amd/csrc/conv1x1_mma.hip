@@ -22,6 +22,7 @@
 
 #include "common.h"
 #include "dtypes.h"
+#include "epilogue.h"
 #include "mma.h"
 #include "pack_live.h"
 
@@ -82,7 +83,7 @@ template <typename T, typename TO, int TM>
 __global__ __launch_bounds__(256) void conv1x1_mma_kernel(const T* __restrict__ x, TO* __restrict__ y,
                                                           const char* __restrict__ wfrag, const char* __restrict__ zeros,
                                                           int64_t P, int Ci, int Co, int m_tiles_total, int co_blocks,
-                                                          int total_work, int work_per_xcd, int relu)
+                                                          int total_work, int work_per_xcd, Epilogue ep)
 {
     constexpr int TN = 2;                                // 16-position blocks per wave
     constexpr int A_PER_WAVE = (TM + 3) / 4;             // copy instructions per wave and stage (64 lanes x 16 B each)
@@ -181,7 +182,6 @@ __global__ __launch_bounds__(256) void conv1x1_mma_kernel(const T* __restrict__ 
         constexpr int ROW = TMH * 16 * EB + (EB == 2 ? 8 : 16);
         static_assert(4 * 16 * TN * ROW <= kRing * STAGE, "epilogue staging must fit in the ring");
         char* stage_out = smem + wave * (16 * TN * ROW);
-        const float relu_floor = relu ? 0.f : -__builtin_inff();
 #pragma unroll
         for (int h = 0; h < HALVES; ++h) {
 #pragma unroll
@@ -189,11 +189,15 @@ __global__ __launch_bounds__(256) void conv1x1_mma_kernel(const T* __restrict__ 
 #pragma unroll
                 for (int mm = 0; mm < TMH; ++mm) {
                     f32x4 v = acc[h * TMH + mm][j];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {  // fused ReLU: max with 0, or with -inf when it is off
-                        float r;
-                        asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(v[e]), "v"(relu_floor));
-                        v[e] = r;
+                    {  // output stage on this lane's 4 consecutive channels of position p_f
+                        const int co4 = 16 * (mt0 + h * TMH + mm) + 4 * qq;
+                        const int64_t p_f = p0 + wave * (TN * 16) + j * 16 + nn;
+                        if (p_f < P && co4 < Co) {
+                            float vv[4] = {v.x, v.y, v.z, v.w};
+                            epi_scale_bias_act<4>(vv, ep, co4);
+                            epi_residual<TO, 4>(vv, ep, p_f * Co + co4);
+                            v = f32x4{vv[0], vv[1], vv[2], vv[3]};
+                        }
                     }
                     char* dst = stage_out + (j * 16 + nn) * ROW + (16 * mm + 4 * qq) * EB;
                     if constexpr (EB == 4) {
@@ -224,7 +228,7 @@ __global__ __launch_bounds__(256) void conv1x1_mma_kernel(const T* __restrict__ 
 }
 
 template <typename T, typename TO, int TM>
-rtoss_status launch_tm(const rtoss_wdesc& d, const rtoss_cdesc& c, const char* wfrag, const void* x, void* y, hipStream_t s)
+rtoss_status launch_tm(const rtoss_wdesc& d, const ConvParams& c, const char* wfrag, const void* x, void* y, hipStream_t s)
 {
     const int64_t P = (int64_t)c.N * c.H * c.W;
     const int64_t pos_tiles = (P + kTilePos - 1) / kTilePos;
@@ -244,12 +248,12 @@ rtoss_status launch_tm(const rtoss_wdesc& d, const rtoss_cdesc& c, const char* w
     }
     dim3 grid((unsigned)(work_per_xcd * 8)), block(256);
     kern<<<grid, block, smem, s>>>((const T*)x, (TO*)y, wfrag, wfrag + frag_bytes(d), P, d.Ci, d.Co, padded_tiles(d.Co),
-                                   co_blocks, (int)total, work_per_xcd, c.fuse_relu);
+                                   co_blocks, (int)total, work_per_xcd, c.ep);
     return check_hip(hipGetLastError(), "conv1x1 launch");
 }
 
 template <typename T, typename TO>
-rtoss_status launch_typed(const rtoss_wdesc& d, const rtoss_cdesc& c, const char* wfrag, const void* x, void* y, hipStream_t s)
+rtoss_status launch_typed(const rtoss_wdesc& d, const ConvParams& c, const char* wfrag, const void* x, void* y, hipStream_t s)
 {
     // the fragment section is padded to a multiple of 8 channel tiles, so a block of TM <= 8 tiles never reads past it
     const int tiles = (d.Co + 15) / 16;
@@ -283,7 +287,7 @@ rtoss_status launch_pack_dense1x1(const rtoss_wdesc& d, const void* w, const uin
     return check_hip(hipGetLastError(), "pack dense1x1 launch");
 }
 
-rtoss_status launch_conv1x1_mma(const rtoss_wdesc& d, const rtoss_cdesc& c, const void* section, const void* x, void* y,
+rtoss_status launch_conv1x1_mma(const rtoss_wdesc& d, const ConvParams& c, const void* section, const void* x, void* y,
                                 hipStream_t s)
 {
     const char* wf = (const char*)section;

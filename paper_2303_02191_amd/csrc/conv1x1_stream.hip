@@ -30,6 +30,7 @@
 
 #include "common.h"
 #include "dtypes.h"
+#include "epilogue.h"
 #include "mma.h"
 #include "pack_live.h"
 
@@ -158,7 +159,7 @@ template <typename T, typename TO, int KS, int WM>
 __global__ __launch_bounds__(320) void conv1x1_stream_kernel(const T* __restrict__ x, TO* __restrict__ y,
                                                              const char* __restrict__ wfrag, const char* __restrict__ zeros,
                                                              int64_t P, int Co, int co_blocks, int64_t nbuf, int wgs_per_cb,
-                                                             int total_wgs, int work_per_xcd, int relu)
+                                                             int total_wgs, int work_per_xcd, Epilogue ep)
 {
     using PL = Plan<KS, WM>;
     constexpr int MT = PL::MT, WN = PL::WN, NB = PL::NB, PB = PL::PB, BUF = PL::BUF, COPIES = PL::COPIES, RING = PL::RING;
@@ -234,7 +235,6 @@ __global__ __launch_bounds__(320) void conv1x1_stream_kernel(const T* __restrict
     // operand read offset within a buffer for stage 0, block 0 (the swizzle depends on nn only)
     const int x_lane = (wn * 16 + nn) * 64 + ((qq ^ ((nn >> 1) & 3)) * 16);
     const int co_lane = cb * PL::SPAN + wm * (16 * MT) + 4 * MT * qq;  // first of this lane's 4*MT channels
-    const float relu_floor = relu ? 0.f : -__builtin_inff();
     constexpr int EB = (int)sizeof(TO);
 
     int slot = 0;
@@ -269,8 +269,9 @@ __global__ __launch_bounds__(320) void conv1x1_stream_kernel(const T* __restrict
 #pragma unroll
             for (int m = 0; m < MT; ++m)
 #pragma unroll
-                for (int e = 0; e < 4; ++e)  // fused ReLU: max with 0, or with -inf when it is off
-                    v[4 * m + e] = __builtin_fmaxf(acc[m][j][e], relu_floor);
+                for (int e = 0; e < 4; ++e) v[4 * m + e] = acc[m][j][e];
+            epi_scale_bias_act<4 * MT>(v, ep, co_lane);
+            epi_residual<TO, 4 * MT>(v, ep, yp - y);
             if constexpr (EB == 4) {
 #pragma unroll
                 for (int g = 0; g < MT; ++g) *(f32x4*)(yp + 4 * g) = f32x4{v[4 * g], v[4 * g + 1], v[4 * g + 2], v[4 * g + 3]};
@@ -296,7 +297,7 @@ __global__ __launch_bounds__(320) void conv1x1_stream_kernel(const T* __restrict
 }
 
 template <typename T, typename TO, int KS, int WM>
-rtoss_status launch_plan(const rtoss_wdesc& d, const rtoss_cdesc& c, const char* wfrag, const void* x, void* y, hipStream_t s)
+rtoss_status launch_plan(const rtoss_wdesc& d, const ConvParams& c, const char* wfrag, const void* x, void* y, hipStream_t s)
 {
     using PL = Plan<KS, WM>;
     const int64_t P = (int64_t)c.N * c.H * c.W;
@@ -328,12 +329,12 @@ rtoss_status launch_plan(const rtoss_wdesc& d, const rtoss_cdesc& c, const char*
     if (P * d.Ci * 2 / PL::PB > 0x7fffffffffffll || nbuf > 0x7fffffff) return fail(RTOSS_ESHAPE, "conv1x1: too many positions");
     dim3 grid((unsigned)(work_per_xcd * 8)), block(320);
     kern<<<grid, block, smem, s>>>((const T*)x, (TO*)y, wfrag, wfrag + frag_bytes(d), P, d.Co, co_blocks, nbuf, wgs_per_cb,
-                                   total, work_per_xcd, c.fuse_relu);
+                                   total, work_per_xcd, c.ep);
     return check_hip(hipGetLastError(), "conv1x1 stream launch");
 }
 
 template <typename T, typename TO, int KS>
-rtoss_status launch_ks(const rtoss_wdesc& d, const rtoss_cdesc& c, const char* wfrag, const void* x, void* y, hipStream_t s)
+rtoss_status launch_ks(const rtoss_wdesc& d, const ConvParams& c, const char* wfrag, const void* x, void* y, hipStream_t s)
 {
     const int wm = wm_of(KS, d.Co);
     if constexpr (KS <= 8)
@@ -344,7 +345,7 @@ rtoss_status launch_ks(const rtoss_wdesc& d, const rtoss_cdesc& c, const char* w
 }
 
 template <typename T, typename TO>
-rtoss_status launch_typed(const rtoss_wdesc& d, const rtoss_cdesc& c, const char* wfrag, const void* x, void* y, hipStream_t s)
+rtoss_status launch_typed(const rtoss_wdesc& d, const ConvParams& c, const char* wfrag, const void* x, void* y, hipStream_t s)
 {
     switch (d.Ci / 32) {
     case 1: return launch_ks<T, TO, 1>(d, c, wfrag, x, y, s);
@@ -386,7 +387,7 @@ rtoss_status launch_pack_stream1x1(const rtoss_wdesc& d, const void* w, const ui
     return check_hip(hipGetLastError(), "pack stream1x1 launch");
 }
 
-rtoss_status launch_conv1x1_stream(const rtoss_wdesc& d, const rtoss_cdesc& c, const void* section, const void* x, void* y,
+rtoss_status launch_conv1x1_stream(const rtoss_wdesc& d, const ConvParams& c, const void* section, const void* x, void* y,
                                    hipStream_t s)
 {
     const char* wf = (const char*)section;

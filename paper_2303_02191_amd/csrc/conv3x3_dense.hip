@@ -27,6 +27,7 @@
 
 #include "common.h"
 #include "dtypes.h"
+#include "epilogue.h"
 #include "mma.h"
 #include "pack_live.h"
 #include "tile3x3.h"
@@ -107,7 +108,7 @@ template <typename T, typename TO, int S>
 __global__ __launch_bounds__(256) void conv3x3_dense_kernel(const T* __restrict__ x, TO* __restrict__ y,
                                                             const char* __restrict__ wfrag, const char* __restrict__ zeros,
                                                             int H, int W, int Ci, int Co, int Ho, int Wo, int cblocks,
-                                                            int tiles_c, int relu)
+                                                            int tiles_c, Epilogue ep)
 {
     using G = Geom<S, 4, 4>;
     constexpr int A_BYTES = kBlockBytes;
@@ -182,7 +183,6 @@ __global__ __launch_bounds__(256) void conv3x3_dense_kernel(const T* __restrict_
     }
 
     // ---- store: 16 consecutive channels of this lane's position in each of its blocks ----
-    const float relu_floor = relu ? 0.f : -__builtin_inff();
     const int co_lane = cb * (16 * kTM) + 16 * qq;
     constexpr int EB = (int)sizeof(TO);
 #pragma unroll
@@ -195,7 +195,9 @@ __global__ __launch_bounds__(256) void conv3x3_dense_kernel(const T* __restrict_
 #pragma unroll
         for (int m = 0; m < kTM; ++m)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[4 * m + e] = __builtin_fmaxf(acc[m][j][e], relu_floor);  // fused ReLU, or max with -inf
+            for (int e = 0; e < 4; ++e) v[4 * m + e] = acc[m][j][e];
+        epi_scale_bias_act<16>(v, ep, co_lane);
+        epi_residual<TO, 16>(v, ep, yp - y);
         if constexpr (EB == 4) {
 #pragma unroll
             for (int g = 0; g < 4; ++g) *(f32x4*)(yp + 4 * g) = f32x4{v[4 * g], v[4 * g + 1], v[4 * g + 2], v[4 * g + 3]};
@@ -214,7 +216,7 @@ __global__ __launch_bounds__(256) void conv3x3_dense_kernel(const T* __restrict_
 }
 
 template <typename T, typename TO, int S>
-rtoss_status launch_stride(const rtoss_wdesc& d, const rtoss_cdesc& c, const char* wfrag, const void* x, void* y, hipStream_t s)
+rtoss_status launch_stride(const rtoss_wdesc& d, const ConvParams& c, const char* wfrag, const void* x, void* y, hipStream_t s)
 {
     using G = Geom<S, 4, 4>;
     const int Ho = (c.H + 2 - 3) / S + 1, Wo = (c.W + 2 - 3) / S + 1;
@@ -233,12 +235,12 @@ rtoss_status launch_stride(const rtoss_wdesc& d, const rtoss_cdesc& c, const cha
     if (c.N > 65535 || cblocks > 65535) return fail(RTOSS_ESHAPE, "conv: batch or channel count too large");
     dim3 grid((unsigned)(tiles_r * tiles_c), (unsigned)cblocks, (unsigned)c.N), block(256);
     kern<<<grid, block, smem, s>>>((const T*)x, (TO*)y, wfrag, wfrag + frag_bytes(d), c.H, c.W, d.Ci, d.Co, Ho, Wo, cblocks,
-                                   tiles_c, c.fuse_relu);
+                                   tiles_c, c.ep);
     return check_hip(hipGetLastError(), "conv3x3 dense launch");
 }
 
 template <typename T, typename TO>
-rtoss_status launch_typed(const rtoss_wdesc& d, const rtoss_cdesc& c, const char* wfrag, const void* x, void* y, hipStream_t s)
+rtoss_status launch_typed(const rtoss_wdesc& d, const ConvParams& c, const char* wfrag, const void* x, void* y, hipStream_t s)
 {
     if (c.stride == 1) return launch_stride<T, TO, 1>(d, c, wfrag, x, y, s);
     return launch_stride<T, TO, 2>(d, c, wfrag, x, y, s);
@@ -270,7 +272,7 @@ rtoss_status launch_pack_dense3x3(const rtoss_wdesc& d, const void* w, const uin
     return check_hip(hipGetLastError(), "pack dense3x3 launch");
 }
 
-rtoss_status launch_conv3x3_dense(const rtoss_wdesc& d, const rtoss_cdesc& c, const void* section, const void* x, void* y,
+rtoss_status launch_conv3x3_dense(const rtoss_wdesc& d, const ConvParams& c, const void* section, const void* x, void* y,
                                   hipStream_t s)
 {
     const char* wf = (const char*)section;

@@ -35,6 +35,7 @@
 
 #include "common.h"
 #include "dtypes.h"
+#include "epilogue.h"
 #include "mma.h"
 #include "pack_live.h"
 #include "tile3x3.h"
@@ -176,7 +177,7 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
                                                                 const char* __restrict__ wfrag,
                                                                 const char* __restrict__ zeros, int H, int W, int Ci,
                                                                 int Co, int Ho, int Wo, int m_tiles_total,
-                                                                int tiles_c, int relu)
+                                                                int tiles_c, Epilogue ep)
 {
     using G = Geom<S, RT, CT>;
     static_assert(RT * CT == 4 * TN, "four waves share the position blocks of a workgroup");
@@ -312,13 +313,10 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
         for (int m = 0; m < TM; ++m) {
             const int co = 16 * (mt0 + m) + 4 * qq;
             if (co >= Co) continue;
-            f32x4 v = acc[m][j];
-            if (relu) {
-                v.x = v.x > 0.f ? v.x : 0.f;
-                v.y = v.y > 0.f ? v.y : 0.f;
-                v.z = v.z > 0.f ? v.z : 0.f;
-                v.w = v.w > 0.f ? v.w : 0.f;
-            }
+            float vv[4] = {acc[m][j].x, acc[m][j].y, acc[m][j].z, acc[m][j].w};
+            epi_scale_bias_act<4>(vv, ep, co);
+            epi_residual<TO, 4>(vv, ep, (yp - y) + co);
+            const f32x4 v = {vv[0], vv[1], vv[2], vv[3]};
             if constexpr (sizeof(TO) == 4) {
                 *(f32x4*)(yp + co) = v;
             } else {
@@ -333,13 +331,15 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
     }
 }
 
-template <typename T, typename TO, int S, int TM, int TN, int RT, int CT>
+// FUSED: scale / bias / SiLU / residual in the epilogue.  The plain instantiation (ReLU or nothing) keeps
+// its branch-free epilogue; the fused one pays for generality with a few uniform branches per tile.
+template <typename T, typename TO, int S, int TM, int TN, int RT, int CT, bool FUSED>
 __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restrict__ x, TO* __restrict__ y,
                                                                 const char* __restrict__ wfrag,
                                                                 const char* __restrict__ zeros, int H, int W, int Ci,
                                                                 int Co, int Ho, int Wo, int m_tiles_total,
                                                                 int tiles_c, int tiles_per_img, int co_blocks,
-                                                                int total_work, int work_per_xcd, int relu)
+                                                                int total_work, int work_per_xcd, Epilogue ep)
 {
     using G = Geom<S, RT, CT>;
     static_assert(RT * CT == 4 * TN, "four waves share the position blocks of a workgroup");
@@ -611,7 +611,7 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
         const int nn_e = lane_e & 15, qq_e = lane_e >> 4;
         // 64-bit address of the tile's first output element once; everything else is 32-bit
         TO* const y_tile = y + (((int64_t)t_n * Ho + t_oh0) * Wo + t_ow0) * Co;
-        const float relu_floor = relu ? 0.f : -__builtin_inff();
+        const float relu_floor = ep.act == 1 ? 0.f : -__builtin_inff();
         if constexpr (kDirectEpilogue) {
             // straight from the D fragments: 4 consecutive channels per lane and store
             const int pr_e = nn_e >> 2, pc_e = nn_e & 3;
@@ -656,14 +656,32 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
                 for (int mm = 0; mm < TMH; ++mm) vals[mm] = acc[h * TMH + mm][j];
                 // fused ReLU without a branch: max with 0, or with -inf when ReLU is off (one v_max_f32 per
                 // value, written as asm so that no NaN-quieting pass is put in front of it)
+                if constexpr (FUSED) {
+                    // this lane's position in block j and its 4 consecutive channels of every channel tile
+                    const int blk_f = blk0 + j;
+                    const int dr_f = 4 * (blk_f / CT) + (nn_e >> 2), dc_f = 4 * (blk_f % CT) + (nn_e & 3);
+                    const bool inside_f = t_oh0 + dr_f < Ho && t_ow0 + dc_f < Wo;
+                    const int64_t pos_f = (y_tile - y) + (int64_t)(dr_f * Wo + dc_f) * Co;
 #pragma unroll
-                for (int mm = 0; mm < TMH; ++mm)
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        float r;
-                        asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(vals[mm][e]), "v"(relu_floor));
-                        vals[mm][e] = r;
+                    for (int mm = 0; mm < TMH; ++mm) {
+                        const int co4 = 16 * (t_mt0 + h * TMH + mm) + 4 * qq_e;
+                        if (inside_f && co4 < Co) {
+                            float vv[4] = {vals[mm].x, vals[mm].y, vals[mm].z, vals[mm].w};
+                            epi_scale_bias_act<4>(vv, ep, co4);
+                            epi_residual<TO, 4>(vv, ep, pos_f + co4);
+                            vals[mm] = f32x4{vv[0], vv[1], vv[2], vv[3]};
+                        }
                     }
+                } else {
+#pragma unroll
+                    for (int mm = 0; mm < TMH; ++mm)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            float r;
+                            asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(vals[mm][e]), "v"(relu_floor));
+                            vals[mm][e] = r;
+                        }
+                }
 #pragma unroll
                 for (int mm = 0; mm < TMH; ++mm) {
                     char* dst = stage_out + (jj * 16 + nn_e) * ROW + (16 * mm + 4 * qq_e) * EB;
@@ -714,8 +732,10 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
   }
 }
 
-template <typename T, typename TO, int S, int TM, int TN, int RT, int CT>
-rtoss_status launch_variant(const rtoss_wdesc& d, const rtoss_cdesc& c, const char* wfrag, const void* x, void* y,
+inline bool needs_fused_stage(const ConvParams& c) { return c.ep.scale || c.ep.bias || c.ep.residual || c.ep.act > 1; }
+
+template <typename T, typename TO, int S, int TM, int TN, int RT, int CT, bool FUSED>
+rtoss_status launch_variant_f(const rtoss_wdesc& d, const ConvParams& c, const char* wfrag, const void* x, void* y,
                             hipStream_t s)
 {
     using G = Geom<S, RT, CT>;
@@ -725,7 +745,7 @@ rtoss_status launch_variant(const rtoss_wdesc& d, const rtoss_cdesc& c, const ch
     const int co_blocks = ((d.Co + 15) / 16 + TM - 1) / TM;
     constexpr int x_copies_per_wave = ((G::x_bytes / 16 + 63) / 64 + 3) / 4;
     const size_t smem = 2 * ((size_t)TM * kTileBytes + (size_t)x_copies_per_wave * 4096);
-    auto kern = conv3x3_sparse_kernel<T, TO, S, TM, TN, RT, CT>;
+    auto kern = conv3x3_sparse_kernel<T, TO, S, TM, TN, RT, CT, FUSED>;
     static bool attr_set = false;  // per instantiation
     if (!attr_set) {
         if (rtoss_status st = check_hip(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem),
@@ -749,12 +769,22 @@ rtoss_status launch_variant(const rtoss_wdesc& d, const rtoss_cdesc& c, const ch
     dim3 grid((unsigned)(slots_per_xcd * 8)), block(256);
     const char* zeros = wfrag + fragment_bytes(d);
     kern<<<grid, block, smem, s>>>((const T*)x, (TO*)y, wfrag, zeros, c.H, c.W, d.Ci, d.Co, Ho, Wo, m_tiles_total,
-                                   tiles_c, tiles_r * tiles_c, co_blocks, (int)total, work_per_xcd, c.fuse_relu);
+                                   tiles_c, tiles_r * tiles_c, co_blocks, (int)total, work_per_xcd, c.ep);
     return check_hip(hipGetLastError(), "conv3x3 sparse launch");
 }
 
 template <typename T, typename TO, int S, int TM, int TN, int RT, int CT>
-rtoss_status launch_variant_sb(const rtoss_wdesc& d, const rtoss_cdesc& c, const char* wfrag, const void* x, void* y,
+rtoss_status launch_variant(const rtoss_wdesc& d, const ConvParams& c, const char* wfrag, const void* x, void* y,
+                            hipStream_t s)
+{
+    if constexpr (TN == 4) {  // (the fused output stage is instantiated for the 16x16 tile only)
+        if (needs_fused_stage(c)) return launch_variant_f<T, TO, S, TM, TN, RT, CT, true>(d, c, wfrag, x, y, s);
+    }
+    return launch_variant_f<T, TO, S, TM, TN, RT, CT, false>(d, c, wfrag, x, y, s);
+}
+
+template <typename T, typename TO, int S, int TM, int TN, int RT, int CT>
+rtoss_status launch_variant_sb(const rtoss_wdesc& d, const ConvParams& c, const char* wfrag, const void* x, void* y,
                             hipStream_t s)
 {
     using G = Geom<S, RT, CT>;
@@ -775,12 +805,12 @@ rtoss_status launch_variant_sb(const rtoss_wdesc& d, const rtoss_cdesc& c, const
     if (c.N > 65535 || co_blocks > 65535) return fail(RTOSS_ESHAPE, "conv: batch or channel count too large");
     dim3 grid((unsigned)(tiles_r * tiles_c), (unsigned)co_blocks, (unsigned)c.N), block(256);
     kern<<<grid, block, smem, s>>>((const T*)x, (TO*)y, wfrag, wfrag + fragment_bytes(d), c.H, c.W, d.Ci, d.Co, Ho, Wo,
-                                   m_tiles_total, tiles_c, c.fuse_relu);
+                                   m_tiles_total, tiles_c, c.ep);
     return check_hip(hipGetLastError(), "conv3x3 sparse launch");
 }
 
 template <typename T, typename TO>
-rtoss_status launch_typed(const rtoss_wdesc& d, const rtoss_cdesc& c, const char* wfrag, const void* x, void* y,
+rtoss_status launch_typed(const rtoss_wdesc& d, const ConvParams& c, const char* wfrag, const void* x, void* y,
                           hipStream_t s)
 {
     // The fragment section is padded to a multiple of 8 channel tiles, so any TM <= 8 may over-read rows
@@ -805,7 +835,7 @@ rtoss_status launch_typed(const rtoss_wdesc& d, const rtoss_cdesc& c, const char
         const int64_t slots = 256;
         const double cost4 = (double)((t4 + slots - 1) / slots) * 4.0, cost5 = (double)((t5 + slots - 1) / slots) * 4.85;
         // (with few stages per tile the taller tile's longer prologue and epilogue outweigh the saved round)
-        if (cost5 < cost4 && d.Ci >= 128) return launch_variant<T, TO, 1, 8, 5, 5, 4>(d, c, wfrag, x, y, s);
+        if (cost5 < cost4 && d.Ci >= 128 && !needs_fused_stage(c)) return launch_variant<T, TO, 1, 8, 5, 5, 4>(d, c, wfrag, x, y, s);
         return launch_variant<T, TO, 1, 8, 4, 4, 4>(d, c, wfrag, x, y, s);
     }
     // Stride 2: the input tile of a 16x16 output tile (33x33 positions) nearly fills the LDS by itself.
@@ -852,7 +882,7 @@ rtoss_status launch_pack_sparse3x3(const rtoss_wdesc& d, const void* w, const ui
     return check_hip(hipGetLastError(), "pack sparse3x3 launch");
 }
 
-rtoss_status launch_conv3x3_sparse(const rtoss_wdesc& d, const rtoss_cdesc& c, const void* section, const void* x,
+rtoss_status launch_conv3x3_sparse(const rtoss_wdesc& d, const ConvParams& c, const void* section, const void* x,
                                    void* y, hipStream_t s)
 {
     const char* wf = (const char*)section;

@@ -12,6 +12,7 @@
 // holds column r, K = 8q..8q+7; D lane holds column r, rows 4q..4q+3.
 #include "common.h"
 #include "dtypes.h"
+#include "epilogue.h"
 #include "mma.h"
 #include "pack_live.h"
 
@@ -72,7 +73,7 @@ __global__ __launch_bounds__(256) void pack_stem_kernel(const T* __restrict__ w,
 template <typename T, typename TO, int S, int TM>
 __global__ __launch_bounds__(256) void conv3x3_stem_kernel(const T* __restrict__ x, TO* __restrict__ y,
                                                            const char* __restrict__ wfrag, int H, int W, int Ci, int Co,
-                                                           int Ho, int Wo, int tiles_c, int relu)
+                                                           int Ho, int Wo, int tiles_c, Epilogue ep)
 {
     constexpr int IH = (kTH - 1) * S + 3, IW = (kTW - 1) * S + 3;
     constexpr int MAXROW = IW * 3 + 1;  // halves per staged row (Ci <= 3), odd pitch
@@ -124,13 +125,13 @@ __global__ __launch_bounds__(256) void conv3x3_stem_kernel(const T* __restrict__
         TO* yp = y + (((int64_t)n_img * Ho + oh) * Wo + ow) * Co;
 #pragma unroll
         for (int m = 0; m < TM; ++m) {
-            f32x4 v = Dense16<T>::mma(afrag[m], b, f32x4{0.f, 0.f, 0.f, 0.f});
-            v.x = relu ? __builtin_fmaxf(v.x, 0.f) : v.x;
-            v.y = relu ? __builtin_fmaxf(v.y, 0.f) : v.y;
-            v.z = relu ? __builtin_fmaxf(v.z, 0.f) : v.z;
-            v.w = relu ? __builtin_fmaxf(v.w, 0.f) : v.w;
+            const f32x4 d4 = Dense16<T>::mma(afrag[m], b, f32x4{0.f, 0.f, 0.f, 0.f});
             const int co = 16 * m + 4 * qq;
             if (inside && co < Co) {
+                float vv[4] = {d4.x, d4.y, d4.z, d4.w};
+                epi_scale_bias_act<4>(vv, ep, co);
+                epi_residual<TO, 4>(vv, ep, (yp - y) + co);
+                const f32x4 v = {vv[0], vv[1], vv[2], vv[3]};
                 if constexpr (sizeof(TO) == 4) {
                     *(f32x4*)(yp + co) = v;
                 } else {
@@ -145,19 +146,19 @@ __global__ __launch_bounds__(256) void conv3x3_stem_kernel(const T* __restrict__
 }
 
 template <typename T, typename TO, int S, int TM>
-rtoss_status launch_stem(const rtoss_wdesc& d, const rtoss_cdesc& c, const char* wfrag, const void* x, void* y, hipStream_t s)
+rtoss_status launch_stem(const rtoss_wdesc& d, const ConvParams& c, const char* wfrag, const void* x, void* y, hipStream_t s)
 {
     const int Ho = (c.H + 2 - 3) / S + 1, Wo = (c.W + 2 - 3) / S + 1;
     const int tiles_r = (Ho + kTH - 1) / kTH, tiles_c = (Wo + kTW - 1) / kTW;
     if (c.N > 65535) return fail(RTOSS_ESHAPE, "conv: batch too large");
     dim3 grid((unsigned)(tiles_r * tiles_c), (unsigned)c.N), block(256);
     conv3x3_stem_kernel<T, TO, S, TM><<<grid, block, 0, s>>>((const T*)x, (TO*)y, wfrag, c.H, c.W, d.Ci, d.Co, Ho, Wo, tiles_c,
-                                                             c.fuse_relu);
+                                                             c.ep);
     return check_hip(hipGetLastError(), "conv3x3 stem launch");
 }
 
 template <typename T, typename TO>
-rtoss_status launch_typed(const rtoss_wdesc& d, const rtoss_cdesc& c, const char* wfrag, const void* x, void* y, hipStream_t s)
+rtoss_status launch_typed(const rtoss_wdesc& d, const ConvParams& c, const char* wfrag, const void* x, void* y, hipStream_t s)
 {
     const int tiles = (d.Co + 15) / 16;
     if (c.stride == 1) {
@@ -189,7 +190,7 @@ rtoss_status launch_pack_stem3x3(const rtoss_wdesc& d, const void* w, const uint
     return check_hip(hipGetLastError(), "pack stem launch");
 }
 
-rtoss_status launch_conv3x3_stem(const rtoss_wdesc& d, const rtoss_cdesc& c, const void* section, const void* x, void* y,
+rtoss_status launch_conv3x3_stem(const rtoss_wdesc& d, const ConvParams& c, const void* section, const void* x, void* y,
                                  hipStream_t s)
 {
     const char* wf = (const char*)section;

@@ -15,6 +15,7 @@
 // activation reads per pair, with no dependent global loads in flight.
 #include "common.h"
 #include "dtypes.h"
+#include "epilogue.h"
 
 namespace rtoss {
 
@@ -37,7 +38,7 @@ template <typename T, typename TO, int KS, int S, int KK>
 __global__ __launch_bounds__(256) void conv_direct_kernel(const T* __restrict__ x, TO* __restrict__ y,
                                                           const T* __restrict__ live, const uint8_t* __restrict__ lidx,
                                                           Dict dict, int N, int H, int W, int Ci, int Co, int Ho, int Wo,
-                                                          int tiles_w, int relu, int64_t G)
+                                                          int tiles_w, Epilogue ep, int64_t G)
 {
     using HL = Halo<KS, S>;
     constexpr int WS = KS == 1 ? 1 : (KK ? KK : 9);  // weights (and offsets) stored per pair
@@ -143,7 +144,10 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(const T* __restrict__ 
             const int co = co_block + wave * kCoPerWave + i;
             if (co < Co) {
                 float v = acc[i];
-                if (relu) v = v > 0.f ? v : 0.f;
+                if (ep.scale) v *= ep.scale[co];
+                if (ep.bias) v += ep.bias[co];
+                v = epi_act(v, ep.act);
+                if (ep.residual) v += to_f32(((const TO*)ep.residual)[(yp - y) + co]);
                 store_from_f32<TO>(yp + co, v);
             }
         }
@@ -151,7 +155,7 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(const T* __restrict__ 
 }
 
 template <typename T, typename TO>
-static rtoss_status launch_typed(const rtoss_wdesc& d, const rtoss_cdesc& c, const Dict& dict, const void* live,
+static rtoss_status launch_typed(const rtoss_wdesc& d, const ConvParams& c, const Dict& dict, const void* live,
                                  const uint8_t* lidx, const void* x, void* y, hipStream_t s)
 {
     const int Ho = (c.H + 2 * c.pad - d.ksize) / c.stride + 1;
@@ -164,7 +168,7 @@ static rtoss_status launch_typed(const rtoss_wdesc& d, const rtoss_cdesc& c, con
     dim3 block(256);
 #define RTOSS_LAUNCH(KS, S, KK)                                                                                  \
     conv_direct_kernel<T, TO, KS, S, KK><<<grid, block, 0, s>>>((const T*)x, (TO*)y, (const T*)live, lidx, dict, c.N, \
-                                                                c.H, c.W, d.Ci, d.Co, Ho, Wo, tiles_w, c.fuse_relu, G)
+                                                                c.H, c.W, d.Ci, d.Co, Ho, Wo, tiles_w, c.ep, G)
 #define RTOSS_LAUNCH3(S)                  \
     switch (dict.k) {                     \
     case 2: RTOSS_LAUNCH(3, S, 2); break; \
@@ -181,7 +185,7 @@ static rtoss_status launch_typed(const rtoss_wdesc& d, const rtoss_cdesc& c, con
     return check_hip(hipGetLastError(), "conv launch");
 }
 
-rtoss_status launch_conv_direct(const rtoss_wdesc& d, const rtoss_cdesc& c, const Dict& dict, const void* live_values,
+rtoss_status launch_conv_direct(const rtoss_wdesc& d, const ConvParams& c, const Dict& dict, const void* live_values,
                                 const uint8_t* live_idx, const void* x, void* y, hipStream_t s)
 {
     const bool f32out = c.out_dt == RTOSS_F32;

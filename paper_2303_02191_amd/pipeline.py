@@ -106,3 +106,23 @@ class PackedLayer:
         B.rtoss_conv2d_pattern(self.wdesc, cdesc, self.masks, self.blob.data_ptr(), x.data_ptr(), y.data_ptr(),
                                _stream())
         return y
+
+    def conv_fused(self, x, stride=1, scale=None, bias=None, act=B.ACT_NONE, residual=None, out_dt=None, y=None):
+        """y = act(scale[co] * conv + bias[co]) + residual.  scale/bias: float32 cuda tensors [Co] or None;
+        residual: cuda tensor of y's dtype and shape or None."""
+        assert x.is_cuda and x.is_contiguous() and x.shape[3] == self.wdesc.Ci
+        out_dt = self.dt if out_dt is None else out_dt
+        if y is None:
+            y = torch.empty(self.out_shape(x.shape, stride), dtype=TORCH_DTYPE[out_dt], device=x.device)
+        for t in (scale, bias):
+            assert t is None or (t.is_cuda and t.dtype == torch.float32 and t.numel() == self.wdesc.Co)
+        assert residual is None or (residual.is_cuda and residual.is_contiguous() and residual.shape == y.shape
+                                    and residual.dtype == y.dtype)
+        N, H, W, _ = x.shape
+        cdesc = B.CDesc(N, H, W, stride, self.wdesc.ksize // 2, B.NHWC, out_dt, 0)
+        ep = B.EpilogueDesc(scale.data_ptr() if scale is not None else None, bias.data_ptr() if bias is not None else None,
+                            int(act), residual.data_ptr() if residual is not None else None)
+        B.rtoss_conv2d_pattern_fused(self.wdesc, cdesc, ep, self.masks, self.blob.data_ptr(), x.data_ptr(), y.data_ptr(),
+                                     _stream())
+        return y
+

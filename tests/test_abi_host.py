@@ -166,3 +166,25 @@ def test_batched_select_argument_errors():
     B.rtoss_select_patterns_batch([], B.F16, masks)             # nothing to do
     B.rtoss_select_patterns_batch([(0, 8, 0)], B.F16, masks)    # fewer than 9 weights: no group, no launch
 
+
+def test_fused_conv_argument_errors():
+    masks = B.rtoss_pattern_dict(2)
+    wd = B.WDesc(32, 32, 3, 2, B.F16)
+    ok = B.CDesc(1, 8, 8, 1, 1, B.NHWC, B.F16, 0)
+    good = B.EpilogueDesc(None, None, B.ACT_SILU, None)
+    with pytest.raises(B.RtossError) as e:
+        B.rtoss_conv2d_pattern_fused(wd, ok, None, masks, 256, 512, 1024)
+    assert e.value.status == B.EINVAL
+    with pytest.raises(B.RtossError) as e:  # fuse_relu together with an epilogue
+        B.rtoss_conv2d_pattern_fused(wd, B.CDesc(1, 8, 8, 1, 1, B.NHWC, B.F16, 1), good, masks, 256, 512, 1 << 20)
+    assert e.value.status == B.EINVAL
+    with pytest.raises(B.RtossError) as e:  # unknown activation
+        B.rtoss_conv2d_pattern_fused(wd, ok, B.EpilogueDesc(None, None, 9, None), masks, 256, 512, 1 << 20)
+    assert e.value.status == B.EINVAL
+    with pytest.raises(B.RtossError) as e:  # misaligned scale
+        B.rtoss_conv2d_pattern_fused(wd, ok, B.EpilogueDesc(4, None, 0, None), masks, 256, 512, 1 << 20)
+    assert e.value.status == B.EINVAL
+    with pytest.raises(B.RtossError) as e:  # residual overlapping the output
+        B.rtoss_conv2d_pattern_fused(wd, ok, B.EpilogueDesc(None, None, 0, (1 << 20) + 64), masks, 256, 512, 1 << 20)
+    assert e.value.status == B.EINVAL
+

@@ -98,3 +98,29 @@ def test_points_match_full():
     pts = np.array([[0, 0, 0, 0], [1, 4, 4, 4], [0, 2, 3, 1], [1, 1, 0, 4]], dtype=np.int32)
     got = oracle.conv2d_points(x, w, pts, stride=2, relu=True)
     assert np.array_equal(got, y[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]])
+
+
+def test_fused_output_stage_against_library_and_closed_form():
+    # y = act(scale * conv + bias) + residual, against torch's float64 CPU routines ...
+    import torch
+    import torch.nn.functional as F
+    rng = np.random.default_rng(77)
+    x = rng.standard_normal((2, 5, 9, 8))
+    w = rng.standard_normal((7, 5, 3, 3)) * 0.3
+    scale, bias = rng.uniform(0.5, 1.5, 7), rng.standard_normal(7)
+    for stride in (1, 2):
+        base = F.conv2d(torch.from_numpy(x), torch.from_numpy(w), stride=stride, padding=1)
+        res = rng.standard_normal(tuple(base.shape))
+        lin = base * torch.from_numpy(scale).view(1, 7, 1, 1) + torch.from_numpy(bias).view(1, 7, 1, 1)
+        for act, f in [(oracle.ACT_NONE, lambda t: t), (oracle.ACT_RELU, F.relu), (oracle.ACT_SILU, F.silu)]:
+            want = (f(lin) + torch.from_numpy(res)).numpy()
+            got = oracle.conv2d_fused(x, w, stride=stride, scale=scale, bias=bias, act=act, residual=res)
+            assert np.max(np.abs(got - want)) < 1e-12
+    # ... and a closed form: a 1x1 identity convolution leaves silu(s * x + b) + r
+    x = np.array([[[[0.0, 1.0, -2.0]]]])
+    got = oracle.conv2d_fused(x, np.ones((1, 1, 1, 1)), scale=[2.0], bias=[0.0], act=oracle.ACT_SILU, residual=np.full((1, 1, 1, 3), 0.5))
+    want = np.array([0.0, 2.0 / (1.0 + np.exp(-2.0)), -4.0 / (1.0 + np.exp(4.0))]) + 0.5
+    assert np.allclose(got.reshape(-1), want, rtol=0, atol=1e-15)
+    # without any stage it is the plain convolution
+    assert np.array_equal(oracle.conv2d_fused(x, np.ones((1, 1, 1, 1))), oracle.conv2d(x, np.ones((1, 1, 1, 1))))
+
