@@ -20,13 +20,33 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
+def _compile_one(args):
+    hipcc, src, obj = args
+    flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    cmd = [hipcc] + flags + ["-I", os.path.join(ROOT, "include"), "-I", CSRC, "-c", src, "-o", obj]
+    subprocess.check_call(cmd)
+    return obj
+
+
 def build_library(verbose=True):
+    """Compiles every source to an object (in parallel: the files are independent) and links them."""
+    import tempfile
+    from concurrent.futures import ThreadPoolExecutor
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     tmp = LIB + ".tmp%d" % os.getpid()
-    cmd = [hipcc] + HIPCC_FLAGS + ["-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", tmp] + sources()
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.check_call(cmd)
+    srcs = sources()
+    jobs = max(1, min(len(srcs), int(os.environ.get("MAX_JOBS", "0")) or (os.cpu_count() or 4), 8))
+    with tempfile.TemporaryDirectory(prefix="rtoss_build_") as objdir:
+        work = [(hipcc, s, os.path.join(objdir, os.path.basename(s) + ".o")) for s in srcs]
+        if verbose:
+            print("hipcc %s -c {%s}  (%d jobs)" % (" ".join(f for f in HIPCC_FLAGS if f != "-shared"),
+                                                 ", ".join(os.path.basename(s) for s in srcs), jobs), flush=True)
+        with ThreadPoolExecutor(max_workers=jobs) as pool:
+            objs = list(pool.map(_compile_one, work))
+        link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs
+        if verbose:
+            print(" ".join(link[:6]) + " <%d objects>" % len(objs), flush=True)
+        subprocess.check_call(link)
     os.replace(tmp, LIB)
     return LIB
 
