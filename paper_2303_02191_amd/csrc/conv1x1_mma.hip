@@ -1,5 +1,7 @@
 // 1x1 pattern-pruned convolution on the CDNA4 matrix cores (fp16 / bf16, fp32 accumulate),
-// and the packer that writes its weight fragments.
+// and the packer that writes its weight fragments: the general kernel, for any input channel
+// count that is a multiple of 32.  (Channel counts of the form 32 * 2^n up to 1024 take the
+// streaming kernel with register-resident weights instead.)
 //
 // Section IV.D prunes a 1x1 layer by cutting the flattened [Co][Ci] weight matrix into groups
 // of 9 and keeping k weights per group, so the pruned layer is a GEMM

@@ -26,11 +26,15 @@
 // (RT x CT) blocks of 4x4 output positions; every wave owns all 16*TM channels and TN of
 // the position blocks.  K runs over stages of 32 input channels: the stage's weight
 // fragments (one contiguous chunk of the packed blob) and its activation tile with halo
-// (channels-last, 32 channels per position, 80-byte position stride) are prefetched from
-// global memory into registers while the previous stage is multiplied, then parked in
-// LDS.  B operands are read from LDS as 16-byte vectors (8 channels of one tap) and the
-// 4x4 (tap, channel) blocks are transposed in registers with byte permutes so that one
-// lane holds, for 4 channels, the 4 taps of a group.
+// (channels-last, 32 channels per position, 80-byte position stride) are copied global ->
+// LDS without passing through registers.  B operands are read from LDS as 16-byte vectors
+// (8 channels of one tap) and the 4x4 (tap, channel) blocks are transposed in registers
+// with byte permutes so that one lane holds, for 4 channels, the 4 taps of a group.
+//
+// Two kernels share that data flow.  The pipelined one (large layers, stride 1) keeps two
+// LDS buffers, one persistent workgroup per compute unit and a hand-placed schedule of
+// matrix instructions, LDS reads, permutes and copies.  The single-buffered one (stride 2,
+// small layers) is a plain loop nest with small tiles, several workgroups per compute unit.
 #include <algorithm>
 
 #include "common.h"
