@@ -148,26 +148,6 @@ def main():
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
 
-    # Selection and packing of different layers are independent (they read weights only), so their
-    # launches are spread over a few streams that fork from and join the current one: in a captured
-    # graph these become parallel branches and the small kernels overlap instead of queueing behind
-    # each other.  The convolutions stay in one stream, in layer order, as a network runs them.
-    side = [torch.cuda.Stream() for _ in range(4)] if len(cfg.layers) > 8 else []
-
-    def fanned_out(calls):
-        """calls: functions taking a raw stream handle; run round-robin over the side streams."""
-        main = torch.cuda.current_stream()
-        if not side:
-            for f in calls:
-                f(main.cuda_stream)
-            return
-        for st in side:
-            st.wait_stream(main)
-        for i, f in enumerate(calls):
-            f(side[i % len(side)].cuda_stream)
-        for st in side:
-            main.wait_stream(st)
-
     def do_select():
         # one batched call: all 3x3 kernels as one tensor, every 1x1 tensor as an item of its own
         items = []
@@ -179,8 +159,7 @@ def main():
         B.rtoss_select_patterns_batch(items, cfg.dtype, masks, torch.cuda.current_stream().cuda_stream)
 
     def do_pack():
-        fanned_out([lambda st, lay=lay, w=w, idx=idx: lay.pack(w, idx, stream=st)
-                    for lay, w, idx in zip(layers, w_dev, idx_dev)])
+        pl.pack_layers(layers, w_dev, idx_dev)  # one batched call: a launch per (format, dtype) group of layers
 
     def do_conv():
         for L, lay, x, y in zip(cfg.layers, layers, xs, ys):

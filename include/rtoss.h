@@ -207,6 +207,25 @@ rtoss_status rtoss_pack(const rtoss_wdesc* desc, const void* w_dev, const uint8_
                         void* packed_dev, size_t packed_bytes,
                         void* workspace_dev, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * rtoss_pack for several layers of one model that share a dictionary, in as few launches as
+ * possible (layers whose private section has the same format and dtype are packed by one
+ * launch).  Each item is packed exactly as by rtoss_pack; no workspace is needed.
+ *
+ *   items_host  n_items entries {desc, w_dev, idx_dev, packed_dev, packed_bytes} with the meaning
+ *               of rtoss_pack's arguments; the array is read before the call returns
+ * Errors: as rtoss_pack (the message names the item); nothing is launched if any item is invalid.
+ */
+typedef struct {
+    rtoss_wdesc desc;
+    const void* w_dev;
+    const uint8_t* idx_dev;
+    void* packed_dev;
+    size_t packed_bytes;
+} rtoss_pack_item;
+rtoss_status rtoss_pack_batch(const rtoss_pack_item* items_host, int n_items,
+                              const uint16_t* masks_host, int P, void* hip_stream);
+
 /* One convolution call. */
 typedef struct {
     int N, H, W;         /* batch, input height, input width */

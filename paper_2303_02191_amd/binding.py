@@ -44,12 +44,17 @@ class EpilogueDesc(ctypes.Structure):
                 ("residual_dev", ctypes.c_void_p)]
 
 
+class PackItemDesc(ctypes.Structure):
+    _fields_ = [("desc", WDesc), ("w_dev", ctypes.c_void_p), ("idx_dev", ctypes.c_void_p), ("packed_dev", ctypes.c_void_p),
+                ("packed_bytes", ctypes.c_size_t)]
+
+
 class SelectItem(ctypes.Structure):
     _fields_ = [("w_dev", ctypes.c_void_p), ("n_elems", ctypes.c_int64), ("idx_dev", ctypes.c_void_p)]
 
 
 EXPORTS = ["rtoss_pattern_dict", "rtoss_select_patterns", "rtoss_select_patterns_batch", "rtoss_pattern_histogram", "rtoss_reduce_dict",
-           "rtoss_pack_size", "rtoss_pack", "rtoss_conv2d_pattern", "rtoss_conv2d_pattern_fused", "rtoss_last_error"]
+           "rtoss_pack_size", "rtoss_pack", "rtoss_pack_batch", "rtoss_conv2d_pattern", "rtoss_conv2d_pattern_fused", "rtoss_last_error"]
 
 
 def lib():
@@ -84,6 +89,8 @@ def lib():
         L.rtoss_pack.argtypes = [ctypes.POINTER(WDesc), vp, vp, u16p, i, vp, ctypes.c_size_t, vp, ctypes.c_size_t, vp]
         L.rtoss_conv2d_pattern.restype = i
         L.rtoss_conv2d_pattern.argtypes = [ctypes.POINTER(WDesc), ctypes.POINTER(CDesc), u16p, i, vp, vp, vp, vp]
+        L.rtoss_pack_batch.restype = i
+        L.rtoss_pack_batch.argtypes = [ctypes.POINTER(PackItemDesc), i, u16p, i, vp]
         L.rtoss_conv2d_pattern_fused.restype = i
         L.rtoss_conv2d_pattern_fused.argtypes = [ctypes.POINTER(WDesc), ctypes.POINTER(CDesc), ctypes.POINTER(EpilogueDesc),
                                                  u16p, i, vp, vp, vp, vp]
@@ -179,4 +186,16 @@ def rtoss_conv2d_pattern_fused(wdesc, cdesc, epilogue, masks, packed_ptr, x_ptr,
                                             ctypes.byref(cdesc) if cdesc is not None else None,
                                             ctypes.byref(epilogue) if epilogue is not None else None, mp, P,
                                             packed_ptr, x_ptr, y_ptr, stream))
+
+
+def rtoss_pack_batch(items, masks, stream=0):
+    """items: sequence of (wdesc, w_ptr, idx_ptr, packed_ptr, packed_bytes)."""
+    mp, P, _keep = _masks_arg(masks)
+    if items is None:
+        _check(lib().rtoss_pack_batch(None, 1, mp, P, stream))
+        return
+    arr = (PackItemDesc * max(len(items), 1))()
+    for i, (wd, w_ptr, idx_ptr, packed_ptr, packed_bytes) in enumerate(items):
+        arr[i] = PackItemDesc(wd, w_ptr, idx_ptr, packed_ptr, int(packed_bytes))
+    _check(lib().rtoss_pack_batch(arr, len(items), mp, P, stream))
 

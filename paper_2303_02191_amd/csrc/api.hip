@@ -260,6 +260,40 @@ rtoss_status rtoss_pack_size(const rtoss_wdesc* desc, const uint16_t* masks_host
     return RTOSS_OK;
 }
 
+// Validation shared by rtoss_pack and rtoss_pack_batch; fills the geometry and the section pointers.
+static rtoss_status check_pack(const rtoss_wdesc* desc, const Dict& dict, const void* w_dev, const uint8_t* idx_dev,
+                               void* packed_dev, size_t packed_bytes, BlobGeometry* g, PackItem* item)
+{
+    if (rtoss_status st = check_wdesc(desc)) return st;
+    if (dict.k != desc->k) return fail(RTOSS_EINVAL, "dictionary keeps %d taps, descriptor says k=%d", dict.k, desc->k);
+    if (rtoss_status st = blob_geometry(desc, dict, g)) return st;
+    if (!packed_dev) return fail(RTOSS_EINVAL, "packed_dev is NULL");
+    if (packed_bytes < g->total)
+        return fail(RTOSS_ENOSPACE, "packed buffer has %zu bytes, %zu needed", packed_bytes, g->total);
+    if (misaligned(packed_dev, 256)) return fail(RTOSS_EINVAL, "packed_dev is not 256-byte aligned");
+    if (g->G > 0 && (!w_dev || !idx_dev)) return fail(RTOSS_EINVAL, "w_dev or idx_dev is NULL");
+    if (misaligned(w_dev, elem_bytes(desc->dt))) return fail(RTOSS_EINVAL, "w_dev is not aligned to its element size");
+    char* blob = (char*)packed_dev;
+    item->d = *desc;
+    item->w = w_dev;
+    item->idx = idx_dev;
+    item->section = blob + g->mat_off;
+    item->live = blob + g->live_off;
+    item->live_idx = (uint8_t*)(blob + g->idx_off);
+    return RTOSS_OK;
+}
+
+// one launch per layer: the fragment packers also write the public section in their first blocks
+static rtoss_status pack_one(const PackItem& it, const BlobGeometry& g, const Dict& dict, hipStream_t s)
+{
+    if (g.format == kFormatSparse24) return launch_pack_sparse3x3(it.d, it.w, it.idx, dict, it.section, it.live, it.live_idx, s);
+    if (g.format == kFormatDense3x3) return launch_pack_dense3x3(it.d, it.w, it.idx, dict, it.section, it.live, it.live_idx, s);
+    if (g.format == kFormatDenseStream) return launch_pack_stream1x1(it.d, it.w, it.idx, dict, it.section, it.live, it.live_idx, s);
+    if (g.format == kFormatDense) return launch_pack_dense1x1(it.d, it.w, it.idx, dict, it.section, it.live, it.live_idx, s);
+    if (g.format == kFormatStem) return launch_pack_stem3x3(it.d, it.w, it.idx, dict, it.section, it.live, it.live_idx, s);
+    return launch_pack_live(it.d, it.w, it.idx, dict, it.live, it.live_idx, g.G, s);
+}
+
 rtoss_status rtoss_pack(const rtoss_wdesc* desc, const void* w_dev, const uint8_t* idx_dev, const uint16_t* masks_host,
                         int P, void* packed_dev, size_t packed_bytes, void* workspace_dev, size_t workspace_bytes,
                         void* hip_stream)
@@ -269,26 +303,46 @@ rtoss_status rtoss_pack(const rtoss_wdesc* desc, const void* w_dev, const uint8_
     if (rtoss_status st = check_wdesc(desc)) return st;
     Dict dict;
     if (rtoss_status st = load_dict(masks_host, P, &dict)) return st;
-    if (dict.k != desc->k) return fail(RTOSS_EINVAL, "dictionary keeps %d taps, descriptor says k=%d", dict.k, desc->k);
     BlobGeometry g;
-    if (rtoss_status st = blob_geometry(desc, dict, &g)) return st;
-    if (!packed_dev) return fail(RTOSS_EINVAL, "packed_dev is NULL");
-    if (packed_bytes < g.total)
-        return fail(RTOSS_ENOSPACE, "packed buffer has %zu bytes, %zu needed", packed_bytes, g.total);
-    if (misaligned(packed_dev, 256)) return fail(RTOSS_EINVAL, "packed_dev is not 256-byte aligned");
-    if (g.G > 0 && (!w_dev || !idx_dev)) return fail(RTOSS_EINVAL, "w_dev or idx_dev is NULL");
-    if (misaligned(w_dev, elem_bytes(desc->dt))) return fail(RTOSS_EINVAL, "w_dev is not aligned to its element size");
+    PackItem it;
+    if (rtoss_status st = check_pack(desc, dict, w_dev, idx_dev, packed_dev, packed_bytes, &g, &it)) return st;
+    return pack_one(it, g, dict, (hipStream_t)hip_stream);
+}
+
+rtoss_status rtoss_pack_batch(const rtoss_pack_item* items_host, int n_items, const uint16_t* masks_host, int P,
+                              void* hip_stream)
+{
+    if (n_items < 0) return fail(RTOSS_EINVAL, "n_items=%d is negative", n_items);
+    Dict dict;
+    if (rtoss_status st = load_dict(masks_host, P, &dict)) return st;
+    if (n_items == 0) return RTOSS_OK;
+    if (!items_host) return fail(RTOSS_EINVAL, "items_host is NULL");
+    std::vector<PackItem> items((size_t)n_items);
+    std::vector<BlobGeometry> geo((size_t)n_items);
+    for (int i = 0; i < n_items; ++i) {
+        const rtoss_pack_item& in = items_host[i];
+        if (rtoss_status st = check_pack(&in.desc, dict, in.w_dev, in.idx_dev, in.packed_dev, in.packed_bytes, &geo[i], &items[i])) {
+            std::string msg = rtoss_last_error();
+            return fail(st, "item %d: %s", i, msg.c_str());
+        }
+    }
     hipStream_t s = (hipStream_t)hip_stream;
-    char* blob = (char*)packed_dev;
-    void* live = blob + g.live_off;
-    uint8_t* live_idx = (uint8_t*)(blob + g.idx_off);
-    // one launch per layer: the fragment packers also write the public section in their first blocks
-    if (g.format == kFormatSparse24) return launch_pack_sparse3x3(*desc, w_dev, idx_dev, dict, blob + g.mat_off, live, live_idx, s);
-    if (g.format == kFormatDense3x3) return launch_pack_dense3x3(*desc, w_dev, idx_dev, dict, blob + g.mat_off, live, live_idx, s);
-    if (g.format == kFormatDenseStream) return launch_pack_stream1x1(*desc, w_dev, idx_dev, dict, blob + g.mat_off, live, live_idx, s);
-    if (g.format == kFormatDense) return launch_pack_dense1x1(*desc, w_dev, idx_dev, dict, blob + g.mat_off, live, live_idx, s);
-    if (g.format == kFormatStem) return launch_pack_stem3x3(*desc, w_dev, idx_dev, dict, blob + g.mat_off, live, live_idx, s);
-    return launch_pack_live(*desc, w_dev, idx_dev, dict, live, live_idx, g.G, s);
+    // layers of the two common formats go out in batched launches, per dtype; the rest one by one
+    for (int fmt : {(int)kFormatSparse24, (int)kFormatDenseStream})
+        for (int dt : {(int)RTOSS_F16, (int)RTOSS_BF16}) {
+            std::vector<PackItem> group;
+            for (int i = 0; i < n_items; ++i)
+                if ((int)geo[i].format == fmt && (int)items[i].d.dt == dt) group.push_back(items[i]);
+            if (group.empty()) continue;
+            const rtoss_status st = fmt == kFormatSparse24 ? launch_pack_sparse3x3_batch(group.data(), (int)group.size(), dict, s)
+                                                           : launch_pack_stream1x1_batch(group.data(), (int)group.size(), dict, s);
+            if (st) return st;
+        }
+    for (int i = 0; i < n_items; ++i) {
+        if (geo[i].format == kFormatSparse24 || geo[i].format == kFormatDenseStream) continue;
+        if (rtoss_status st = pack_one(items[i], geo[i], dict, s)) return st;
+    }
+    return RTOSS_OK;
 }
 
 static rtoss_status conv_impl(const rtoss_wdesc* desc, const rtoss_cdesc* c, const rtoss_epilogue* e,

@@ -73,6 +73,26 @@ rtoss_status launch_pack_live(const rtoss_wdesc& d, const void* w, const uint8_t
 rtoss_status launch_conv_direct(const rtoss_wdesc& d, const ConvParams& c, const Dict& dict, const void* live_values,
                                 const uint8_t* live_idx, const void* x, void* y, hipStream_t s);
 
+// Several layers packed by one launch (layers of one format and dtype; the table travels in the launch arguments).
+struct PackItem {
+    rtoss_wdesc d;
+    const void* w;
+    const uint8_t* idx;
+    void* section;      // private section of the blob
+    void* live;         // public section: values
+    uint8_t* live_idx;  // public section: indices
+};
+constexpr int kPackBatchMax = 24;
+// block -> (entry, block within the entry) for the batched kernels: first_block[t] <= block < first_block[t+1]
+template <typename Batch> __device__ __forceinline__ int batch_entry(const Batch& b, int block)
+{
+    int t = 0;
+    while (t + 1 < b.n && block >= b.first_block[t + 1]) ++t;
+    return t;
+}
+rtoss_status launch_pack_sparse3x3_batch(const PackItem* items, int n, const Dict& dict, hipStream_t s);
+rtoss_status launch_pack_stream1x1_batch(const PackItem* items, int n, const Dict& dict, hipStream_t s);
+
 // 3x3 convolution on the sparse matrix instruction (conv3x3_sparse.hip)
 bool sparse3x3_dictionary_ok(const Dict& dict);
 bool sparse3x3_shape_ok(const rtoss_wdesc& d);

@@ -93,20 +93,33 @@ inline size_t frag_bytes(const rtoss_wdesc& d)
 inline size_t zero_bytes(const rtoss_wdesc& d) { return align_up((size_t)2 * d.Ci + 16, 256); }
 
 // Fragment order: [channel block][wave slice wm][fragment m][stage s][lane].
+struct StreamPackArgs {
+    const void* w;
+    const uint8_t* idx;
+    char* out;
+    int Co, Ci, KS, MT, WM, zero_items;
+    int64_t G, total_items;
+    LiveJob job;
+};
+
+// One block of 256 items of one layer (`block` counts from the layer's first block).
 template <typename T>
-__global__ __launch_bounds__(256) void pack_stream1x1_kernel(const T* __restrict__ w, const uint8_t* __restrict__ idx,
-                                                             Dict dict, char* __restrict__ out, int Co, int Ci, int KS,
-                                                             int MT, int WM, int64_t G, int64_t total_items,
-                                                             int zero_items, LiveJob job)
+__device__ __forceinline__ void pack_stream1x1_body(const StreamPackArgs& a, const Dict& dict, int block)
 {
+    const T* __restrict__ w = (const T*)a.w;
+    const uint8_t* __restrict__ idx = a.idx;
+    char* __restrict__ out = a.out;
+    const int Co = a.Co, Ci = a.Ci, KS = a.KS, MT = a.MT, WM = a.WM, zero_items = a.zero_items;
+    const int64_t G = a.G, total_items = a.total_items;
+    const LiveJob job = a.job;
     __shared__ uint16_t masks[256];
     masks[threadIdx.x] = dict.mask[threadIdx.x];
     __syncthreads();
-    if ((int)blockIdx.x < job.blocks) {  // the first blocks write the blob's public section
-        pack_live_block<T>(w, idx, masks, dict.k, job, blockIdx.x);
+    if (block < job.blocks) {  // the first blocks write the blob's public section
+        pack_live_block<T>(w, idx, masks, dict.k, job, block);
         return;
     }
-    const int64_t item = (int64_t)(blockIdx.x - job.blocks) * 256 + threadIdx.x;
+    const int64_t item = (int64_t)(block - job.blocks) * 256 + threadIdx.x;
     if (item >= total_items) {
         if (item < total_items + zero_items) *(u32x4*)(out + total_items * 16 + (item - total_items) * 16) = u32x4{0, 0, 0, 0};
         return;
@@ -139,6 +152,25 @@ __global__ __launch_bounds__(256) void pack_stream1x1_kernel(const T* __restrict
     pk.z = v[4] | ((uint32_t)v[5] << 16);
     pk.w = v[6] | ((uint32_t)v[7] << 16);
     *(u32x4*)(out + item * 16) = pk;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void pack_stream1x1_kernel(StreamPackArgs a, Dict dict)
+{
+    pack_stream1x1_body<T>(a, dict, (int)blockIdx.x);
+}
+
+struct StreamPackBatch {
+    StreamPackArgs a[kPackBatchMax];
+    int first_block[kPackBatchMax + 1];
+    int n;
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void pack_stream1x1_batch_kernel(StreamPackBatch b, Dict dict)
+{
+    const int t = batch_entry(b, (int)blockIdx.x);  // block-uniform
+    pack_stream1x1_body<T>(b.a[t], dict, (int)blockIdx.x - b.first_block[t]);
 }
 
 template <typename T> struct Dense16;
@@ -371,20 +403,57 @@ bool stream1x1_shape_ok(const rtoss_wdesc& d)
 
 size_t stream1x1_section_bytes(const rtoss_wdesc& d) { return frag_bytes(d) + zero_bytes(d); }
 
+static StreamPackArgs stream_pack_args(const rtoss_wdesc& d, const void* w, const uint8_t* idx, void* section,
+                                       void* live_values, uint8_t* live_idx, int* blocks)
+{
+    StreamPackArgs a;
+    a.w = w;
+    a.idx = idx;
+    a.out = (char*)section;
+    a.Co = d.Co;
+    a.Ci = d.Ci;
+    a.KS = d.Ci / 32;
+    a.MT = mt_of(a.KS);
+    a.WM = wm_of(a.KS, d.Co);
+    a.G = (int64_t)d.Co * d.Ci / 9;
+    a.total_items = (int64_t)(frag_bytes(d) / 16);
+    a.zero_items = (int)(zero_bytes(d) / 16);
+    a.job = make_live_job(live_values, live_idx, a.G);
+    *blocks = (int)(a.job.blocks + (a.total_items + a.zero_items + 255) / 256);
+    return a;
+}
+
 rtoss_status launch_pack_stream1x1(const rtoss_wdesc& d, const void* w, const uint8_t* idx, const Dict& dict, void* section,
                                    void* live_values, uint8_t* live_idx, hipStream_t s)
 {
-    const int64_t G = (int64_t)d.Co * d.Ci / 9;
-    const LiveJob job = make_live_job(live_values, live_idx, G);
-    const int KS = d.Ci / 32, MT = mt_of(KS), WM = wm_of(KS, d.Co);
-    const int64_t items = (int64_t)(frag_bytes(d) / 16);
-    const int zero_items = (int)(zero_bytes(d) / 16);
-    dim3 grid((unsigned)(job.blocks + (items + zero_items + 255) / 256)), block(256);
-    if (d.dt == RTOSS_F16)
-        pack_stream1x1_kernel<f16_t><<<grid, block, 0, s>>>((const f16_t*)w, idx, dict, (char*)section, d.Co, d.Ci, KS, MT, WM, G, items, zero_items, job);
-    else
-        pack_stream1x1_kernel<bf16_t><<<grid, block, 0, s>>>((const bf16_t*)w, idx, dict, (char*)section, d.Co, d.Ci, KS, MT, WM, G, items, zero_items, job);
+    int blocks = 0;
+    const StreamPackArgs a = stream_pack_args(d, w, idx, section, live_values, live_idx, &blocks);
+    dim3 grid((unsigned)blocks), block(256);
+    if (d.dt == RTOSS_F16) pack_stream1x1_kernel<f16_t><<<grid, block, 0, s>>>(a, dict);
+    else pack_stream1x1_kernel<bf16_t><<<grid, block, 0, s>>>(a, dict);
     return check_hip(hipGetLastError(), "pack stream1x1 launch");
+}
+
+rtoss_status launch_pack_stream1x1_batch(const PackItem* items, int n, const Dict& dict, hipStream_t s)
+{
+    for (int base = 0; base < n; base += kPackBatchMax) {
+        StreamPackBatch b;
+        b.n = std::min(kPackBatchMax, n - base);
+        int total = 0;
+        for (int i = 0; i < b.n; ++i) {
+            const PackItem& it = items[base + i];
+            int blocks = 0;
+            b.a[i] = stream_pack_args(it.d, it.w, it.idx, it.section, it.live, it.live_idx, &blocks);
+            b.first_block[i] = total;
+            total += blocks;
+        }
+        b.first_block[b.n] = total;
+        dim3 grid((unsigned)total), block(256);
+        if (items[base].d.dt == RTOSS_F16) pack_stream1x1_batch_kernel<f16_t><<<grid, block, 0, s>>>(b, dict);
+        else pack_stream1x1_batch_kernel<bf16_t><<<grid, block, 0, s>>>(b, dict);
+        if (rtoss_status st = check_hip(hipGetLastError(), "pack stream1x1 batch launch")) return st;
+    }
+    return RTOSS_OK;
 }
 
 rtoss_status launch_conv1x1_stream(const rtoss_wdesc& d, const ConvParams& c, const void* section, const void* x, void* y,

@@ -68,19 +68,33 @@ __device__ __forceinline__ int stage_channel(int q, int g, int half)
     return 8 * (2 * (q & 1) + (g >> 1)) + 4 * half + 2 * (q >> 1) + (g & 1);
 }
 
+struct SparsePackArgs {
+    const void* w;
+    const uint8_t* idx;
+    char* out;
+    int Co, Ci, m_tiles, zero_items;
+    int64_t total_items;
+    LiveJob job;
+};
+
+// One block of 256 items of one layer (`block` counts from the layer's first block).
 template <typename T>
-__global__ __launch_bounds__(256) void pack_sparse3x3_kernel(const T* __restrict__ w, const uint8_t* __restrict__ idx,
-                                                             Dict dict, char* __restrict__ out, int Co, int Ci,
-                                                             int m_tiles, int64_t total_items, int zero_items, LiveJob job)
+__device__ __forceinline__ void pack_sparse3x3_body(const SparsePackArgs& a, const Dict& dict, int block)
 {
+    const T* __restrict__ w = (const T*)a.w;
+    const uint8_t* __restrict__ idx = a.idx;
+    char* __restrict__ out = a.out;
+    const int Co = a.Co, Ci = a.Ci, m_tiles = a.m_tiles, zero_items = a.zero_items;
+    const int64_t total_items = a.total_items;
+    const LiveJob job = a.job;
     __shared__ uint16_t masks[256];
     masks[threadIdx.x] = dict.mask[threadIdx.x];
     __syncthreads();
-    if ((int)blockIdx.x < job.blocks) {  // the first blocks write the blob's public section
-        pack_live_block<T>(w, idx, masks, dict.k, job, blockIdx.x);
+    if (block < job.blocks) {  // the first blocks write the blob's public section
+        pack_live_block<T>(w, idx, masks, dict.k, job, block);
         return;
     }
-    const int64_t item = (int64_t)(blockIdx.x - job.blocks) * 256 + threadIdx.x;  // (stage, m_tile, step 0..4, lane)
+    const int64_t item = (int64_t)(block - job.blocks) * 256 + threadIdx.x;  // (stage, m_tile, step 0..4, lane)
     if (item >= total_items) {  // the items behind the fragments write the block of zeros, 16 bytes each
         if (item < total_items + zero_items) *(u32x4*)(out + (total_items / 320) * kTileBytes + (item - total_items) * 16) = u32x4{0, 0, 0, 0};
         return;
@@ -138,6 +152,25 @@ __global__ __launch_bounds__(256) void pack_sparse3x3_kernel(const T* __restrict
     pk.z = vals[4] | ((uint32_t)vals[5] << 16);
     pk.w = vals[6] | ((uint32_t)vals[7] << 16);
     *(u32x4*)(tile_out + step * kFragBytes + lane * 16) = pk;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void pack_sparse3x3_kernel(SparsePackArgs a, Dict dict)
+{
+    pack_sparse3x3_body<T>(a, dict, (int)blockIdx.x);
+}
+
+struct SparsePackBatch {
+    SparsePackArgs a[kPackBatchMax];
+    int first_block[kPackBatchMax + 1];
+    int n;
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void pack_sparse3x3_batch_kernel(SparsePackBatch b, Dict dict)
+{
+    const int t = batch_entry(b, (int)blockIdx.x);  // block-uniform
+    pack_sparse3x3_body<T>(b.a[t], dict, (int)blockIdx.x - b.first_block[t]);
 }
 
 // Channel tiles per stage in the packed section: padded so that every block of 8 tiles is complete.
@@ -871,19 +904,54 @@ size_t sparse3x3_section_bytes(const rtoss_wdesc& d)
     return fragment_bytes(d) + zero_block_bytes(d);
 }
 
+static SparsePackArgs sparse_pack_args(const rtoss_wdesc& d, const void* w, const uint8_t* idx, void* section,
+                                       void* live_values, uint8_t* live_idx, int* blocks)
+{
+    SparsePackArgs a;
+    a.w = w;
+    a.idx = idx;
+    a.out = (char*)section;
+    a.Co = d.Co;
+    a.Ci = d.Ci;
+    a.m_tiles = padded_m_tiles(d.Co);
+    a.total_items = (int64_t)(d.Ci / 32) * a.m_tiles * 320;
+    a.zero_items = (int)(zero_block_bytes(d) / 16);
+    a.job = make_live_job(live_values, live_idx, (int64_t)d.Co * d.Ci);
+    *blocks = (int)(a.job.blocks + (a.total_items + a.zero_items + 255) / 256);
+    return a;
+}
+
 rtoss_status launch_pack_sparse3x3(const rtoss_wdesc& d, const void* w, const uint8_t* idx, const Dict& dict,
                                    void* section, void* live_values, uint8_t* live_idx, hipStream_t s)
 {
-    const LiveJob job = make_live_job(live_values, live_idx, (int64_t)d.Co * d.Ci);
-    const int m_tiles = padded_m_tiles(d.Co);
-    const int64_t items = (int64_t)(d.Ci / 32) * m_tiles * 320;
-    const int zero_items = (int)(zero_block_bytes(d) / 16);
-    dim3 grid((unsigned)(job.blocks + (items + zero_items + 255) / 256)), block(256);
-    if (d.dt == RTOSS_F16)
-        pack_sparse3x3_kernel<f16_t><<<grid, block, 0, s>>>((const f16_t*)w, idx, dict, (char*)section, d.Co, d.Ci, m_tiles, items, zero_items, job);
-    else
-        pack_sparse3x3_kernel<bf16_t><<<grid, block, 0, s>>>((const bf16_t*)w, idx, dict, (char*)section, d.Co, d.Ci, m_tiles, items, zero_items, job);
+    int blocks = 0;
+    const SparsePackArgs a = sparse_pack_args(d, w, idx, section, live_values, live_idx, &blocks);
+    dim3 grid((unsigned)blocks), block(256);
+    if (d.dt == RTOSS_F16) pack_sparse3x3_kernel<f16_t><<<grid, block, 0, s>>>(a, dict);
+    else pack_sparse3x3_kernel<bf16_t><<<grid, block, 0, s>>>(a, dict);
     return check_hip(hipGetLastError(), "pack sparse3x3 launch");
+}
+
+rtoss_status launch_pack_sparse3x3_batch(const PackItem* items, int n, const Dict& dict, hipStream_t s)
+{
+    for (int base = 0; base < n; base += kPackBatchMax) {
+        SparsePackBatch b;
+        b.n = std::min(kPackBatchMax, n - base);
+        int total = 0;
+        for (int i = 0; i < b.n; ++i) {
+            const PackItem& it = items[base + i];
+            int blocks = 0;
+            b.a[i] = sparse_pack_args(it.d, it.w, it.idx, it.section, it.live, it.live_idx, &blocks);
+            b.first_block[i] = total;
+            total += blocks;
+        }
+        b.first_block[b.n] = total;
+        dim3 grid((unsigned)total), block(256);
+        if (items[base].d.dt == RTOSS_F16) pack_sparse3x3_batch_kernel<f16_t><<<grid, block, 0, s>>>(b, dict);
+        else pack_sparse3x3_batch_kernel<bf16_t><<<grid, block, 0, s>>>(b, dict);
+        if (rtoss_status st = check_hip(hipGetLastError(), "pack sparse3x3 batch launch")) return st;
+    }
+    return RTOSS_OK;
 }
 
 rtoss_status launch_conv3x3_sparse(const rtoss_wdesc& d, const ConvParams& c, const void* section, const void* x,

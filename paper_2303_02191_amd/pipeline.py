@@ -51,6 +51,18 @@ def select_patterns_batch(ws, dt, masks, idxs=None, stream=None):
     return [idx[: w.numel() // 9] for w, idx in zip(ws, idxs)]
 
 
+def pack_layers(layers, ws, idxs, stream=None):
+    """Pack several PackedLayer objects (one dictionary) from their weight and index tensors in one call."""
+    if not layers:
+        return layers
+    items = []
+    for lay, w, idx in zip(layers, ws, idxs):
+        assert w.is_cuda and w.is_contiguous() and idx.is_cuda
+        items.append((lay.wdesc, w.data_ptr(), idx.data_ptr(), lay.blob.data_ptr(), lay.packed_bytes))
+    B.rtoss_pack_batch(items, layers[0].masks, _stream() if stream is None else stream)
+    return layers
+
+
 def pattern_histogram(idx, P, hist=None):
     """Adds the usage counts of idx (uint8 cuda tensor) to hist (uint32 counts as an int32 cuda tensor [P])."""
     assert idx.is_cuda and idx.dtype == torch.uint8 and idx.is_contiguous()

@@ -188,3 +188,21 @@ def test_fused_conv_argument_errors():
         B.rtoss_conv2d_pattern_fused(wd, ok, B.EpilogueDesc(None, None, 0, (1 << 20) + 64), masks, 256, 512, 1 << 20)
     assert e.value.status == B.EINVAL
 
+
+def test_batched_pack_argument_errors():
+    masks = B.rtoss_pattern_dict(2)
+    good = (B.WDesc(32, 32, 3, 2, B.F16), 256, 512, 1024, 1 << 20)
+    with pytest.raises(B.RtossError) as e:
+        B.rtoss_pack_batch(None, masks)
+    assert e.value.status == B.EINVAL
+    with pytest.raises(B.RtossError) as e:  # second item: blob too small; nothing is launched
+        B.rtoss_pack_batch([good, (B.WDesc(32, 32, 3, 2, B.F16), 256, 512, 1024, 16)], masks)
+    assert e.value.status == B.ENOSPACE and "item 1" in str(e.value)
+    with pytest.raises(B.RtossError) as e:  # dictionary / descriptor mismatch
+        B.rtoss_pack_batch([(B.WDesc(32, 32, 3, 3, B.F16), 256, 512, 1024, 1 << 20)], masks)
+    assert e.value.status == B.EINVAL
+    with pytest.raises(B.RtossError) as e:
+        B.rtoss_pack_batch([(B.WDesc(32, 32, 3, 2, B.F16), 0, 512, 1024, 1 << 20)], masks)
+    assert e.value.status == B.EINVAL
+    B.rtoss_pack_batch([], masks)
+

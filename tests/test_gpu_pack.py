@@ -30,3 +30,31 @@ def test_pack_live_section(dt, Co, Ci, ks, k):
     tail = (Co * Ci * ks * ks) % 9
     if tail:
         assert (got.reshape(-1)[-tail:] == 0).all()
+
+
+def test_batched_pack_equals_single_packs():
+    # layers of every blob format (and more of one format than a launch table holds): the batched call must
+    # write exactly the bytes the per-layer call writes
+    import torch
+    from paper_2303_02191_amd import pipeline as pl
+    dt, k = wl.F16, 2
+    masks = B.rtoss_pattern_dict(k)
+    shapes = [(64, 64, 3), (32, 3, 3), (48, 96, 1), (40, 24, 3), (128, 256, 1)] + [(32 + 16 * (i % 3), 64, 1) for i in range(30)] \
+        + [(16 * (1 + i % 4), 32 * (1 + i % 2), 3) for i in range(27)]
+    rng = np.random.default_rng(5)
+    ws, idxs, single, batched = [], [], [], []
+    for Co, Ci, ks in shapes:
+        w = pl.to_device(wl.round_to_dtype(rng.standard_normal((Co, Ci, ks, ks)) * 0.05, dt), dt)
+        ws.append(w)
+        idxs.append(pl.select_patterns(w, dt, masks))
+        single.append(pl.PackedLayer(Co, Ci, ks, k, dt, masks))
+        batched.append(pl.PackedLayer(Co, Ci, ks, k, dt, masks))
+        single[-1].blob.zero_()
+        batched[-1].blob.zero_()
+    for lay, w, idx in zip(single, ws, idxs):
+        lay.pack(w, idx)
+    pl.pack_layers(batched, ws, idxs)
+    torch.cuda.synchronize()
+    for (Co, Ci, ks), a, b in zip(shapes, single, batched):
+        assert torch.equal(a.blob, b.blob), (Co, Ci, ks)
+
