@@ -70,9 +70,11 @@ __global__ __launch_bounds__(256) void pack_stem_kernel(const T* __restrict__ w,
     *(u32x4*)(out + (size_t)item * 16) = pk;
 }
 
-template <typename T, typename TO, int S, int TM>
+// Ci is a template parameter: the index arithmetic below divides by it (and by 3 * Ci) per element, which
+// as run-time divisions made the kernel bound by integer ALU work.
+template <typename T, typename TO, int S, int TM, int Ci>
 __global__ __launch_bounds__(256) void conv3x3_stem_kernel(const T* __restrict__ x, TO* __restrict__ y,
-                                                           const char* __restrict__ wfrag, int H, int W, int Ci, int Co,
+                                                           const char* __restrict__ wfrag, int H, int W, int Co,
                                                            int Ho, int Wo, int tiles_c, Epilogue ep)
 {
     constexpr int IH = (kTH - 1) * S + 3, IW = (kTW - 1) * S + 3;
@@ -85,7 +87,7 @@ __global__ __launch_bounds__(256) void conv3x3_stem_kernel(const T* __restrict__
     const int n_img = blockIdx.y;
     const int oh0 = tile_r * kTH, ow0 = tile_c * kTW;
     const int ih0 = oh0 * S - 1, iw0 = ow0 * S - 1;
-    const int rowlen = IW * Ci;  // halves per row actually used
+    constexpr int rowlen = IW * Ci;  // halves per row actually used
 
     // ---- stage the input tile (with halo, zero padded): consecutive lanes read consecutive halves ----
     const uint16_t* xin = (const uint16_t*)x;
@@ -103,18 +105,22 @@ __global__ __launch_bounds__(256) void conv3x3_stem_kernel(const T* __restrict__
     __syncthreads();
 
     const int nn = lane & 15, qq = lane >> 4;
-    const int k3 = 3 * Ci, K = 9 * Ci;
+    constexpr int k3 = 3 * Ci, K = 9 * Ci;
+    // LDS offset of each of this lane's 8 K values relative to the block's first tap (same for all blocks)
+    int koff[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int k = 8 * qq + j;
+        const int kh = k / k3, off = k - kh * k3;
+        koff[j] = k < K ? kh * MAXROW + off : -1;
+    }
 #pragma unroll 1
     for (int jb = 0; jb < 4; ++jb) {
         const int blk = wave * 4 + jb;            // 16 blocks: 8 rows x 2 half-rows of 16 columns
         const int r = blk >> 1, c = (blk & 1) * 16 + nn;
         uint16_t bv[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int k = 8 * qq + j;
-            const int kh = k / k3, off = k - kh * k3;
-            bv[j] = k < K ? xs[(r * S + kh) * MAXROW + c * S * Ci + off] : (uint16_t)0;
-        }
+        for (int j = 0; j < 8; ++j) bv[j] = koff[j] >= 0 ? xs[r * S * MAXROW + c * S * Ci + koff[j]] : (uint16_t)0;
         u32x4 b;
         b.x = bv[0] | ((uint32_t)bv[1] << 16);
         b.y = bv[2] | ((uint32_t)bv[3] << 16);
@@ -145,16 +151,24 @@ __global__ __launch_bounds__(256) void conv3x3_stem_kernel(const T* __restrict__
     }
 }
 
-template <typename T, typename TO, int S, int TM>
-rtoss_status launch_stem(const rtoss_wdesc& d, const ConvParams& c, const char* wfrag, const void* x, void* y, hipStream_t s)
+template <typename T, typename TO, int S, int TM, int Ci>
+rtoss_status launch_stem_ci(const rtoss_wdesc& d, const ConvParams& c, const char* wfrag, const void* x, void* y, hipStream_t s)
 {
     const int Ho = (c.H + 2 - 3) / S + 1, Wo = (c.W + 2 - 3) / S + 1;
     const int tiles_r = (Ho + kTH - 1) / kTH, tiles_c = (Wo + kTW - 1) / kTW;
     if (c.N > 65535) return fail(RTOSS_ESHAPE, "conv: batch too large");
     dim3 grid((unsigned)(tiles_r * tiles_c), (unsigned)c.N), block(256);
-    conv3x3_stem_kernel<T, TO, S, TM><<<grid, block, 0, s>>>((const T*)x, (TO*)y, wfrag, c.H, c.W, d.Ci, d.Co, Ho, Wo, tiles_c,
-                                                             c.ep);
+    conv3x3_stem_kernel<T, TO, S, TM, Ci><<<grid, block, 0, s>>>((const T*)x, (TO*)y, wfrag, c.H, c.W, d.Co, Ho, Wo, tiles_c,
+                                                                 c.ep);
     return check_hip(hipGetLastError(), "conv3x3 stem launch");
+}
+
+template <typename T, typename TO, int S, int TM>
+rtoss_status launch_stem(const rtoss_wdesc& d, const ConvParams& c, const char* wfrag, const void* x, void* y, hipStream_t s)
+{
+    if (d.Ci == 3) return launch_stem_ci<T, TO, S, TM, 3>(d, c, wfrag, x, y, s);
+    if (d.Ci == 2) return launch_stem_ci<T, TO, S, TM, 2>(d, c, wfrag, x, y, s);
+    return launch_stem_ci<T, TO, S, TM, 1>(d, c, wfrag, x, y, s);
 }
 
 template <typename T, typename TO>
