@@ -312,6 +312,7 @@ def main():
             masked.append(oracle.mask(wv, masks, oracle.select(wv, masks)))
         t_sel = time.perf_counter() - t_sel
         done_macs, t_conv, n_done = 0.0, 0.0, 0
+        worst = 0.0  # the same sample doubles as a parity spot check of what the timed region computed
         for li, L in enumerate(cfg.layers):
             for n in range(cfg.N):
                 if t_conv >= args.cpu_seconds:
@@ -319,15 +320,21 @@ def main():
                 x0 = pl.to_host(xs[li][n:n + 1]).copy()  # [1, H, W, Ci] storage, as the GPU saw it
                 xv = wl.to_f64(wl.nhwc_to_nchw(x0), cfg.dtype)
                 t_a = time.perf_counter()
-                oracle.conv2d(xv, masked[li], stride=L.stride, relu=L.relu)
+                ref = oracle.conv2d(xv, masked[li], stride=L.stride, relu=L.relu)
                 t_conv += time.perf_counter() - t_a
+                got = wl.to_f64(wl.nhwc_to_nchw(pl.to_host(ys[li][n:n + 1])), cfg.dtype)
+                rms = float(np.sqrt(np.mean(ref ** 2))) or 1.0
+                worst = max(worst, float(np.max(np.abs(got - ref))) / rms)
                 done_macs += L.Ho * L.Wo * cfg.k * L.groups
                 n_done += 1
         cpu = {"value": 2.0 * done_macs / t_conv / 1e12, "unit": "TFLOP/s", "cores": oracle.threads(),
                "kind": "oracle",
                "sample": "%d whole (layer, batch item) convolutions of %s in layer-major order, %.2f s of oracle "
                          "conv time; select+mask of all %d groups took %.3f s" % (
-                             n_done, cfg.name, t_conv, sum(L.groups for L in cfg.layers), t_sel)}
+                             n_done, cfg.name, t_conv, sum(L.groups for L in cfg.layers), t_sel),
+               # max |stored GPU output - oracle| / rms(oracle) over the sampled convolutions; a stored 16-bit
+               # output carries its own rounding (bf16: up to 2^-9 of the value) on top of the accumulation error
+               "parity_max_err_over_rms": worst}
 
     out = {
         "metric": "effective TFLOP/s on non-zero MACs, select+pack+pattern-sparse conv",
