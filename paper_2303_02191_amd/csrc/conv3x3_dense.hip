@@ -21,8 +21,16 @@
 // fragment m is channel 16q + 4m + i of the workgroup's 64), and the four lane quarters of a
 // position together write 128 contiguous bytes.
 //
+// fp32 tensors run through the same kernel on v_mfma_f32_16x16x4_f32: a stage is then 16 input
+// channels (the same 64 bytes per position), a lane's 16 bytes are 4 consecutive channels, and the
+// K step of 16 channels is 4 instructions, instruction s taking element s of every lane's 16 bytes
+// (the K slots of an instruction are the channels 4q + s: any assignment of channels to slots is
+// valid as long as both operands use it).  Small launches use 16 channels x 4x16 positions per
+// workgroup so that they still fill the chip.
+//
 // Operand layout of v_mfma_f32_16x16x32 (wave64; r = lane % 16, q = lane / 16): A lane holds
 // row r, K = 8q..8q+7; B lane holds column r, K = 8q..8q+7; D lane holds column r, rows 4q..4q+3.
+// v_mfma_f32_16x16x4_f32: A lane holds row r, K = q; B lane holds column r, K = q; same D.
 #include <algorithm>
 
 #include "common.h"
@@ -37,13 +45,16 @@ namespace rtoss {
 namespace {
 
 constexpr int kFrag = 1024;            // 64 lanes x 16 bytes = 16 output channels x 32 input channels of one tap
-constexpr int kTM = 4;                 // channel fragments per workgroup (64 output channels)
-constexpr int kTN = 4;                 // position blocks per wave
+constexpr int kTM = 4;                 // channel fragments per block of the blob (64 output channels)
 constexpr int kBlockBytes = kTM * 9 * kFrag;  // weights of one (stage, channel block)
+inline int stage_channels(rtoss_dtype dt) { return dt == RTOSS_F32 ? 16 : 32; }  // 64 bytes per position
 
 inline int channel_blocks(int Co) { return (Co + 16 * kTM - 1) / (16 * kTM); }
-inline size_t frag_bytes(const rtoss_wdesc& d) { return (size_t)(d.Ci / 32) * channel_blocks(d.Co) * kBlockBytes; }
-inline size_t zero_bytes(const rtoss_wdesc& d) { return align_up((size_t)2 * d.Ci + 16, 256); }
+inline size_t frag_bytes(const rtoss_wdesc& d)
+{
+    return (size_t)(d.Ci / stage_channels(d.dt)) * channel_blocks(d.Co) * kBlockBytes;
+}
+inline size_t zero_bytes(const rtoss_wdesc& d) { return align_up((size_t)elem_bytes(d.dt) * d.Ci + 16, 256); }
 
 // Fragment order: [stage][channel block][fragment m][tap t][lane].
 template <typename T>
@@ -73,20 +84,18 @@ __global__ __launch_bounds__(256) void pack_dense3x3_kernel(const T* __restrict_
     const int stage = (int)(f / cblocks);
     const int r = lane % 16, q = lane / 16;
     const int co = cb * (16 * kTM) + (r / 4) * 16 + 4 * m + (r % 4);
-    uint16_t v[8];
-    for (int j = 0; j < 8; ++j) {
-        const int ci = 32 * stage + 8 * q + j;
-        v[j] = 0;
+    constexpr int PER_LANE = 16 / (int)sizeof(T);  // elements in a lane's 16 bytes: 8 (16-bit) or 4 (fp32)
+    T v[PER_LANE];
+    for (int j = 0; j < PER_LANE; ++j) {
+        const int ci = (4 * PER_LANE) * stage + PER_LANE * q + j;
+        __builtin_memset(&v[j], 0, sizeof(T));
         if (co < Co) {
             const int64_t g = (int64_t)co * Ci + ci;
-            if ((masks[idx[g]] >> t) & 1u) v[j] = __builtin_bit_cast(uint16_t, w[g * 9 + t]);
+            if ((masks[idx[g]] >> t) & 1u) v[j] = w[g * 9 + t];
         }
     }
     u32x4 pk;
-    pk.x = v[0] | ((uint32_t)v[1] << 16);
-    pk.y = v[2] | ((uint32_t)v[3] << 16);
-    pk.z = v[4] | ((uint32_t)v[5] << 16);
-    pk.w = v[6] | ((uint32_t)v[7] << 16);
+    __builtin_memcpy(&pk, v, 16);
     *(u32x4*)(out + item * 16) = pk;
 }
 
@@ -103,30 +112,45 @@ template <> struct Dense16<bf16_t> {
         return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(b8, a), __builtin_bit_cast(b8, b), c, 0, 0, 0);
     }
 };
+template <> struct Dense16<float> {  // 16 channels: four K = 4 steps, step s on element s of every lane's 16 bytes
+    static __device__ __forceinline__ f32x4 mma(u32x4 a, u32x4 b, f32x4 c)
+    {
+        const f32x4 af = __builtin_bit_cast(f32x4, a), bf = __builtin_bit_cast(f32x4, b);
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(af.x, bf.x, c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(af.y, bf.y, c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(af.z, bf.z, c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(af.w, bf.w, c, 0, 0, 0);
+        return c;
+    }
+};
 
-template <typename T, typename TO, int S>
+// TM channel fragments (of the blob's blocks of 4) and RT x CT position blocks per workgroup.
+template <typename T, typename TO, int S, int TM, int RT, int CT>
 __global__ __launch_bounds__(256) void conv3x3_dense_kernel(const T* __restrict__ x, TO* __restrict__ y,
                                                             const char* __restrict__ wfrag, const char* __restrict__ zeros,
                                                             int H, int W, int Ci, int Co, int Ho, int Wo, int cblocks,
                                                             int tiles_c, Epilogue ep)
 {
-    using G = Geom<S, 4, 4>;
-    constexpr int A_BYTES = kBlockBytes;
-    constexpr int A_PER_WAVE = A_BYTES / 1024 / 4;              // copy instructions (64 lanes x 16 B) per wave
+    using G = Geom<S, RT, CT>;
+    constexpr int kTN = RT * CT / 4;                            // position blocks per wave
+    static_assert(RT * CT % 4 == 0 && kTM % TM == 0, "four waves share the blocks; fragments split the blob's blocks evenly");
+    constexpr int A_BYTES = TM * 9 * kFrag;
+    constexpr int A_COPIES = A_BYTES / 1024;                    // copy instructions (64 lanes x 16 B)
+    constexpr int A_PER_WAVE = (A_COPIES + 3) / 4;
+    constexpr int EBI = (int)sizeof(T);                         // a stage is 64 bytes of channels per position
     constexpr int X_CHUNKS = G::x_bytes / 16;                   // including the pad chunk of every position
     constexpr int X_PER_WAVE = ((X_CHUNKS + 63) / 64 + 3) / 4;
-    static_assert(A_BYTES % 4096 == 0, "every wave issues the same number of weight copies");
-    extern __shared__ __attribute__((aligned(16))) char smem[];  // [weights][activations, rounded up to whole copies]
+    extern __shared__ __attribute__((aligned(16))) char smem[];  // [weights, rounded up][activations, rounded up to whole copies]
     char* lds_a = smem;
-    char* lds_x = smem + A_BYTES;
+    char* lds_x = smem + A_PER_WAVE * 4096;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int tile_r = blockIdx.x / tiles_c, tile_c = blockIdx.x % tiles_c;
-    const int cb = blockIdx.y, n_img = blockIdx.z;
+    const int cb = blockIdx.y / (kTM / TM), m_first = (blockIdx.y % (kTM / TM)) * TM, n_img = blockIdx.z;
     const int oh0 = tile_r * G::TH, ow0 = tile_c * G::TW;
     const int ih0 = oh0 * S - 1, iw0 = ow0 * S - 1;
-    const int stages = Ci / 32;
+    const int stages = Ci / (64 / EBI);
 
     // Copy sources of stage 0.  Every lane copies 16 bytes in every copy instruction; a lane whose LDS
     // slot is zero padding of the tile (or a pad chunk) reads the block of zeros behind the fragments.
@@ -138,10 +162,10 @@ __global__ __launch_bounds__(256) void conv3x3_dense_kernel(const T* __restrict_
         const int pr = pos / G::LW, pc = pos % G::LW;
         const int ih = ih0 + pr, iw = iw0 + pc;
         const bool inside = q < 4 && pr < G::IH && pc < G::IW && ih >= 0 && ih < H && iw >= 0 && iw < W;
-        x_ptr[k] = inside ? (const char*)x + ((((int64_t)n_img * H + ih) * W + iw) * Ci + q * 8) * 2 : zeros;
+        x_ptr[k] = inside ? (const char*)x + ((((int64_t)n_img * H + ih) * W + iw) * Ci + q * (16 / EBI)) * EBI : zeros;
     }
-    const char* a_src = wfrag + (int64_t)cb * A_BYTES + lane * 16;
-    const int64_t a_stage_stride = (int64_t)cblocks * A_BYTES;
+    const char* a_src = wfrag + (int64_t)cb * kBlockBytes + m_first * 9 * kFrag + lane * 16;
+    const int64_t a_stage_stride = (int64_t)cblocks * kBlockBytes;
 
     const int nn = lane & 15, qq = lane >> 4;
     const int pr = nn >> 2, pc = nn & 3;
@@ -149,20 +173,22 @@ __global__ __launch_bounds__(256) void conv3x3_dense_kernel(const T* __restrict_
 #pragma unroll
     for (int j = 0; j < kTN; ++j) {
         const int blk = wave * kTN + j;
-        xb[j] = (((4 * (blk / 4) + pr) * S) * G::LW + (4 * (blk % 4) + pc) * S) * kXPosBytes + qq * 16;
+        xb[j] = (((4 * (blk / CT) + pr) * S) * G::LW + (4 * (blk % CT) + pc) * S) * kXPosBytes + qq * 16;
     }
 
-    f32x4 acc[kTM][kTN];
+    f32x4 acc[TM][kTN];
 #pragma unroll
-    for (int m = 0; m < kTM; ++m)
+    for (int m = 0; m < TM; ++m)
 #pragma unroll
         for (int j = 0; j < kTN; ++j) acc[m][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     for (int stage = 0; stage < stages; ++stage) {
         __syncthreads();  // everybody is done reading the previous stage
 #pragma unroll
-        for (int k = 0; k < A_PER_WAVE; ++k)
-            copy16_to_lds(a_src + stage * a_stage_stride + (k * 4 + wave) * 1024, lds_a + (k * 4 + wave) * 1024);
+        for (int k = 0; k < A_PER_WAVE; ++k) {  // (copy slots past the fragments read the block of zeros)
+            const int kk = k * 4 + wave;
+            copy16_to_lds(kk < A_COPIES ? a_src + stage * a_stage_stride + kk * 1024 : zeros, lds_a + kk * 1024);
+        }
 #pragma unroll
         for (int k = 0; k < X_PER_WAVE; ++k) copy16_to_lds(x_ptr[k] + stage * 64, lds_x + (k * 4 + wave) * 1024);
         __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's copies have landed in LDS
@@ -174,7 +200,7 @@ __global__ __launch_bounds__(256) void conv3x3_dense_kernel(const T* __restrict_
             for (int j = 0; j < kTN; ++j)
                 b[j] = *(const u32x4*)(lds_x + xb[j] + ((t / 3) * G::LW + (t % 3)) * kXPosBytes);
 #pragma unroll
-            for (int m = 0; m < kTM; ++m) {
+            for (int m = 0; m < TM; ++m) {
                 const u32x4 a = *(const u32x4*)(lds_a + (m * 9 + t) * kFrag + lane * 16);
 #pragma unroll
                 for (int j = 0; j < kTN; ++j) acc[m][j] = Dense16<T>::mma(a, b[j], acc[m][j]);
@@ -182,28 +208,34 @@ __global__ __launch_bounds__(256) void conv3x3_dense_kernel(const T* __restrict_
         }
     }
 
-    // ---- store: 16 consecutive channels of this lane's position in each of its blocks ----
-    const int co_lane = cb * (16 * kTM) + 16 * qq;
+    // ---- store: 4*TM consecutive channels of this lane's position in each of its blocks ----
+    const int co_lane = cb * (16 * kTM) + 16 * qq + 4 * m_first;
     constexpr int EB = (int)sizeof(TO);
+    constexpr int RUN = 4 * TM;
 #pragma unroll
     for (int j = 0; j < kTN; ++j) {
         const int blk = wave * kTN + j;
-        const int oh = oh0 + 4 * (blk / 4) + pr, ow = ow0 + 4 * (blk % 4) + pc;
+        const int oh = oh0 + 4 * (blk / CT) + pr, ow = ow0 + 4 * (blk % CT) + pc;
         if (oh >= Ho || ow >= Wo || co_lane >= Co) continue;  // Co is a multiple of 16: a run is all in or all out
         TO* yp = y + (((int64_t)n_img * Ho + oh) * Wo + ow) * Co + co_lane;
-        float v[16];
+        float v[RUN];
 #pragma unroll
-        for (int m = 0; m < kTM; ++m)
+        for (int m = 0; m < TM; ++m)
 #pragma unroll
             for (int e = 0; e < 4; ++e) v[4 * m + e] = acc[m][j][e];
-        epi_scale_bias_act<16>(v, ep, co_lane);
-        epi_residual<TO, 16>(v, ep, yp - y);
+        epi_scale_bias_act<RUN>(v, ep, co_lane);
+        epi_residual<TO, RUN>(v, ep, yp - y);
         if constexpr (EB == 4) {
 #pragma unroll
-            for (int g = 0; g < 4; ++g) *(f32x4*)(yp + 4 * g) = f32x4{v[4 * g], v[4 * g + 1], v[4 * g + 2], v[4 * g + 3]};
+            for (int g = 0; g < TM; ++g) *(f32x4*)(yp + 4 * g) = f32x4{v[4 * g], v[4 * g + 1], v[4 * g + 2], v[4 * g + 3]};
+        } else if constexpr (TM == 1) {
+            uint2 o;
+            o.x = pack2_from_f32<TO>(v[0], v[1]);
+            o.y = pack2_from_f32<TO>(v[2], v[3]);
+            *(uint2*)yp = o;
         } else {
 #pragma unroll
-            for (int g = 0; g < 2; ++g) {
+            for (int g = 0; g < TM / 2; ++g) {
                 u32x4 o;
                 o.x = pack2_from_f32<TO>(v[8 * g + 0], v[8 * g + 1]);
                 o.y = pack2_from_f32<TO>(v[8 * g + 2], v[8 * g + 3]);
@@ -215,16 +247,17 @@ __global__ __launch_bounds__(256) void conv3x3_dense_kernel(const T* __restrict_
     }
 }
 
-template <typename T, typename TO, int S>
-rtoss_status launch_stride(const rtoss_wdesc& d, const ConvParams& c, const char* wfrag, const void* x, void* y, hipStream_t s)
+template <typename T, typename TO, int S, int TM, int RT, int CT>
+rtoss_status launch_shape(const rtoss_wdesc& d, const ConvParams& c, const char* wfrag, const void* x, void* y, hipStream_t s)
 {
-    using G = Geom<S, 4, 4>;
+    using G = Geom<S, RT, CT>;
     const int Ho = (c.H + 2 - 3) / S + 1, Wo = (c.W + 2 - 3) / S + 1;
     const int tiles_r = (Ho + G::TH - 1) / G::TH, tiles_c = (Wo + G::TW - 1) / G::TW;
     const int cblocks = channel_blocks(d.Co);
     constexpr int x_copies_per_wave = ((G::x_bytes / 16 + 63) / 64 + 3) / 4;
-    const size_t smem = (size_t)kBlockBytes + (size_t)x_copies_per_wave * 4096;
-    auto kern = conv3x3_dense_kernel<T, TO, S>;
+    constexpr int a_copies_per_wave = (TM * 9 + 3) / 4;
+    const size_t smem = (size_t)(a_copies_per_wave + x_copies_per_wave) * 4096;
+    auto kern = conv3x3_dense_kernel<T, TO, S, TM, RT, CT>;
     static bool attr_set = false;  // per instantiation
     if (!attr_set) {
         if (rtoss_status st = check_hip(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem),
@@ -232,11 +265,23 @@ rtoss_status launch_stride(const rtoss_wdesc& d, const ConvParams& c, const char
             return st;
         attr_set = true;
     }
-    if (c.N > 65535 || cblocks > 65535) return fail(RTOSS_ESHAPE, "conv: batch or channel count too large");
-    dim3 grid((unsigned)(tiles_r * tiles_c), (unsigned)cblocks, (unsigned)c.N), block(256);
+    const int ygrid = cblocks * (kTM / TM);
+    if (c.N > 65535 || ygrid > 65535) return fail(RTOSS_ESHAPE, "conv: batch or channel count too large");
+    dim3 grid((unsigned)(tiles_r * tiles_c), (unsigned)ygrid, (unsigned)c.N), block(256);
     kern<<<grid, block, smem, s>>>((const T*)x, (TO*)y, wfrag, wfrag + frag_bytes(d), c.H, c.W, d.Ci, d.Co, Ho, Wo, cblocks,
                                    tiles_c, c.ep);
     return check_hip(hipGetLastError(), "conv3x3 dense launch");
+}
+
+template <typename T, typename TO, int S>
+rtoss_status launch_stride(const rtoss_wdesc& d, const ConvParams& c, const char* wfrag, const void* x, void* y, hipStream_t s)
+{
+    // 64 channels x 16x16 positions per workgroup; launches that would not fill the chip that way take
+    // 16 channels x 4x16 positions (16 times as many workgroups).
+    const int Ho = (c.H + 2 - 3) / S + 1, Wo = (c.W + 2 - 3) / S + 1;
+    const int64_t big = (int64_t)((Ho + 15) / 16) * ((Wo + 15) / 16) * channel_blocks(d.Co) * c.N;
+    if (big < 256) return launch_shape<T, TO, S, 1, 1, 4>(d, c, wfrag, x, y, s);
+    return launch_shape<T, TO, S, 4, 4, 4>(d, c, wfrag, x, y, s);
 }
 
 template <typename T, typename TO>
@@ -252,7 +297,7 @@ rtoss_status launch_typed(const rtoss_wdesc& d, const ConvParams& c, const char*
 
 bool dense3x3_shape_ok(const rtoss_wdesc& d)
 {
-    return d.ksize == 3 && (d.dt == RTOSS_F16 || d.dt == RTOSS_BF16) && d.Ci % 32 == 0 && d.Co % 16 == 0;
+    return d.ksize == 3 && d.Ci % stage_channels(d.dt) == 0 && d.Co % 16 == 0;
 }
 
 size_t dense3x3_section_bytes(const rtoss_wdesc& d) { return frag_bytes(d) + zero_bytes(d); }
@@ -267,8 +312,10 @@ rtoss_status launch_pack_dense3x3(const rtoss_wdesc& d, const void* w, const uin
     dim3 grid((unsigned)(job.blocks + (items + zero_items + 255) / 256)), block(256);
     if (d.dt == RTOSS_F16)
         pack_dense3x3_kernel<f16_t><<<grid, block, 0, s>>>((const f16_t*)w, idx, dict, (char*)section, d.Co, d.Ci, cblocks, items, zero_items, job);
-    else
+    else if (d.dt == RTOSS_BF16)
         pack_dense3x3_kernel<bf16_t><<<grid, block, 0, s>>>((const bf16_t*)w, idx, dict, (char*)section, d.Co, d.Ci, cblocks, items, zero_items, job);
+    else
+        pack_dense3x3_kernel<float><<<grid, block, 0, s>>>((const float*)w, idx, dict, (char*)section, d.Co, d.Ci, cblocks, items, zero_items, job);
     return check_hip(hipGetLastError(), "pack dense3x3 launch");
 }
 
@@ -277,6 +324,7 @@ rtoss_status launch_conv3x3_dense(const rtoss_wdesc& d, const ConvParams& c, con
 {
     const char* wf = (const char*)section;
     const bool f32out = c.out_dt == RTOSS_F32;
+    if (d.dt == RTOSS_F32) return launch_typed<float, float>(d, c, wf, x, y, s);
     if (d.dt == RTOSS_F16)
         return f32out ? launch_typed<f16_t, float>(d, c, wf, x, y, s) : launch_typed<f16_t, f16_t>(d, c, wf, x, y, s);
     return f32out ? launch_typed<bf16_t, float>(d, c, wf, x, y, s) : launch_typed<bf16_t, bf16_t>(d, c, wf, x, y, s);

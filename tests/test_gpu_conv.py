@@ -122,6 +122,25 @@ def test_conv3x3_dense_mode_shapes(dt, case):
     run_case(dt, N, Ci, Co, H, W, 3, stride, k, relu, seed=hash(case) % 10000 + dt, w_std=0.02, rule=rule)
 
 
+FP32_MATRIX_CORE = [
+    # fp32 tensors with Ci % 16 == 0 and Co % 16 == 0: dense mode on the fp32 matrix instruction, small
+    # launches (16 channels x 4x16 positions per workgroup) and large ones (64 channels x 16x16)
+    # N, Ci, Co,  H,  W, stride, k, relu
+    (1, 16, 16, 4, 4, 1, 3, False),
+    (1, 64, 64, 56, 56, 1, 4, False),
+    (2, 48, 80, 19, 21, 1, 2, True),
+    (1, 32, 48, 33, 18, 2, 3, False),
+    (16, 16, 64, 64, 64, 1, 3, True),
+    (20, 16, 32, 63, 65, 2, 2, False),
+]
+
+
+@pytest.mark.parametrize("case", FP32_MATRIX_CORE)
+def test_conv3x3_fp32_matrix_core_shapes(case):
+    N, Ci, Co, H, W, stride, k, relu = case
+    run_case(wl.F32, N, Ci, Co, H, W, 3, stride, k, relu, seed=hash(case) % 10000, w_std=0.05)
+
+
 def test_conv3x3_matrix_core_dictionaries():
     # every pair of taps (36 patterns): still at most 2 corners and 2 edge midpoints -> sparse path
     run_case(wl.F16, 1, 64, 64, 12, 12, 3, 1, 2, False, seed=31, rule=B.RULE_ALL)
