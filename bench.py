@@ -83,8 +83,8 @@ def parse():
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build measures one GPU only; --gpus %d is not supported "
-              "(the path shards by batch with no collective, see DESIGN.md)" % args.gpus, file=sys.stderr)
+        print("bench.py: one GPU only; --gpus %d is not supported (the path would shard by batch, with no "
+              "collective; this program measures a single device)" % args.gpus, file=sys.stderr)
         return 2
 
     import torch
