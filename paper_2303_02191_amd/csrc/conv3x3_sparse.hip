@@ -878,6 +878,8 @@ rtoss_status launch_typed(const rtoss_wdesc& d, const ConvParams& c, const char*
     // Stride 2: the input tile of a 16x16 output tile (33x33 positions) nearly fills the LDS by itself.
     // Half-height tiles (8x16 outputs, 17x33 inputs) with 64 channels per workgroup need 72 KB, so two
     // workgroups share a compute unit and overlap each other's copies, and small images pad less.
+    // (a single-stage layer is all copy, short multiply, store: quarter-height tiles put three workgroups on a unit)
+    if (d.Ci == 32) return launch_variant_sb<T, TO, 2, 4, 1, 1, 4>(d, c, wfrag, x, y, s);
     return launch_variant_sb<T, TO, 2, 4, 2, 2, 4>(d, c, wfrag, x, y, s);
 }
 
