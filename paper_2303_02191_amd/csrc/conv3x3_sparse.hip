@@ -51,9 +51,9 @@ namespace {
 // Packed weight fragments: per (stage of 32 input channels, tile of 16 output channels)
 //   5 operand fragments of 64 lanes x 16 bytes: corner step 0/1, edge step 0/1, centre
 //   then 2 index words per lane: [corner][lane], [edge][lane]; low half = step 0, high = step 1
+// (which output channel a row of a tile is: tile_row_channel)
 constexpr int kFragBytes = 1024;
 constexpr int kTileBytes = 5 * kFragBytes + 2 * 64 * 4;  // 5632
-constexpr bool kDirectEpilogue = false;                 // store D fragments directly (false: transpose through LDS)
 
 __device__ __forceinline__ int tap_of_slot(int group, int f)
 {
@@ -66,6 +66,22 @@ __device__ __forceinline__ int tap_of_slot(int group, int f)
 __device__ __forceinline__ int stage_channel(int q, int g, int half)
 {
     return 8 * (2 * (q & 1) + (g >> 1)) + 4 * half + 2 * (q >> 1) + (g & 1);
+}
+
+// Output channel held by row r of channel tile mt.  Within a group of 4 tiles (64 channels) the rows
+// are dealt so that the accumulator values one lane holds after the multiplication -- rows
+// 4q .. 4q+3 of every tile -- are, for each pair of tiles, the 8 consecutive channels
+// 64*(mt/4) + 32*(pair) + 8q .. +7.  A 16-bit epilogue then stores 16 bytes per lane and pair, and the
+// four lane quarters of a position write one contiguous 64-byte run, without any exchange between lanes.
+__device__ __forceinline__ int tile_row_channel(int mt, int r)
+{
+    return 64 * (mt >> 2) + 32 * ((mt & 3) >> 1) + 8 * (r >> 2) + 4 * (mt & 1) + (r & 3);
+}
+// first of the 4 consecutive channels that quarter q of a lane holds of tile mm (counted from the
+// first channel of mm's group of 4 tiles when mm < 4; mm may run over several groups)
+__device__ __forceinline__ int tile_quarter_offset(int mm, int q)
+{
+    return 64 * (mm >> 2) + 32 * ((mm & 3) >> 1) + 8 * q + 4 * (mm & 1);
 }
 
 struct SparsePackArgs {
@@ -105,7 +121,7 @@ __device__ __forceinline__ void pack_sparse3x3_body(const SparsePackArgs& a, con
     const int mt = (int)(tile % m_tiles);
     const int cb = (int)(tile / m_tiles);
     const int r = lane % 16, q = lane / 16;
-    const int co = 16 * mt + r;
+    const int co = tile_row_channel(mt, r);
     char* tile_out = out + tile * kTileBytes;
     uint16_t vals[8];
     if (step == 4) {  // dense centre tap: K = 8q + j
@@ -214,7 +230,8 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
                                                                 const char* __restrict__ wfrag,
                                                                 const char* __restrict__ zeros, int H, int W, int Ci,
                                                                 int Co, int Ho, int Wo, int m_tiles_total,
-                                                                int tiles_c, Epilogue ep)
+                                                                int tiles_c, int tiles_per_image, int co_blocks, int total,
+                                                                int work_per_xcd, Epilogue ep)
 {
     using G = Geom<S, RT, CT>;
     static_assert(RT * CT == 4 * TN, "four waves share the position blocks of a workgroup");
@@ -231,9 +248,15 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int tile_r = blockIdx.x / tiles_c, tile_c = blockIdx.x % tiles_c;
-    const int mt0 = blockIdx.y * TM;
-    const int n_img = blockIdx.z;
+    // Workgroups are dealt to the 8 XCDs in turn.  Work items are numbered with the channel block
+    // fastest and each XCD takes a contiguous range, so the workgroups that read the same activation
+    // tile (one per channel block) run on one XCD at about the same time and share its L2.
+    const int work = (blockIdx.x % 8) * work_per_xcd + blockIdx.x / 8;
+    if (work >= total) return;
+    const int mt0 = (work % co_blocks) * TM;
+    const int tile = (work / co_blocks) % tiles_per_image;
+    const int n_img = (work / co_blocks) / tiles_per_image;
+    const int tile_r = tile / tiles_c, tile_c = tile % tiles_c;
     const int oh0 = tile_r * G::TH, ow0 = tile_c * G::TW;
     const int ih0 = oh0 * S - 1, iw0 = ow0 * S - 1;
     const int stages = Ci / 32;
@@ -248,7 +271,9 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
         const int xr = pos / G::LW, xc = pos % G::LW;
         const int ih = ih0 + xr, iw = iw0 + xc;
         const bool inside = q < 4 && xr < G::IH && xc < G::IW && ih >= 0 && ih < H && iw >= 0 && iw < W;
-        x_ptr[k] = inside ? (const char*)x + ((((int64_t)n_img * H + ih) * W + iw) * Ci + q * 8) * 2 : zeros;
+        // offset in 16-byte chunks: fits 31 bits (checked by the launcher)
+        const int off = ((n_img * H + ih) * W + iw) * (Ci >> 3) + q;
+        x_ptr[k] = inside ? (const char*)x + (int64_t)off * 16 : zeros;
     }
     const char* a_src = wfrag + (int64_t)mt0 * kTileBytes + lane * 16;
     const int64_t a_stage_stride = (int64_t)m_tiles_total * kTileBytes;
@@ -281,25 +306,41 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
         __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's copies have landed in LDS
         __syncthreads();                     // ... and everybody's
 
+        // Operand reads run ahead of the matrix instructions that use them: the centre step's and the
+        // corner group's are issued together, the edge group's behind the centre step.  (The matrix
+        // instructions are asm statements that loads are not moved across: source order is issue order.)
+        u32x4 bc[TN], ac[TM];
+        u32x4 rr[2][TN][4], as[2][TM][2];
+        int iw2[2][TM];
+        auto load_group = [&](int group) {
 #pragma unroll
-        for (int group = 0; group < 2; ++group) {
-            // B operands of both sparse steps of this tap group, for all TN position blocks
-            u32x8 bf[2][TN];
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                u32x4 rr[4];
+            for (int j = 0; j < TN; ++j)
 #pragma unroll
                 for (int f = 0; f < 4; ++f) {
                     const int t = group == 0 ? ((f & 1) * 2 + (f >> 1) * 6) : (2 * f + 1);
-                    rr[f] = *(const u32x4*)(lds_x + xb[j] + ((t / 3) * G::LW + (t % 3)) * kXPosBytes);
+                    rr[group][j][f] = *(const u32x4*)(lds_x + xb[j] + ((t / 3) * G::LW + (t % 3)) * kXPosBytes);
                 }
-                // element 4*c + f of a step = channel c (of this lane's 4), tap slot f
+#pragma unroll
+            for (int m = 0; m < TM; ++m) {
+                const char* at = lds_a + m * kTileBytes;
+                iw2[group][m] = *(const int*)(at + 5 * kFragBytes + (group * 64 + lane) * 4);
+                as[group][m][0] = *(const u32x4*)(at + (group * 2 + 0) * kFragBytes + lane * 16);
+                as[group][m][1] = *(const u32x4*)(at + (group * 2 + 1) * kFragBytes + lane * 16);
+            }
+        };
+        auto run_group = [&](int group) {
+            // B operands of both sparse steps of this tap group: element 4*c + f of a step = channel c
+            // (of this lane's 4), tap slot f
+            u32x8 bf[2][TN];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const u32x4(&r)[4] = rr[group][j];
 #pragma unroll
                 for (int half = 0; half < 2; ++half) {
-                    const uint32_t s0 = half ? rr[0].z : rr[0].x, s1 = half ? rr[1].z : rr[1].x;
-                    const uint32_t s2 = half ? rr[2].z : rr[2].x, s3 = half ? rr[3].z : rr[3].x;
-                    const uint32_t u0 = half ? rr[0].w : rr[0].y, u1 = half ? rr[1].w : rr[1].y;
-                    const uint32_t u2 = half ? rr[2].w : rr[2].y, u3 = half ? rr[3].w : rr[3].y;
+                    const uint32_t s0 = half ? r[0].z : r[0].x, s1 = half ? r[1].z : r[1].x;
+                    const uint32_t s2 = half ? r[2].z : r[2].x, s3 = half ? r[3].z : r[3].x;
+                    const uint32_t u0 = half ? r[0].w : r[0].y, u1 = half ? r[1].w : r[1].y;
+                    const uint32_t u2 = half ? r[2].w : r[2].y, u3 = half ? r[3].w : r[3].y;
                     u32x8 b;
                     b[0] = __builtin_amdgcn_perm(s1, s0, 0x05040100u);  // channel 0: taps 0,1
                     b[1] = __builtin_amdgcn_perm(s3, s2, 0x05040100u);  // channel 0: taps 2,3
@@ -314,32 +355,32 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
             }
 #pragma unroll
             for (int m = 0; m < TM; ++m) {
-                const char* at = lds_a + m * kTileBytes;
-                const int iw2 = *(const int*)(at + 5 * kFragBytes + (group * 64 + lane) * 4);
-                const u32x4 a0 = *(const u32x4*)(at + (group * 2 + 0) * kFragBytes + lane * 16);
-                const u32x4 a1 = *(const u32x4*)(at + (group * 2 + 1) * kFragBytes + lane * 16);
 #pragma unroll
-                for (int j = 0; j < TN; ++j) Mat<T>::template sparse<0>(a0, bf[0][j], acc[m][j], iw2);
+                for (int j = 0; j < TN; ++j) Mat<T>::template sparse<0>(as[group][m][0], bf[0][j], acc[m][j], iw2[group][m]);
 #pragma unroll
-                for (int j = 0; j < TN; ++j) Mat<T>::template sparse<1>(a1, bf[1][j], acc[m][j], iw2);
+                for (int j = 0; j < TN; ++j) Mat<T>::template sparse<1>(as[group][m][1], bf[1][j], acc[m][j], iw2[group][m]);
             }
-        }
-        {  // centre tap: dense step over the 32 channels of the stage
-            u32x4 bc[TN];
+        };
 #pragma unroll
-            for (int j = 0; j < TN; ++j) bc[j] = *(const u32x4*)(lds_x + xb[j] + (G::LW + 1) * kXPosBytes);
+        for (int j = 0; j < TN; ++j) bc[j] = *(const u32x4*)(lds_x + xb[j] + (G::LW + 1) * kXPosBytes);
 #pragma unroll
-            for (int m = 0; m < TM; ++m) {
-                const u32x4 a = *(const u32x4*)(lds_a + m * kTileBytes + 4 * kFragBytes + lane * 16);
+        for (int m = 0; m < TM; ++m) ac[m] = *(const u32x4*)(lds_a + m * kTileBytes + 4 * kFragBytes + lane * 16);
+        load_group(0);
+        // centre tap: dense step over the 32 channels of the stage
 #pragma unroll
-                for (int j = 0; j < TN; ++j) Mat<T>::dense(a, bc[j], acc[m][j]);
-            }
-        }
+        for (int m = 0; m < TM; ++m)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) Mat<T>::dense(ac[m], bc[j], acc[m][j]);
+        load_group(1);
+        run_group(0);
+        run_group(1);
     }
 
     // the last matrix instructions must have written their accumulators before anything reads them
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
-    // ---- epilogue: D lane holds column nn (position), rows 4*qq .. 4*qq+3 (output channels) ----
+    // ---- epilogue: a D lane holds column nn (position) and rows 4*qq .. 4*qq+3 of every channel tile,
+    // which tile_row_channel makes 8 consecutive output channels per pair of tiles ----
+    static_assert(TM % 4 == 0, "whole groups of 4 channel tiles");
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         const int blk = wave * TN + j;
@@ -347,22 +388,27 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
         if (oh >= Ho || ow >= Wo) continue;
         TO* yp = y + (((int64_t)n_img * Ho + oh) * Wo + ow) * Co;
 #pragma unroll
-        for (int m = 0; m < TM; ++m) {
-            const int co = 16 * (mt0 + m) + 4 * qq;
-            if (co >= Co) continue;
-            float vv[4] = {acc[m][j].x, acc[m][j].y, acc[m][j].z, acc[m][j].w};
-            epi_scale_bias_act<4>(vv, ep, co);
-            epi_residual<TO, 4>(vv, ep, (yp - y) + co);
-            const f32x4 v = {vv[0], vv[1], vv[2], vv[3]};
+        for (int mp = 0; mp < TM; mp += 2) {
+            const int co = 16 * mt0 + tile_quarter_offset(mp, qq);
+            if (co >= Co) continue;  // Co is a multiple of 16 and the run of 8 starts at a multiple of 8: all in or all out
+            float vv[8];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                vv[e] = acc[mp][j][e];
+                vv[4 + e] = acc[mp + 1][j][e];
+            }
+            epi_scale_bias_act<8>(vv, ep, co);
+            epi_residual<TO, 8>(vv, ep, (yp - y) + co);
             if constexpr (sizeof(TO) == 4) {
-                *(f32x4*)(yp + co) = v;
+                *(f32x4*)(yp + co) = f32x4{vv[0], vv[1], vv[2], vv[3]};
+                *(f32x4*)(yp + co + 4) = f32x4{vv[4], vv[5], vv[6], vv[7]};
             } else {
-                TO o[4];
-                store_from_f32<TO>(&o[0], v.x);
-                store_from_f32<TO>(&o[1], v.y);
-                store_from_f32<TO>(&o[2], v.z);
-                store_from_f32<TO>(&o[3], v.w);
-                *(uint2*)(yp + co) = *(const uint2*)o;
+                u32x4 o;
+                o.x = pack2_from_f32<TO>(vv[0], vv[1]);
+                o.y = pack2_from_f32<TO>(vv[2], vv[3]);
+                o.z = pack2_from_f32<TO>(vv[4], vv[5]);
+                o.w = pack2_from_f32<TO>(vv[6], vv[7]);
+                *(u32x4*)(yp + co) = o;
             }
         }
     }
@@ -635,7 +681,7 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
         constexpr int EB = (int)sizeof(TO);
         constexpr int HALVES = EB == 4 ? 2 : 1;
         constexpr int TMH = TM / HALVES;
-        static_assert(TM % HALVES == 0, "channel tiles must split evenly");
+        static_assert(TM % HALVES == 0 && TMH % 4 == 0, "each half is whole groups of 4 channel tiles (tile_row_channel)");
         constexpr int ROW = TMH * 16 * EB + (EB == 2 ? 8 : 16);  // padded row pitch: spreads the banks
         // position blocks staged together: as many as fit when the four waves share one region
         constexpr int JG = (REGION / (4 * 16 * ROW)) < TN ? (REGION / (4 * 16 * ROW)) : TN;
@@ -649,37 +695,7 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
         // 64-bit address of the tile's first output element once; everything else is 32-bit
         TO* const y_tile = y + (((int64_t)t_n * Ho + t_oh0) * Wo + t_ow0) * Co;
         const float relu_floor = ep.act == 1 ? 0.f : -__builtin_inff();
-        if constexpr (kDirectEpilogue) {
-            // straight from the D fragments: 4 consecutive channels per lane and store
-            const int pr_e = nn_e >> 2, pc_e = nn_e & 3;
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int blk = blk0 + j;
-                const int dr = 4 * (blk / CT) + pr_e, dc = 4 * (blk % CT) + pc_e;
-                const bool inside = t_oh0 + dr < Ho && t_ow0 + dc < Wo;
-                TO* yp = y_tile + (dr * Wo + dc) * Co + 16 * t_mt0 + 4 * qq_e;
-#pragma unroll
-                for (int m = 0; m < TM; ++m) {
-                    f32x4 v = acc[m][j];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        float r;
-                        asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(v[e]), "v"(relu_floor));
-                        v[e] = r;
-                    }
-                    if (inside && 16 * (t_mt0 + m) < Co) {
-                        if constexpr (EB == 4) {
-                            *(f32x4*)(yp + 16 * m) = v;
-                        } else {
-                            uint2 o;
-                            o.x = pack2_from_f32<TO>(v.x, v.y);
-                            o.y = pack2_from_f32<TO>(v.z, v.w);
-                            *(uint2*)(yp + 16 * m) = o;
-                        }
-                    }
-                }
-            }
-        } else {
+        {
 #pragma unroll
         for (int h = 0; h < HALVES; ++h) {
 #pragma unroll
@@ -701,7 +717,7 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
                     const int64_t pos_f = (y_tile - y) + (int64_t)(dr_f * Wo + dc_f) * Co;
 #pragma unroll
                     for (int mm = 0; mm < TMH; ++mm) {
-                        const int co4 = 16 * (t_mt0 + h * TMH + mm) + 4 * qq_e;
+                        const int co4 = 16 * (t_mt0 + h * TMH) + tile_quarter_offset(mm, qq_e);
                         if (inside_f && co4 < Co) {
                             float vv[4] = {vals[mm].x, vals[mm].y, vals[mm].z, vals[mm].w};
                             epi_scale_bias_act<4>(vv, ep, co4);
@@ -721,7 +737,7 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
                 }
 #pragma unroll
                 for (int mm = 0; mm < TMH; ++mm) {
-                    char* dst = stage_out + (jj * 16 + nn_e) * ROW + (16 * mm + 4 * qq_e) * EB;
+                    char* dst = stage_out + (jj * 16 + nn_e) * ROW + tile_quarter_offset(mm, qq_e) * EB;
                     if constexpr (EB == 4) {
                         *(f32x4*)dst = vals[mm];
                     } else {
@@ -839,10 +855,13 @@ rtoss_status launch_variant_sb(const rtoss_wdesc& d, const ConvParams& c, const 
             return st;
         attr_set = true;
     }
-    if (c.N > 65535 || co_blocks > 65535) return fail(RTOSS_ESHAPE, "conv: batch or channel count too large");
-    dim3 grid((unsigned)(tiles_r * tiles_c), (unsigned)co_blocks, (unsigned)c.N), block(256);
+    const int64_t total = (int64_t)tiles_r * tiles_c * co_blocks * c.N;
+    if (total > 0x3fffffff) return fail(RTOSS_ESHAPE, "conv: too many tiles");
+    if ((int64_t)c.N * c.H * c.W * d.Ci / 8 > 0x7fffffff) return fail(RTOSS_ESHAPE, "conv: input too large for 32-bit chunk offsets");
+    const int work_per_xcd = (int)((total + 7) / 8);
+    dim3 grid((unsigned)(work_per_xcd * 8)), block(256);
     kern<<<grid, block, smem, s>>>((const T*)x, (TO*)y, wfrag, wfrag + fragment_bytes(d), c.H, c.W, d.Ci, d.Co, Ho, Wo,
-                                   m_tiles_total, tiles_c, c.ep);
+                                   m_tiles_total, tiles_c, tiles_r * tiles_c, co_blocks, (int)total, work_per_xcd, c.ep);
     return check_hip(hipGetLastError(), "conv3x3 sparse launch");
 }
 
