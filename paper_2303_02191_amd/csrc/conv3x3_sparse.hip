@@ -225,7 +225,7 @@ template <int TN> struct JobSchedule {
 // workgroups share a compute unit and hide each other's copy latency and epilogue.  Used for stride 2
 // (whose activation tile is too large to keep twice in LDS) and for layers too small for the
 // pipelined kernel's 128-channel, 8-stage appetite: TM = 4 covers 64 output channels per workgroup.
-template <typename T, typename TO, int S, int TM, int TN, int RT, int CT>
+template <typename T, typename TO, int S, int TM, int TN, int RT, int CT, bool AHEAD>
 __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restrict__ x, TO* __restrict__ y,
                                                                 const char* __restrict__ wfrag,
                                                                 const char* __restrict__ zeros, int H, int W, int Ci,
@@ -306,13 +306,15 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
         __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's copies have landed in LDS
         __syncthreads();                     // ... and everybody's
 
-        // Operand reads run ahead of the matrix instructions that use them: the centre step's and the
-        // corner group's are issued together, the edge group's behind the centre step.  (The matrix
+        // AHEAD: operand reads run ahead of the matrix instructions that use them: the centre step's and
+        // the corner group's are issued together, the edge group's behind the centre step.  (The matrix
         // instructions are asm statements that loads are not moved across: source order is issue order.)
+        // This hides the LDS latency inside a workgroup; shallow layers over large images, which live on
+        // hiding HBM latency across workgroups, do better without it and with the registers it costs.
         u32x4 bc[TN], ac[TM];
         u32x4 rr[2][TN][4], as[2][TM][2];
         int iw2[2][TM];
-        auto load_group = [&](int group) {
+        auto load_group_x = [&](int group) {
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -320,18 +322,22 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
                     const int t = group == 0 ? ((f & 1) * 2 + (f >> 1) * 6) : (2 * f + 1);
                     rr[group][j][f] = *(const u32x4*)(lds_x + xb[j] + ((t / 3) * G::LW + (t % 3)) * kXPosBytes);
                 }
-#pragma unroll
-            for (int m = 0; m < TM; ++m) {
-                const char* at = lds_a + m * kTileBytes;
-                iw2[group][m] = *(const int*)(at + 5 * kFragBytes + (group * 64 + lane) * 4);
-                as[group][m][0] = *(const u32x4*)(at + (group * 2 + 0) * kFragBytes + lane * 16);
-                as[group][m][1] = *(const u32x4*)(at + (group * 2 + 1) * kFragBytes + lane * 16);
-            }
         };
-        auto run_group = [&](int group) {
-            // B operands of both sparse steps of this tap group: element 4*c + f of a step = channel c
-            // (of this lane's 4), tap slot f
-            u32x8 bf[2][TN];
+        auto load_group_a = [&](int group, int m) {
+            const char* at = lds_a + m * kTileBytes;
+            iw2[group][m] = *(const int*)(at + 5 * kFragBytes + (group * 64 + lane) * 4);
+            as[group][m][0] = *(const u32x4*)(at + (group * 2 + 0) * kFragBytes + lane * 16);
+            as[group][m][1] = *(const u32x4*)(at + (group * 2 + 1) * kFragBytes + lane * 16);
+        };
+        auto load_group = [&](int group) {
+            load_group_x(group);
+#pragma unroll
+            for (int m = 0; m < TM; ++m) load_group_a(group, m);
+        };
+        // B operands of both sparse steps of a tap group: element 4*c + f of a step = channel c (of this
+        // lane's 4), tap slot f
+        u32x8 bf[2][TN];
+        auto permute_group = [&](int group) {
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 const u32x4(&r)[4] = rr[group][j];
@@ -353,27 +359,51 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
                     bf[half][j] = b;
                 }
             }
-#pragma unroll
-            for (int m = 0; m < TM; ++m) {
-#pragma unroll
-                for (int j = 0; j < TN; ++j) Mat<T>::template sparse<0>(as[group][m][0], bf[0][j], acc[m][j], iw2[group][m]);
-#pragma unroll
-                for (int j = 0; j < TN; ++j) Mat<T>::template sparse<1>(as[group][m][1], bf[1][j], acc[m][j], iw2[group][m]);
-            }
         };
+        auto multiply_group = [&](int group, int m) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) bc[j] = *(const u32x4*)(lds_x + xb[j] + (G::LW + 1) * kXPosBytes);
+            for (int j = 0; j < TN; ++j) Mat<T>::template sparse<0>(as[group][m][0], bf[0][j], acc[m][j], iw2[group][m]);
 #pragma unroll
-        for (int m = 0; m < TM; ++m) ac[m] = *(const u32x4*)(lds_a + m * kTileBytes + 4 * kFragBytes + lane * 16);
-        load_group(0);
-        // centre tap: dense step over the 32 channels of the stage
+            for (int j = 0; j < TN; ++j) Mat<T>::template sparse<1>(as[group][m][1], bf[1][j], acc[m][j], iw2[group][m]);
+        };
+        auto run_group = [&](int group) {
+            permute_group(group);
 #pragma unroll
-        for (int m = 0; m < TM; ++m)
+            for (int m = 0; m < TM; ++m) multiply_group(group, m);
+        };
+        auto load_centre = [&]() {
 #pragma unroll
-            for (int j = 0; j < TN; ++j) Mat<T>::dense(ac[m], bc[j], acc[m][j]);
-        load_group(1);
-        run_group(0);
-        run_group(1);
+            for (int j = 0; j < TN; ++j) bc[j] = *(const u32x4*)(lds_x + xb[j] + (G::LW + 1) * kXPosBytes);
+#pragma unroll
+            for (int m = 0; m < TM; ++m) ac[m] = *(const u32x4*)(lds_a + m * kTileBytes + 4 * kFragBytes + lane * 16);
+        };
+        auto run_centre = [&]() {  // centre tap: dense step over the 32 channels of the stage
+#pragma unroll
+            for (int m = 0; m < TM; ++m)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) Mat<T>::dense(ac[m], bc[j], acc[m][j]);
+        };
+        if constexpr (AHEAD) {
+            load_centre();
+            load_group(0);
+            run_centre();
+            load_group(1);
+            run_group(0);
+            run_group(1);
+        } else {  // few operands live at a time: fewer registers, one more workgroup per compute unit
+#pragma unroll
+            for (int group = 0; group < 2; ++group) {
+                load_group_x(group);
+                permute_group(group);
+#pragma unroll
+                for (int m = 0; m < TM; ++m) {
+                    load_group_a(group, m);
+                    multiply_group(group, m);
+                }
+            }
+            load_centre();
+            run_centre();
+        }
     }
 
     // the last matrix instructions must have written their accumulators before anything reads them
@@ -836,7 +866,7 @@ rtoss_status launch_variant(const rtoss_wdesc& d, const ConvParams& c, const cha
     return launch_variant_f<T, TO, S, TM, TN, RT, CT, false>(d, c, wfrag, x, y, s);
 }
 
-template <typename T, typename TO, int S, int TM, int TN, int RT, int CT>
+template <typename T, typename TO, int S, int TM, int TN, int RT, int CT, bool AHEAD = true>
 rtoss_status launch_variant_sb(const rtoss_wdesc& d, const ConvParams& c, const char* wfrag, const void* x, void* y,
                             hipStream_t s)
 {
@@ -847,7 +877,7 @@ rtoss_status launch_variant_sb(const rtoss_wdesc& d, const ConvParams& c, const 
     const int co_blocks = ((d.Co + 15) / 16 + TM - 1) / TM;
     constexpr int x_copies_per_wave = ((G::x_bytes / 16 + 63) / 64 + 3) / 4;
     const size_t smem = (size_t)TM * kTileBytes + (size_t)x_copies_per_wave * 4096;
-    auto kern = conv3x3_sparse_sb_kernel<T, TO, S, TM, TN, RT, CT>;
+    auto kern = conv3x3_sparse_sb_kernel<T, TO, S, TM, TN, RT, CT, AHEAD>;
     static bool attr_set = false;  // per instantiation
     if (!attr_set) {
         if (rtoss_status st = check_hip(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem),
@@ -877,6 +907,8 @@ rtoss_status launch_typed(const rtoss_wdesc& d, const ConvParams& c, const char*
     if (c.stride == 1) {
         // 8x16-position tiles for these: 38 KB of LDS, four workgroups per compute unit.  (Measured: more
         // resident workgroups beat double-buffering inside one, and beat 16x16 tiles, on every such layer.)
+        // (up to 64 input channels are one or two stages: nothing to gain inside a workgroup, see AHEAD)
+        if (d.Ci <= 64) return launch_variant_sb<T, TO, 1, 4, 2, 2, 4, false>(d, c, wfrag, x, y, s);
         if (small) return launch_variant_sb<T, TO, 1, 4, 2, 2, 4>(d, c, wfrag, x, y, s);
         // ... and so do launches that would leave compute units idle with 128 channels per workgroup
         const int64_t tiles8 = (int64_t)((c.H + 15) / 16) * ((c.W + 15) / 16) * c.N * (((d.Co + 15) / 16 + 7) / 8);

@@ -50,7 +50,10 @@ __global__ __launch_bounds__(256) void pack_stem_kernel(const T* __restrict__ w,
     const int item = (blockIdx.x - job.blocks) * 256 + threadIdx.x;  // (m_tile, lane)
     if (item >= m_tiles * 64) return;
     const int lane = item % 64, mt = item / 64;
-    const int co = 16 * mt + lane % 16, q = lane / 16;
+    // Rows are dealt over each pair of channel tiles so that the 4 + 4 accumulator values a lane holds
+    // (rows 4q .. 4q+3 of both tiles) are the 8 consecutive channels 32*(mt/2) + 8q .. +7.
+    const int r = lane % 16, q = lane / 16;
+    const int co = 32 * (mt >> 1) + 8 * (r >> 2) + 4 * (mt & 1) + (r & 3);
     uint16_t v[8];
     for (int j = 0; j < 8; ++j) {
         const int k = 8 * q + j;
@@ -73,7 +76,7 @@ __global__ __launch_bounds__(256) void pack_stem_kernel(const T* __restrict__ w,
 // Ci is a template parameter: the index arithmetic below divides by it (and by 3 * Ci) per element, which
 // as run-time divisions made the kernel bound by integer ALU work.
 template <typename T, typename TO, int S, int TM, int Ci>
-__global__ __launch_bounds__(256) void conv3x3_stem_kernel(const T* __restrict__ x, TO* __restrict__ y,
+__global__ __launch_bounds__(256, TM == 2 ? 8 : 4) void conv3x3_stem_kernel(const T* __restrict__ x, TO* __restrict__ y,
                                                            const char* __restrict__ wfrag, int H, int W, int Co,
                                                            int Ho, int Wo, int tiles_c, Epilogue ep)
 {
@@ -89,14 +92,24 @@ __global__ __launch_bounds__(256) void conv3x3_stem_kernel(const T* __restrict__
     const int ih0 = oh0 * S - 1, iw0 = ow0 * S - 1;
     constexpr int rowlen = IW * Ci;  // halves per row actually used
 
-    // ---- stage the input tile (with halo, zero padded): consecutive lanes read consecutive halves ----
+    // ---- stage the input tile (with halo, zero padded): consecutive lanes read consecutive halves; all of a
+    // lane's loads are issued before the first one is used ----
     const uint16_t* xin = (const uint16_t*)x;
-    for (int e = tid; e < IH * rowlen; e += 256) {
+    constexpr int kElems = IH * rowlen, kLoads = (kElems + 255) / 256;
+    uint16_t staged[kLoads];
+#pragma unroll
+    for (int i = 0; i < kLoads; ++i) {
+        const int e = tid + 256 * i;
         const int pr = e / rowlen, off = e - pr * rowlen;
         const int ih = ih0 + pr, iw = iw0 + off / Ci;
-        uint16_t v = 0;
-        if (ih >= 0 && ih < H && iw >= 0 && iw < W) v = xin[(((int64_t)n_img * H + ih) * W + iw0) * Ci + off];
-        xs[pr * MAXROW + off] = v;
+        staged[i] = 0;
+        if (e < kElems && ih >= 0 && ih < H && iw >= 0 && iw < W) staged[i] = xin[(((int64_t)n_img * H + ih) * W + iw0) * Ci + off];
+    }
+#pragma unroll
+    for (int i = 0; i < kLoads; ++i) {
+        const int e = tid + 256 * i;
+        const int pr = e / rowlen, off = e - pr * rowlen;
+        if (e < kElems) xs[pr * MAXROW + off] = staged[i];
     }
     // weight fragments stay in registers: TM tiles of 16 output channels
     u32x4 afrag[TM];
@@ -129,22 +142,26 @@ __global__ __launch_bounds__(256) void conv3x3_stem_kernel(const T* __restrict__
         const int oh = oh0 + r, ow = ow0 + c;
         const bool inside = oh < Ho && ow < Wo;
         TO* yp = y + (((int64_t)n_img * Ho + oh) * Wo + ow) * Co;
+        static_assert(TM % 2 == 0, "pairs of channel tiles");
 #pragma unroll
-        for (int m = 0; m < TM; ++m) {
-            const f32x4 d4 = Dense16<T>::mma(afrag[m], b, f32x4{0.f, 0.f, 0.f, 0.f});
-            const int co = 16 * m + 4 * qq;
+        for (int mp = 0; mp < TM; mp += 2) {
+            const f32x4 d0 = Dense16<T>::mma(afrag[mp], b, f32x4{0.f, 0.f, 0.f, 0.f});
+            const f32x4 d1 = Dense16<T>::mma(afrag[mp + 1], b, f32x4{0.f, 0.f, 0.f, 0.f});
+            const int co = 16 * mp + 8 * qq;  // this lane's 8 consecutive channels of the pair
             if (inside && co < Co) {
-                float vv[4] = {d4.x, d4.y, d4.z, d4.w};
-                epi_scale_bias_act<4>(vv, ep, co);
-                epi_residual<TO, 4>(vv, ep, (yp - y) + co);
-                const f32x4 v = {vv[0], vv[1], vv[2], vv[3]};
+                float vv[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
+                epi_scale_bias_act<8>(vv, ep, co);
+                epi_residual<TO, 8>(vv, ep, (yp - y) + co);
                 if constexpr (sizeof(TO) == 4) {
-                    *(f32x4*)(yp + co) = v;
+                    *(f32x4*)(yp + co) = f32x4{vv[0], vv[1], vv[2], vv[3]};
+                    *(f32x4*)(yp + co + 4) = f32x4{vv[4], vv[5], vv[6], vv[7]};
                 } else {
-                    uint2 o;
-                    o.x = pack2_from_f32<TO>(v.x, v.y);
-                    o.y = pack2_from_f32<TO>(v.z, v.w);
-                    *(uint2*)(yp + co) = o;
+                    u32x4 o;
+                    o.x = pack2_from_f32<TO>(vv[0], vv[1]);
+                    o.y = pack2_from_f32<TO>(vv[2], vv[3]);
+                    o.z = pack2_from_f32<TO>(vv[4], vv[5]);
+                    o.w = pack2_from_f32<TO>(vv[6], vv[7]);
+                    *(u32x4*)(yp + co) = o;
                 }
             }
         }

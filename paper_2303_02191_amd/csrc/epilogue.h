@@ -48,9 +48,13 @@ template <int N> __device__ __forceinline__ void epi_scale_bias_act(float (&v)[N
             for (int i = 0; i < 4; ++i) v[4 * g + i] += b[i];
         }
     }
-    if (ep.act) {
+    // (one uniform branch per activation around the whole run, not one per value)
+    if (ep.act == 1) {
 #pragma unroll
-        for (int i = 0; i < N; ++i) v[i] = epi_act(v[i], ep.act);
+        for (int i = 0; i < N; ++i) v[i] = __builtin_fmaxf(v[i], 0.f);
+    } else if (ep.act == 2) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) v[i] = epi_act(v[i], 2);
     }
 }
 
