@@ -70,18 +70,17 @@ __device__ __forceinline__ int stage_channel(int q, int g, int half)
 
 // Output channel held by row r of channel tile mt.  Within a group of 4 tiles (64 channels) the rows
 // are dealt so that the accumulator values one lane holds after the multiplication -- rows
-// 4q .. 4q+3 of every tile -- are, for each pair of tiles, the 8 consecutive channels
-// 64*(mt/4) + 32*(pair) + 8q .. +7.  A 16-bit epilogue then stores 16 bytes per lane and pair, and the
-// four lane quarters of a position write one contiguous 64-byte run, without any exchange between lanes.
+// 4q .. 4q+3 of each of the 4 tiles -- are the 16 consecutive channels 64*(mt/4) + 16q .. +15:
+// the epilogues store runs of 16 channels without exchanging data between lanes.
 __device__ __forceinline__ int tile_row_channel(int mt, int r)
 {
-    return 64 * (mt >> 2) + 32 * ((mt & 3) >> 1) + 8 * (r >> 2) + 4 * (mt & 1) + (r & 3);
+    return 64 * (mt >> 2) + 16 * (r >> 2) + 4 * (mt & 3) + (r & 3);
 }
 // first of the 4 consecutive channels that quarter q of a lane holds of tile mm (counted from the
 // first channel of mm's group of 4 tiles when mm < 4; mm may run over several groups)
 __device__ __forceinline__ int tile_quarter_offset(int mm, int q)
 {
-    return 64 * (mm >> 2) + 32 * ((mm & 3) >> 1) + 8 * q + 4 * (mm & 1);
+    return 64 * (mm >> 2) + 16 * q + 4 * (mm & 3);
 }
 
 struct SparsePackArgs {
@@ -409,7 +408,7 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
     // the last matrix instructions must have written their accumulators before anything reads them
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
     // ---- epilogue: a D lane holds column nn (position) and rows 4*qq .. 4*qq+3 of every channel tile,
-    // which tile_row_channel makes 8 consecutive output channels per pair of tiles ----
+    // which tile_row_channel makes 16 consecutive output channels per group of 4 tiles ----
     static_assert(TM % 4 == 0, "whole groups of 4 channel tiles");
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
@@ -418,27 +417,29 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
         if (oh >= Ho || ow >= Wo) continue;
         TO* yp = y + (((int64_t)n_img * Ho + oh) * Wo + ow) * Co;
 #pragma unroll
-        for (int mp = 0; mp < TM; mp += 2) {
-            const int co = 16 * mt0 + tile_quarter_offset(mp, qq);
-            if (co >= Co) continue;  // Co is a multiple of 16 and the run of 8 starts at a multiple of 8: all in or all out
-            float vv[8];
+        for (int mg = 0; mg < TM; mg += 4) {
+            const int co = 16 * mt0 + tile_quarter_offset(mg, qq);
+            if (co >= Co) continue;  // Co is a multiple of 16 and the run of 16 starts at a multiple of 16: all in or all out
+            float vv[16];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                vv[e] = acc[mp][j][e];
-                vv[4 + e] = acc[mp + 1][j][e];
-            }
-            epi_scale_bias_act<8>(vv, ep, co);
-            epi_residual<TO, 8>(vv, ep, (yp - y) + co);
+            for (int m = 0; m < 4; ++m)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) vv[4 * m + e] = acc[mg + m][j][e];
+            epi_scale_bias_act<16>(vv, ep, co);
+            epi_residual<TO, 16>(vv, ep, (yp - y) + co);
             if constexpr (sizeof(TO) == 4) {
-                *(f32x4*)(yp + co) = f32x4{vv[0], vv[1], vv[2], vv[3]};
-                *(f32x4*)(yp + co + 4) = f32x4{vv[4], vv[5], vv[6], vv[7]};
+#pragma unroll
+                for (int g = 0; g < 4; ++g) *(f32x4*)(yp + co + 4 * g) = f32x4{vv[4 * g], vv[4 * g + 1], vv[4 * g + 2], vv[4 * g + 3]};
             } else {
-                u32x4 o;
-                o.x = pack2_from_f32<TO>(vv[0], vv[1]);
-                o.y = pack2_from_f32<TO>(vv[2], vv[3]);
-                o.z = pack2_from_f32<TO>(vv[4], vv[5]);
-                o.w = pack2_from_f32<TO>(vv[6], vv[7]);
-                *(u32x4*)(yp + co) = o;
+#pragma unroll
+                for (int g = 0; g < 2; ++g) {
+                    u32x4 o;
+                    o.x = pack2_from_f32<TO>(vv[8 * g + 0], vv[8 * g + 1]);
+                    o.y = pack2_from_f32<TO>(vv[8 * g + 2], vv[8 * g + 3]);
+                    o.z = pack2_from_f32<TO>(vv[8 * g + 4], vv[8 * g + 5]);
+                    o.w = pack2_from_f32<TO>(vv[8 * g + 6], vv[8 * g + 7]);
+                    *(u32x4*)(yp + co + 8 * g) = o;
+                }
             }
         }
     }
