@@ -54,6 +54,9 @@ namespace {
 // (which output channel a row of a tile is: tile_row_channel)
 constexpr int kFragBytes = 1024;
 constexpr int kTileBytes = 5 * kFragBytes + 2 * 64 * 4;  // 5632
+// 16-bit outputs without a fused output stage are stored straight from the accumulators (measured faster
+// than the transposition through LDS once a lane's values are 32 contiguous bytes: tile_row_channel)
+constexpr bool kDirectEpilogue = true;
 
 __device__ __forceinline__ int tap_of_slot(int group, int f)
 {
@@ -703,11 +706,12 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
     // the last matrix instructions must have written their accumulators before anything reads them
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
     // ---- epilogue ----
-    // A D fragment has, per lane, 4 consecutive output channels of one position; stored directly
-    // that is 8-byte pieces scattered over 16 positions.  Instead each wave transposes its
+    // Per lane and group of 4 channel tiles the accumulators hold 16 consecutive output channels of one
+    // position (tile_row_channel).  16-bit outputs without a fused output stage are stored directly:
+    // 32 contiguous bytes per lane, 128 per position and group.  Otherwise each wave transposes its
     // 64 positions x 16*TM channels through its own slice of the region that was multiplied last
     // (free now; the other region is receiving the next tile's first stage) and writes whole
-    // channel rows, 16 bytes per lane.  fp32 output goes in two halves of the channel tiles.
+    // channel rows, 16 bytes per lane; fp32 output goes in two halves of the channel tiles.
     {
         constexpr int EB = (int)sizeof(TO);
         constexpr int HALVES = EB == 4 ? 2 : 1;
@@ -726,7 +730,33 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
         // 64-bit address of the tile's first output element once; everything else is 32-bit
         TO* const y_tile = y + (((int64_t)t_n * Ho + t_oh0) * Wo + t_ow0) * Co;
         const float relu_floor = ep.act == 1 ? 0.f : -__builtin_inff();
-        {
+        if constexpr (kDirectEpilogue && EB == 2 && !FUSED) {
+            // straight from the accumulators: 16 consecutive channels (32 bytes) per lane and group of 4 tiles
+            const int pr_e = nn_e >> 2, pc_e = nn_e & 3;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int blk = blk0 + j;
+                const int dr = 4 * (blk / CT) + pr_e, dc = 4 * (blk % CT) + pc_e;
+                const bool inside = t_oh0 + dr < Ho && t_ow0 + dc < Wo;
+                TO* yp = y_tile + (dr * Wo + dc) * Co + 16 * t_mt0 + 16 * qq_e;
+#pragma unroll
+                for (int mg = 0; mg < TM; mg += 4) {
+                    uint32_t o[8];
+#pragma unroll
+                    for (int m = 0; m < 4; ++m) {
+                        float r[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) asm("v_max_f32 %0, %1, %2" : "=v"(r[e]) : "v"(acc[mg + m][j][e]), "v"(relu_floor));
+                        o[2 * m] = pack2_from_f32<TO>(r[0], r[1]);
+                        o[2 * m + 1] = pack2_from_f32<TO>(r[2], r[3]);
+                    }
+                    if (inside && 16 * (t_mt0 + mg) + 16 * qq_e < Co) {
+                        *(u32x4*)(yp + 16 * mg) = u32x4{o[0], o[1], o[2], o[3]};
+                        *(u32x4*)(yp + 16 * mg + 8) = u32x4{o[4], o[5], o[6], o[7]};
+                    }
+                }
+            }
+        } else {
 #pragma unroll
         for (int h = 0; h < HALVES; ++h) {
 #pragma unroll
@@ -808,11 +838,14 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
     work = next_work;
     // staging slices are read (LDS only): the region may be overwritten by the next copies.  A bare
     // barrier, because __syncthreads() carries a fence that would wait here for this tile's output
-    // stores to drain; they drain behind the next tile's first stage instead.
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0) only
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
+    // stores to drain; they drain behind the next tile's first stage instead.  (The direct epilogue
+    // does not touch LDS: nothing to wait for.)
+    if constexpr (!(kDirectEpilogue && sizeof(TO) == 2 && !FUSED)) {
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0) only
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    }
   }
 }
 
