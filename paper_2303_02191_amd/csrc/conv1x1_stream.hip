@@ -15,7 +15,8 @@
 //     buffer holds PB positions x all Ci channels (16 KB for most shapes), laid out
 //     [32-channel stage][position][64 bytes] with the four 16-byte chunks of a position
 //     XOR-swizzled by (position / 2) % 4: conflict-free 16-byte operand reads without padding.
-//   * A fifth wave is the producer: it issues every copy and nothing else, so its count of
+//   * A fifth wave is the producer: it issues every copy (but for the first two buffers of a
+//     workgroup, which the consumers fetch while they would otherwise idle) and nothing else, so its count of
 //     outstanding memory operations counts copies only and "buffer b has landed" is an exact
 //     counted wait (the four consumer waves also store outputs, which would share the counter).
 //     One barrier per buffer hands a filled buffer to the consumers and a drained one back.
@@ -39,6 +40,7 @@ namespace rtoss {
 namespace {
 
 constexpr int kFrag = 1024;  // one A fragment: 64 lanes x 16 bytes = 16 output channels x 32 input channels
+constexpr int kHeadBuffers = 2;  // buffers of a workgroup's range that the consumer waves copy themselves
 
 // Shape plan, a function of KS = Ci / 32 (1, 2, 4 ... 32) and of WM, the number of waves a
 // workgroup spreads over output channels (the other 4 / WM spread over positions).
@@ -233,16 +235,19 @@ __global__ __launch_bounds__(320) void conv1x1_stream_kernel(const T* __restrict
                     copy16_to_lds(p0 + src_pos[k] < P ? base + src_off[k] : zeros, dst + k * 1024);
             }
         };
-        for (int i = 0; i < RING - 1; ++i)
+        // (the first kHeadBuffers buffers are copied by the consumer waves, see below)
+        for (int i = kHeadBuffers; i < RING - 1; ++i)
             if (b0 + i < b1) issue_buffer(b0 + i, i);
         int slot = 0;
         for (int64_t b = b0; b < b1; ++b) {
-            // buffer b has landed once no more copies are outstanding than were issued after it
-            const int64_t later = std::min<int64_t>(b1 - 1 - b, RING - 2);
             asm volatile("" ::: "memory");
-            if (later >= RING - 2) __builtin_amdgcn_s_waitcnt(vmcnt_imm((RING - 2) * COPIES));
-            else if (later == 0) __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-            else wait_tail<RING - 3, COPIES>(later);
+            if (b - b0 >= kHeadBuffers) {
+                // buffer b has landed once no more copies are outstanding than were issued after it
+                const int64_t later = std::min<int64_t>(b1 - 1 - b, RING - 2);
+                if (later >= RING - 2) __builtin_amdgcn_s_waitcnt(vmcnt_imm((RING - 2) * COPIES));
+                else if (later == 0) __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+                else wait_tail<RING - 3, COPIES>(later);
+            }
             __builtin_amdgcn_s_barrier();  // consumers may read buffer b; they are done with the slot refilled next
             asm volatile("" ::: "memory");
             if (b + RING - 1 < b1) issue_buffer(b + RING - 1, (slot + RING - 1) % RING);
@@ -263,6 +268,30 @@ __global__ __launch_bounds__(320) void conv1x1_stream_kernel(const T* __restrict
 #pragma unroll
             for (int s = 0; s < KS; ++s) a[m][s] = *(const u32x4*)(af + (m * KS + s) * kFrag);
     }
+    // Start-up: one wave needs about 70 cycles per copy instruction, so a producer that fills the ring alone
+    // delivers the first buffer late.  The four consumer waves, idle until then, issue the copies of the
+    // first kHeadBuffers buffers (every fourth copy instruction each), and wait for them together with
+    // their weight fragments before the first barrier.
+    for (int i = 0; i < kHeadBuffers; ++i) {
+        const int64_t bb = b0 + i;
+        if (bb >= b1) break;
+        const int64_t p0 = bb * PB;
+        const char* base = (const char*)x + p0 * (Ci * 2);
+        char* dst = smem + i * BUF;
+#pragma unroll
+        for (int t = 0; t < (COPIES + 3) / 4; ++t) {
+            const int k = wave + 4 * t;  // wave-uniform
+            if (k >= COPIES) break;
+            const int c = k * 64 + lane;
+            const int st = c / (PB * 4), rem = c % (PB * 4);
+            const int pos = rem >> 2, q = (rem & 3) ^ ((pos >> 1) & 3);
+            copy16_to_lds(p0 + pos < P ? base + (pos * Ci + st * 32 + q * 8) * 2 : zeros, dst + k * 1024);
+        }
+    }
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    asm volatile("" ::: "memory");
+
     const int nn = lane & 15, qq = lane >> 4;
     // operand read offset within a buffer for stage 0, block 0 (the swizzle depends on nn only)
     const int x_lane = (wn * 16 + nn) * 64 + ((qq ^ ((nn >> 1) & 3)) * 16);
@@ -344,7 +373,7 @@ rtoss_status launch_plan(const rtoss_wdesc& d, const ConvParams& c, const char* 
             return st;
         attr_set = true;
     }
-    // Persistent workgroups: as many as are resident at once, but no fewer than 4 buffers each: every
+    // Persistent workgroups: as many as are resident at once, but no fewer than 2 buffers each: every
     // workgroup loads its weight fragments once, which for deep layers is more bytes than a buffer.
     static int resident = 0;  // per instantiation
     if (resident == 0) {
@@ -354,7 +383,7 @@ rtoss_status launch_plan(const rtoss_wdesc& d, const ConvParams& c, const char* 
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)kern, 320, smem) != hipSuccess || per_cu < 1) per_cu = 1;
         resident = cus * per_cu;
     }
-    const int64_t by_work = std::max<int64_t>(1, (nbuf + 3) / 4);
+    const int64_t by_work = std::max<int64_t>(1, (nbuf + 1) / 2);
     const int wgs_per_cb = (int)std::max<int64_t>(1, std::min<int64_t>(by_work, resident / co_blocks));
     const int total = wgs_per_cb * co_blocks;
     const int work_per_xcd = (total + 7) / 8;
