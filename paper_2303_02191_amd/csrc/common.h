@@ -86,9 +86,14 @@ constexpr int kPackBatchMax = 24;
 // block -> (entry, block within the entry) for the batched kernels: first_block[t] <= block < first_block[t+1]
 template <typename Batch> __device__ __forceinline__ int batch_entry(const Batch& b, int block)
 {
-    int t = 0;
-    while (t + 1 < b.n && block >= b.first_block[t + 1]) ++t;
-    return t;
+    // binary search: the table sits in the kernel arguments, and every probe is a dependent scalar load
+    int lo = 0, hi = b.n - 1;  // the entry is in [lo, hi]
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (block >= b.first_block[mid]) lo = mid;
+        else hi = mid - 1;
+    }
+    return lo;
 }
 rtoss_status launch_pack_sparse3x3_batch(const PackItem* items, int n, const Dict& dict, hipStream_t s);
 rtoss_status launch_pack_stream1x1_batch(const PackItem* items, int n, const Dict& dict, hipStream_t s);

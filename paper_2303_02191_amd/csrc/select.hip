@@ -33,9 +33,21 @@ __device__ __forceinline__ void select_block(const T* __restrict__ w, int64_t G,
 
     masks[tid] = dict.mask[tid];
     const T* span = w + g0 * 9;
-    for (int e = tid; e < ngroups * 9; e += kSelBlock) {
-        double v = (double)to_f32(span[e]);
-        sq[e] = v * v;
+    // (all of a lane's loads are issued before the first is used: a workgroup pays the memory latency once)
+    constexpr int kLoads = (kSelGroupsPerBlock * 9 + kSelBlock - 1) / kSelBlock;
+    T raw[kLoads];
+#pragma unroll
+    for (int i = 0; i < kLoads; ++i) {
+        const int e = tid + i * kSelBlock;
+        if (e < ngroups * 9) raw[i] = span[e];
+    }
+#pragma unroll
+    for (int i = 0; i < kLoads; ++i) {
+        const int e = tid + i * kSelBlock;
+        if (e < ngroups * 9) {
+            const double v = (double)to_f32(raw[i]);
+            sq[e] = v * v;
+        }
     }
     __syncthreads();
 
@@ -73,7 +85,7 @@ __global__ __launch_bounds__(kSelBlock) void select_kernel(const T* __restrict__
 
 // Several tensors in one launch (every layer of a model: the selection of a 1x1 tensor is over its own
 // flattening, Section IV.D, so tensors cannot simply be concatenated).  The table travels in the
-// launch arguments; a workgroup finds its tensor by scanning the table's first-block numbers.
+// launch arguments; a workgroup finds its tensor by a binary search of the table's first-block numbers.
 struct SelectBatch {
     const void* w[kSelectBatchMax];
     uint8_t* idx[kSelectBatchMax];
@@ -85,8 +97,7 @@ struct SelectBatch {
 template <typename T>
 __global__ __launch_bounds__(kSelBlock) void select_batch_kernel(SelectBatch batch, Dict dict)
 {
-    int t = 0;
-    while (t + 1 < batch.n && (int)blockIdx.x >= batch.first_block[t + 1]) ++t;  // block-uniform
+    const int t = batch_entry(batch, (int)blockIdx.x);  // block-uniform
     select_block<T>((const T*)batch.w[t], batch.G[t], dict, batch.idx[t],
                     (int64_t)((int)blockIdx.x - batch.first_block[t]) * kSelGroupsPerBlock);
 }
