@@ -56,14 +56,11 @@ __device__ __forceinline__ void select_block(const T* __restrict__ w, int64_t G,
     double best_s = -1.0;  // below every real score
     int best_p = 0xffff;   // "none yet"
     if (gl < ngroups) {
-        double s9[9];
-#pragma unroll
-        for (int t = 0; t < 9; ++t) s9[t] = sq[gl * 9 + t];
+        const double* g9 = sq + gl * 9;
         for (int p = q; p < dict.P; p += kSelLanesPerGroup) {
-            const unsigned m = masks[p];
+            // only the live taps, lowest first (every pattern of a dictionary has the same number of them)
             double s = 0.0;
-#pragma unroll
-            for (int t = 0; t < 9; ++t) s = ((m >> t) & 1u) ? s + s9[t] : s;
+            for (unsigned m = masks[p]; m != 0; m &= m - 1) s += g9[__builtin_ctz(m)];
             if (s > best_s) { best_s = s; best_p = p; }
         }
     }
