@@ -36,6 +36,7 @@
 // matrix instructions, LDS reads, permutes and copies.  The single-buffered one (stride 2,
 // small layers) is a plain loop nest with small tiles, several workgroups per compute unit.
 #include <algorithm>
+#include <type_traits>
 
 #include "common.h"
 #include "dtypes.h"
@@ -604,12 +605,10 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
     const int t_n = n_img, t_mt0 = mt0, t_oh0 = oh0, t_ow0 = ow0;
     const int next_work = work + slots_per_xcd;
     const bool has_next = next_work < work_end;
-#pragma unroll
-    for (int m = 0; m < TM; ++m)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) acc[m][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    for (int stage = 0; stage < stages; ++stage) {
+    // (no clearing of the accumulators: the first stage's centre step, which visits every one of them
+    // first, writes a * b instead of adding to it)
+    auto run_stage = [&](auto first_tag, int stage) {
+        constexpr bool FIRST = decltype(first_tag)::value;
         // the stage copied while this one is multiplied: the tile's next stage, or the next tile's first
         // (in the very last stage of the last tile there is nothing left to fetch; stage 0 of the
         // same tile is fetched again into the free region, which keeps this code free of branches)
@@ -655,7 +654,10 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
             static_for<UNIT>([&](auto I) {
                 constexpr int i = decltype(I)::value;
                 constexpr int mi = i / TN, j = i % TN, m = m0 + mi;
-                if constexpr (phase == 0) Mat<T>::dense(a_cur[mi], bc[j], acc[m][j]);
+                if constexpr (phase == 0) {
+                    if constexpr (FIRST) Mat<T>::dense_first(a_cur[mi], bc[j], acc[m][j]);
+                    else Mat<T>::dense(a_cur[mi], bc[j], acc[m][j]);
+                }
                 if constexpr (phase == 1) Mat<T>::template sparse<0>(a_cur[mi], bfc[0][j], acc[m][j], i_cur[mi]);
                 if constexpr (phase == 2) Mat<T>::template sparse<1>(a_cur[mi], bfc[1][j], acc[m][j], i_cur[mi]);
                 if constexpr (phase == 3) Mat<T>::template sparse<0>(a_cur[mi], bfe[0][j], acc[m][j], i_cur[mi]);
@@ -701,7 +703,9 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
             }
         });
         gpar ^= 1;
-    }
+    };
+    run_stage(std::true_type{}, 0);
+    for (int stage = 1; stage < stages; ++stage) run_stage(std::false_type{}, stage);
 
     // the last matrix instructions must have written their accumulators before anything reads them
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
