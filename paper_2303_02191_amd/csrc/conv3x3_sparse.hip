@@ -293,12 +293,10 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
     }
 
     f32x4 acc[TM][TN];
-#pragma unroll
-    for (int m = 0; m < TM; ++m)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) acc[m][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    for (int stage = 0; stage < stages; ++stage) {
+    // (no clearing of the accumulators: the centre step comes first in a stage, and the first stage's
+    // writes a * b instead of adding to it)
+    auto run_stage = [&](auto first_tag, int stage) {
+        constexpr bool FIRST = decltype(first_tag)::value;
         __syncthreads();  // every wave is done reading the previous stage
 #pragma unroll
         for (int k = 0; k < A_PER_WAVE; ++k)
@@ -384,7 +382,10 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
 #pragma unroll
             for (int m = 0; m < TM; ++m)
 #pragma unroll
-                for (int j = 0; j < TN; ++j) Mat<T>::dense(ac[m], bc[j], acc[m][j]);
+                for (int j = 0; j < TN; ++j) {
+                    if constexpr (FIRST) Mat<T>::dense_first(ac[m], bc[j], acc[m][j]);
+                    else Mat<T>::dense(ac[m], bc[j], acc[m][j]);
+                }
         };
         if constexpr (AHEAD) {
             load_centre();
@@ -394,6 +395,8 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
             run_group(0);
             run_group(1);
         } else {  // few operands live at a time: fewer registers, one more workgroup per compute unit
+            load_centre();
+            run_centre();
 #pragma unroll
             for (int group = 0; group < 2; ++group) {
                 load_group_x(group);
@@ -404,10 +407,10 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
                     multiply_group(group, m);
                 }
             }
-            load_centre();
-            run_centre();
         }
-    }
+    };
+    run_stage(std::true_type{}, 0);
+    for (int stage = 1; stage < stages; ++stage) run_stage(std::false_type{}, stage);
 
     // the last matrix instructions must have written their accumulators before anything reads them
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
