@@ -363,9 +363,9 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
         };
         auto multiply_group = [&](int group, int m) {
 #pragma unroll
-            for (int j = 0; j < TN; ++j) Mat<T>::template sparse<0>(as[group][m][0], bf[0][j], acc[m][j], iw2[group][m]);
+            for (int j = 0; j < TN; ++j) MatV<T>::template sparse<0>(as[group][m][0], bf[0][j], acc[m][j], iw2[group][m]);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) Mat<T>::template sparse<1>(as[group][m][1], bf[1][j], acc[m][j], iw2[group][m]);
+            for (int j = 0; j < TN; ++j) MatV<T>::template sparse<1>(as[group][m][1], bf[1][j], acc[m][j], iw2[group][m]);
         };
         auto run_group = [&](int group) {
             permute_group(group);
@@ -383,8 +383,8 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
             for (int m = 0; m < TM; ++m)
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
-                    if constexpr (FIRST) Mat<T>::dense_first(ac[m], bc[j], acc[m][j]);
-                    else Mat<T>::dense(ac[m], bc[j], acc[m][j]);
+                    if constexpr (FIRST) MatV<T>::dense_first(ac[m], bc[j], acc[m][j]);
+                    else MatV<T>::dense(ac[m], bc[j], acc[m][j]);
                 }
         };
         if constexpr (AHEAD) {

@@ -37,39 +37,34 @@ typedef __bf16 b16 __attribute__((ext_vector_type(16)));
 // Operand hazards: A/B come from LDS reads (waited on by the compiler) or vector ALU results;
 // an accumulator is touched again by a matrix instruction no sooner than TN instructions later,
 // and is read by other instructions only after the K loop (see the s_nop before the epilogue).
+// dense_first: c = a * b through the instruction's constant-zero C operand, the first product of an
+// accumulator.  (Clearing accumulators with v_accvgpr_write costs about 18 cycles per register in
+// front of the next matrix instruction.)
+// MatV is the same with the accumulator in the vector registers: kernels with registers to spare keep
+// it there and spare themselves the (equally slow) v_accvgpr_read of the epilogue.
+#define RTOSS_MAT_STRUCT(NAME, T, SFX, RW, WO)                                                                        \
+    template <> struct NAME<T> {                                                                                      \
+        static __device__ __forceinline__ void dense(u32x4 a, u32x4 b, f32x4& c)                                      \
+        {                                                                                                             \
+            asm volatile("v_mfma_f32_16x16x32_" SFX " %0, %1, %2, %0" : RW(c) : "v"(a), "v"(b));                      \
+        }                                                                                                             \
+        static __device__ __forceinline__ void dense_first(u32x4 a, u32x4 b, f32x4& c)                                \
+        {                                                                                                             \
+            asm volatile("v_mfma_f32_16x16x32_" SFX " %0, %1, %2, 0" : WO(c) : "v"(a), "v"(b));                       \
+        }                                                                                                             \
+        template <int ABID> static __device__ __forceinline__ void sparse(u32x4 a, u32x8 b, f32x4& c, int idx)        \
+        {                                                                                                             \
+            if (ABID == 0) asm volatile("v_smfmac_f32_16x16x64_" SFX " %0, %1, %2, %3" : RW(c) : "v"(a), "v"(b), "v"(idx)); \
+            else asm volatile("v_smfmac_f32_16x16x64_" SFX " %0, %1, %2, %3 abid:1" : RW(c) : "v"(a), "v"(b), "v"(idx));    \
+        }                                                                                                             \
+    };
 template <typename T> struct Mat;
-template <> struct Mat<f16_t> {
-    static __device__ __forceinline__ void dense(u32x4 a, u32x4 b, f32x4& c)
-    {
-        asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
-    }
-    // c = a * b: the first product of an accumulator.  (Clearing accumulators with v_accvgpr_write
-    // costs about 18 cycles per register in front of the next matrix instruction.)
-    static __device__ __forceinline__ void dense_first(u32x4 a, u32x4 b, f32x4& c)
-    {
-        asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, 0" : "=a"(c) : "v"(a), "v"(b));
-    }
-    template <int ABID> static __device__ __forceinline__ void sparse(u32x4 a, u32x8 b, f32x4& c, int idx)
-    {
-        if (ABID == 0) asm volatile("v_smfmac_f32_16x16x64_f16 %0, %1, %2, %3" : "+a"(c) : "v"(a), "v"(b), "v"(idx));
-        else asm volatile("v_smfmac_f32_16x16x64_f16 %0, %1, %2, %3 abid:1" : "+a"(c) : "v"(a), "v"(b), "v"(idx));
-    }
-};
-template <> struct Mat<bf16_t> {
-    static __device__ __forceinline__ void dense(u32x4 a, u32x4 b, f32x4& c)
-    {
-        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
-    }
-    static __device__ __forceinline__ void dense_first(u32x4 a, u32x4 b, f32x4& c)
-    {
-        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, 0" : "=a"(c) : "v"(a), "v"(b));
-    }
-    template <int ABID> static __device__ __forceinline__ void sparse(u32x4 a, u32x8 b, f32x4& c, int idx)
-    {
-        if (ABID == 0) asm volatile("v_smfmac_f32_16x16x64_bf16 %0, %1, %2, %3" : "+a"(c) : "v"(a), "v"(b), "v"(idx));
-        else asm volatile("v_smfmac_f32_16x16x64_bf16 %0, %1, %2, %3 abid:1" : "+a"(c) : "v"(a), "v"(b), "v"(idx));
-    }
-};
+template <typename T> struct MatV;
+RTOSS_MAT_STRUCT(Mat, f16_t, "f16", "+a", "=a")
+RTOSS_MAT_STRUCT(Mat, bf16_t, "bf16", "+a", "=a")
+RTOSS_MAT_STRUCT(MatV, f16_t, "f16", "+v", "=v")
+RTOSS_MAT_STRUCT(MatV, bf16_t, "bf16", "+v", "=v")
+#undef RTOSS_MAT_STRUCT
 
 // One 16-byte global -> LDS copy per lane without passing through registers: lane i of the
 // wave writes LDS address lds_wave_base + 16 * i (the base must be wave-uniform).
