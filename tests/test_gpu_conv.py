@@ -89,6 +89,11 @@ MATRIX_CORE = [
     # launcher takes the tall tile (5 position blocks per wave), here with ragged rows and columns
     (43, 128, 48, 37, 30, 1, 3, True),
     (130, 160, 16, 21, 16, 1, 2, False),
+    # the pipelined kernel (more than 64 channels in and out, at least 200 tiles of 16x16 positions x 128
+    # channels): 20x16 tiles with ragged rows and columns and a partial group of 64 output channels ...
+    (43, 128, 80, 37, 30, 1, 3, True),
+    # ... and 16x16 tiles, three stages, two channel blocks of which the second is mostly padding
+    (13, 96, 144, 64, 50, 1, 2, False),
 ]
 
 

@@ -15,8 +15,9 @@ pytestmark = pytest.mark.gpu
 
 # dt, N, Ci, Co, H, W, ks, stride, k, rule: one case per kernel family and shape class
 CASES = [
-    (wl.BF16, 1, 128, 128, 20, 24, 3, 1, 3, B.RULE_CONNECTED4),   # pipelined sparse kernel
-    (wl.F16, 2, 256, 272, 17, 33, 3, 1, 2, B.RULE_CONNECTED4),    # ... ragged tiles, padded channel block
+    (wl.BF16, 13, 128, 128, 52, 50, 3, 1, 3, B.RULE_CONNECTED4),  # pipelined sparse kernel (>= 200 tiles of 16x16 x 128 channels)
+    (wl.F16, 7, 256, 272, 33, 49, 3, 1, 2, B.RULE_CONNECTED4),    # ... ragged tiles, padded channel block
+    (wl.BF16, 1, 128, 128, 20, 24, 3, 1, 3, B.RULE_CONNECTED4),   # single-buffered sparse kernel, deep layer
     (wl.F16, 2, 64, 48, 19, 21, 3, 1, 3, B.RULE_CONNECTED4),      # single-buffered sparse kernel, stride 1
     (wl.BF16, 1, 128, 144, 37, 41, 3, 2, 2, B.RULE_CONNECTED4),   # ... stride 2
     (wl.F16, 1, 64, 80, 18, 20, 3, 1, 4, B.RULE_CONNECTED4),      # dense mode
