@@ -96,7 +96,10 @@ struct SparsePackArgs {
     LiveJob job;
 };
 
-// One block of 256 items of one layer (`block` counts from the layer's first block).
+// One workgroup of one layer (`block` counts from the layer's first block): the first blocks write the
+// public section, then comes one block per (stage, channel tile) and last the block of zeros.
+// A tile's 16 x 32 kernels (16 rows of 576 contiguous bytes) and their pattern indices are staged in LDS with
+// coalesced 16-byte loads; the 5 x 64 fragment pieces are then assembled from LDS.
 template <typename T>
 __device__ __forceinline__ void pack_sparse3x3_body(const SparsePackArgs& a, const Dict& dict, int block)
 {
@@ -104,73 +107,86 @@ __device__ __forceinline__ void pack_sparse3x3_body(const SparsePackArgs& a, con
     const uint8_t* __restrict__ idx = a.idx;
     char* __restrict__ out = a.out;
     const int Co = a.Co, Ci = a.Ci, m_tiles = a.m_tiles, zero_items = a.zero_items;
-    const int64_t total_items = a.total_items;
     const LiveJob job = a.job;
     __shared__ uint16_t masks[256];
+    __shared__ __attribute__((aligned(16))) uint16_t wl[16][32 * 9];  // [row][channel][tap]
+    __shared__ __attribute__((aligned(16))) uint8_t il[16][32];       // [row][channel]
     masks[threadIdx.x] = dict.mask[threadIdx.x];
-    __syncthreads();
     if (block < job.blocks) {  // the first blocks write the blob's public section
+        __syncthreads();
         pack_live_block<T>(w, idx, masks, dict.k, job, block);
         return;
     }
-    const int64_t item = (int64_t)(block - job.blocks) * 256 + threadIdx.x;  // (stage, m_tile, step 0..4, lane)
-    if (item >= total_items) {  // the items behind the fragments write the block of zeros, 16 bytes each
-        if (item < total_items + zero_items) *(u32x4*)(out + (total_items / 320) * kTileBytes + (item - total_items) * 16) = u32x4{0, 0, 0, 0};
+    const int n_tiles = (int)(a.total_items / 320);
+    const int tile = block - job.blocks;  // stage * m_tiles + m_tile
+    if (tile >= n_tiles) {  // the blocks behind the fragments write the block of zeros, 16 bytes per lane
+        const int item = (tile - n_tiles) * 256 + (int)threadIdx.x;
+        if (item < zero_items) *(u32x4*)(out + (size_t)n_tiles * kTileBytes + (size_t)item * 16) = u32x4{0, 0, 0, 0};
         return;
     }
-    const int lane = (int)(item % 64);
-    const int step = (int)((item / 64) % 5);
-    const int64_t tile = item / 320;  // stage * m_tiles + m_tile
-    const int mt = (int)(tile % m_tiles);
-    const int cb = (int)(tile / m_tiles);
-    const int r = lane % 16, q = lane / 16;
-    const int co = tile_row_channel(mt, r);
-    char* tile_out = out + tile * kTileBytes;
-    uint16_t vals[8];
-    if (step == 4) {  // dense centre tap: K = 8q + j
-        for (int j = 0; j < 8; ++j) {
-            const int ci = 32 * cb + 8 * q + j;
-            uint16_t v = 0;
-            if (co < Co && ci < Ci) {
-                const int64_t g9 = (int64_t)co * Ci + ci;
-                if ((masks[idx[g9]] >> 4) & 1u) v = __builtin_bit_cast(uint16_t, w[g9 * 9 + 4]);
-            }
-            vals[j] = v;
-        }
-    } else {
-        const int group = step >> 1, half = step & 1;
-        unsigned fields = 0;
-        for (int g = 0; g < 4; ++g) {
-            const int ci = 32 * cb + stage_channel(q, g, half);
-            uint16_t v[2] = {0, 0};
-            int f[2] = {0, 1};
-            if (co < Co && ci < Ci) {
-                const int64_t g9 = (int64_t)co * Ci + ci;
-                const unsigned m = masks[idx[g9]];
-                int n = 0;
-                for (int s = 0; s < 4; ++s) {
-                    const int t = tap_of_slot(group, s);
-                    if (((m >> t) & 1u) && n < 2) {
-                        v[n] = __builtin_bit_cast(uint16_t, w[g9 * 9 + t]);
-                        f[n] = s;
-                        ++n;
-                    }
-                }
-                if (n == 1) f[1] = (f[0] + 1) & 3;  // padding value 0 may point anywhere
-            }
-            vals[2 * g] = v[0];
-            vals[2 * g + 1] = v[1];
-            fields |= (unsigned)(f[0] | (f[1] << 2)) << (4 * g);
-        }
-        uint16_t* ip = (uint16_t*)(tile_out + 5 * kFragBytes + (group * 64 + lane) * 4 + half * 2);
-        *ip = (uint16_t)fields;
+    const int mt = tile % m_tiles, cb = tile / m_tiles;
+    // ---- stage: 16 rows x 36 chunks of weights, 16 rows x 2 chunks of indices (rows past Co are zeros) ----
+    for (int c = threadIdx.x; c < 16 * 36; c += 256) {
+        const int r = c / 36, k = c % 36;
+        const int co = tile_row_channel(mt, r);
+        u32x4 v = {0, 0, 0, 0};
+        if (co < Co) v = *(const u32x4*)((const char*)w + ((int64_t)co * Ci + 32 * cb) * 18 + k * 16);
+        *(u32x4*)((char*)&wl[r][0] + k * 16) = v;
     }
-    u32x4 pk;
-    pk.x = vals[0] | ((uint32_t)vals[1] << 16);
-    pk.y = vals[2] | ((uint32_t)vals[3] << 16);
-    pk.z = vals[4] | ((uint32_t)vals[5] << 16);
-    pk.w = vals[6] | ((uint32_t)vals[7] << 16);
-    *(u32x4*)(tile_out + step * kFragBytes + lane * 16) = pk;
+    if (threadIdx.x < 32) {
+        const int r = threadIdx.x / 2, k = threadIdx.x % 2;
+        const int co = tile_row_channel(mt, r);
+        u32x4 v = {0, 0, 0, 0};
+        if (co < Co) v = *(const u32x4*)(idx + (int64_t)co * Ci + 32 * cb + k * 16);
+        *(u32x4*)(&il[r][k * 16]) = v;
+    }
+    __syncthreads();
+    // ---- assemble: item = (step 0..4, lane); 320 items, the last 64 by the first wave in a second pass ----
+    char* tile_out = out + (size_t)tile * kTileBytes;
+    for (int item = threadIdx.x; item < 320; item += 256) {
+        const int lane = item % 64, step = item / 64;
+        const int r = lane % 16, q = lane / 16;
+        const bool row_live = tile_row_channel(mt, r) < Co;
+        uint16_t vals[8];
+        if (step == 4) {  // dense centre tap: K = 8q + j
+            for (int j = 0; j < 8; ++j) {
+                const int c = 8 * q + j;
+                vals[j] = (row_live && ((masks[il[r][c]] >> 4) & 1u)) ? wl[r][c * 9 + 4] : (uint16_t)0;
+            }
+        } else {
+            const int group = step >> 1, half = step & 1;
+            unsigned fields = 0;
+            for (int g = 0; g < 4; ++g) {
+                const int c = stage_channel(q, g, half);
+                uint16_t v[2] = {0, 0};
+                int f[2] = {0, 1};
+                if (row_live) {
+                    const unsigned m = masks[il[r][c]];
+                    int n = 0;
+                    for (int sl = 0; sl < 4; ++sl) {
+                        const int t = tap_of_slot(group, sl);
+                        if (((m >> t) & 1u) && n < 2) {
+                            v[n] = wl[r][c * 9 + t];
+                            f[n] = sl;
+                            ++n;
+                        }
+                    }
+                    if (n == 1) f[1] = (f[0] + 1) & 3;  // padding value 0 may point anywhere
+                }
+                vals[2 * g] = v[0];
+                vals[2 * g + 1] = v[1];
+                fields |= (unsigned)(f[0] | (f[1] << 2)) << (4 * g);
+            }
+            uint16_t* ip = (uint16_t*)(tile_out + 5 * kFragBytes + (group * 64 + lane) * 4 + half * 2);
+            *ip = (uint16_t)fields;
+        }
+        u32x4 pk;
+        pk.x = vals[0] | ((uint32_t)vals[1] << 16);
+        pk.y = vals[2] | ((uint32_t)vals[3] << 16);
+        pk.z = vals[4] | ((uint32_t)vals[5] << 16);
+        pk.w = vals[6] | ((uint32_t)vals[7] << 16);
+        *(u32x4*)(tile_out + step * kFragBytes + lane * 16) = pk;
+    }
 }
 
 template <typename T>
@@ -1011,7 +1027,7 @@ static SparsePackArgs sparse_pack_args(const rtoss_wdesc& d, const void* w, cons
     a.total_items = (int64_t)(d.Ci / 32) * a.m_tiles * 320;
     a.zero_items = (int)(zero_block_bytes(d) / 16);
     a.job = make_live_job(live_values, live_idx, (int64_t)d.Co * d.Ci);
-    *blocks = (int)(a.job.blocks + (a.total_items + a.zero_items + 255) / 256);
+    *blocks = (int)(a.job.blocks + a.total_items / 320 + (a.zero_items + 255) / 256);  // public section, tiles, zeros
     return a;
 }
 
