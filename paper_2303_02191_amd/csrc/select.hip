@@ -3,74 +3,85 @@
 //
 // Mapping: one workgroup of 256 lanes scores 64 groups.  The 9*64 weights of those groups
 // are one contiguous span; the lanes load it element-wise (coalesced), square it in fp64
-// and park the squares in LDS.  Four neighbouring lanes share a group: lane q scores the
-// patterns q, q+4, q+8, ... in ascending order, then the four (score, index) pairs are
-// merged with two cross-lane exchanges.  Sums run over the live taps in ascending tap
-// order in fp64, comparisons are strict, and the merge prefers the lower index on equal
-// scores, so the result equals a serial ascending scan bit for bit.
+// and park the squares in LDS.  Every wave holds all 64 groups, one per lane, and scores
+// every fourth pattern for them (wave v: patterns v, v+4, ... in ascending order), so the
+// pattern and the walk over its live taps are uniform over a wave.  The four (score, index)
+// candidates of a group meet in LDS.  Sums run over the live taps in ascending tap order in
+// fp64, comparisons are strict, and the merge prefers the lower index on equal scores, so
+// the result equals a serial ascending scan bit for bit.
 #include <algorithm>
 
 #include "common.h"
 #include "dtypes.h"
+#include "mma.h"
 
 namespace rtoss {
 
-constexpr int kSelLanesPerGroup = 4;
 constexpr int kSelBlock = 256;
-constexpr int kSelGroupsPerBlock = kSelBlock / kSelLanesPerGroup;
+constexpr int kSelWaves = kSelBlock / 64;
+constexpr int kSelGroupsPerBlock = 64;  // one group per lane of a wave
 
 // One workgroup's share: 64 groups of tensor `w` starting at group g0.
 template <typename T>
 __device__ __forceinline__ void select_block(const T* __restrict__ w, int64_t G, const Dict& dict, uint8_t* __restrict__ idx,
                                              int64_t g0)
 {
-    __shared__ double sq[kSelGroupsPerBlock * 9];
-    __shared__ uint16_t masks[256];
+    __shared__ double sq[9][kSelGroupsPerBlock];  // tap-major: a wave's 64 reads of one tap are contiguous
+    __shared__ double cand_s[kSelWaves][kSelGroupsPerBlock];
+    __shared__ int cand_p[kSelWaves][kSelGroupsPerBlock];
 
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int64_t remaining = G - g0;
     const int ngroups = remaining < kSelGroupsPerBlock ? (int)remaining : kSelGroupsPerBlock;
 
-    masks[tid] = dict.mask[tid];
     const T* span = w + g0 * 9;
-    // (all of a lane's loads are issued before the first is used: a workgroup pays the memory latency once)
-    constexpr int kLoads = (kSelGroupsPerBlock * 9 + kSelBlock - 1) / kSelBlock;
-    T raw[kLoads];
+    // 16-byte loads of whole vectors of the span (a full block is 72 of them for 16-bit weights); the
+    // ragged end of a tensor's last block is read element by element
+    constexpr int EPV = 16 / (int)sizeof(T);  // elements per vector
+    const int n_elems = ngroups * 9;
+    static_assert(kSelGroupsPerBlock * 9 <= kSelBlock * EPV, "one vector per lane covers a block");
+    {
+        const int e0 = tid * EPV;
+        if (e0 + EPV <= n_elems) {
+            T v[EPV];
+            *(u32x4*)v = *(const u32x4*)(span + e0);
 #pragma unroll
-    for (int i = 0; i < kLoads; ++i) {
-        const int e = tid + i * kSelBlock;
-        if (e < ngroups * 9) raw[i] = span[e];
-    }
-#pragma unroll
-    for (int i = 0; i < kLoads; ++i) {
-        const int e = tid + i * kSelBlock;
-        if (e < ngroups * 9) {
-            const double v = (double)to_f32(raw[i]);
-            sq[e] = v * v;
+            for (int i = 0; i < EPV; ++i) {
+                const double d = (double)to_f32(v[i]);
+                sq[(e0 + i) % 9][(e0 + i) / 9] = d * d;
+            }
+        } else {
+            for (int e = e0; e < n_elems; ++e) {
+                const double d = (double)to_f32(span[e]);
+                sq[e % 9][e / 9] = d * d;
+            }
         }
     }
     __syncthreads();
 
-    const int gl = tid / kSelLanesPerGroup;
-    const int q = tid % kSelLanesPerGroup;
+    // Wave v scores the patterns v, v+4, v+8, ... in ascending order for all 64 groups, lane = group.  The
+    // pattern, and so the walk over its live taps (lowest first), is uniform over the wave: per tap one LDS
+    // read and one fp64 add per lane.
     double best_s = -1.0;  // below every real score
     int best_p = 0xffff;   // "none yet"
-    if (gl < ngroups) {
-        const double* g9 = sq + gl * 9;
-        for (int p = q; p < dict.P; p += kSelLanesPerGroup) {
-            // only the live taps, lowest first (every pattern of a dictionary has the same number of them)
-            double s = 0.0;
-            for (unsigned m = masks[p]; m != 0; m &= m - 1) s += g9[__builtin_ctz(m)];
-            if (s > best_s) { best_s = s; best_p = p; }
-        }
+    for (int p = wave; p < dict.P; p += kSelWaves) {
+        double s = 0.0;
+        for (unsigned m = dict.mask[p]; m != 0; m &= m - 1) s += sq[__builtin_ctz(m)][lane];
+        if (s > best_s) { best_s = s; best_p = p; }
     }
+    cand_s[wave][lane] = best_s;
+    cand_p[wave][lane] = best_p;
+    __syncthreads();
+    if (wave == 0 && lane < ngroups) {
 #pragma unroll
-    for (int d = 1; d < kSelLanesPerGroup; d <<= 1) {
-        const double o_s = __shfl_xor(best_s, d);
-        const int o_p = __shfl_xor(best_p, d);
-        if (o_s > best_s || (o_s == best_s && o_p < best_p)) { best_s = o_s; best_p = o_p; }
+        for (int v = 1; v < kSelWaves; ++v) {
+            const double o_s = cand_s[v][lane];
+            const int o_p = cand_p[v][lane];
+            if (o_s > best_s || (o_s == best_s && o_p < best_p)) { best_s = o_s; best_p = o_p; }
+        }
+        idx[g0 + lane] = (uint8_t)(best_p == 0xffff ? 0 : best_p);
     }
-    if (gl < ngroups && q == 0) idx[g0 + gl] = (uint8_t)(best_p == 0xffff ? 0 : best_p);
 }
 
 template <typename T>
