@@ -529,13 +529,15 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
     // per-stage advance of 64 bytes stays inside it).
     int n_img, mt0, oh0, ow0;
     const char* x_ptr[X_PER_WAVE];  // per lane and copy slot: source address for stage 0
-    auto setup_tile = [&](int w) {
+    auto setup_tile_coords = [&](int w) {
         const int cblk = w % co_blocks;
         const int tile = (w / co_blocks) % tiles_per_img;
         n_img = w / (co_blocks * tiles_per_img);
         mt0 = cblk * TM;
         oh0 = (tile / tiles_c) * G::TH;
         ow0 = (tile % tiles_c) * G::TW;
+    };
+    auto setup_tile_sources = [&]() {
         const int ih0 = oh0 * S - 1, iw0 = ow0 * S - 1;
 #pragma unroll
         for (int k = 0; k < X_PER_WAVE; ++k) {
@@ -544,7 +546,9 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
             const int pr = pos / G::LW, pc = pos % G::LW;
             const int ih = ih0 + pr, iw = iw0 + pc;
             const bool inside = q < 4 && pr < G::IH && pc < G::IW && ih >= 0 && ih < H && iw >= 0 && iw < W;
-            x_ptr[k] = inside ? (const char*)x + ((((int64_t)n_img * H + ih) * W + iw) * Ci + q * 8) * 2 : zeros;
+            // offset in 16-byte chunks: fits 31 bits (checked by the launcher)
+            const int off = ((n_img * H + ih) * W + iw) * (Ci >> 3) + q;
+            x_ptr[k] = inside ? (const char*)x + (int64_t)off * 16 : zeros;
         }
     };
     // One copy instruction (64 lanes x 16 bytes) of stage `stage` of the current tile into region
@@ -611,9 +615,14 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
         });
     };
 
-    setup_tile(work);
+    // (the weight copies need only the tile's channel block: they are under way while the lanes work out
+    // their activation sources, ~3 k cycles of address arithmetic)
+    setup_tile_coords(work);
 #pragma unroll
-    for (int slot = 0; slot < COPY_SLOTS; ++slot) issue_copy_slot(slot, 0, 0);
+    for (int slot = 0; slot < A_PER_WAVE; ++slot) issue_copy_slot(slot, 0, 0);
+    setup_tile_sources();
+#pragma unroll
+    for (int slot = A_PER_WAVE; slot < COPY_SLOTS; ++slot) issue_copy_slot(slot, 0, 0);
     __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's copies have landed in LDS
     __syncthreads();                     // ... and everybody's
     int gpar = 0;     // region that holds the stage about to be multiplied
@@ -633,7 +642,10 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
         // same tile is fetched again into the free region, which keeps this code free of branches)
         const bool last_stage = stage + 1 == stages;
         const int copy_stage = last_stage ? 0 : stage + 1;
-        if (last_stage && has_next) setup_tile(next_work);
+        if (last_stage && has_next) {
+            setup_tile_coords(next_work);
+            setup_tile_sources();
+        }
         const char* A = smem + gpar * REGION + lane * 16;
         const char* AI = smem + gpar * REGION + 5 * kFragBytes + lane * 4;
         const char* X = smem + gpar * REGION + A_BYTES;
