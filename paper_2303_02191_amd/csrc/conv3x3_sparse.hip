@@ -126,19 +126,35 @@ __device__ __forceinline__ void pack_sparse3x3_body(const SparsePackArgs& a, con
     }
     const int mt = tile % m_tiles, cb = tile / m_tiles;
     // ---- stage: 16 rows x 36 chunks of weights, 16 rows x 2 chunks of indices (rows past Co are zeros) ----
-    for (int c = threadIdx.x; c < 16 * 36; c += 256) {
-        const int r = c / 36, k = c % 36;
-        const int co = tile_row_channel(mt, r);
-        u32x4 v = {0, 0, 0, 0};
-        if (co < Co) v = *(const u32x4*)((const char*)w + ((int64_t)co * Ci + 32 * cb) * 18 + k * 16);
-        *(u32x4*)((char*)&wl[r][0] + k * 16) = v;
-    }
-    if (threadIdx.x < 32) {
-        const int r = threadIdx.x / 2, k = threadIdx.x % 2;
-        const int co = tile_row_channel(mt, r);
-        u32x4 v = {0, 0, 0, 0};
-        if (co < Co) v = *(const u32x4*)(idx + (int64_t)co * Ci + 32 * cb + k * 16);
-        *(u32x4*)(&il[r][k * 16]) = v;
+    // (rows start at multiples of 576 and 32 bytes from the tensors' first elements; the interface asks for
+    // element alignment only, so tensors that do not start on a 16-byte boundary are staged element-wise)
+    if (((reinterpret_cast<uintptr_t>(w) | reinterpret_cast<uintptr_t>(idx)) & 15) == 0) {
+        for (int c = threadIdx.x; c < 16 * 36; c += 256) {
+            const int r = c / 36, k = c % 36;
+            const int co = tile_row_channel(mt, r);
+            u32x4 v = {0, 0, 0, 0};
+            if (co < Co) v = *(const u32x4*)((const char*)w + ((int64_t)co * Ci + 32 * cb) * 18 + k * 16);
+            *(u32x4*)((char*)&wl[r][0] + k * 16) = v;
+        }
+        if (threadIdx.x < 32) {
+            const int r = threadIdx.x / 2, k = threadIdx.x % 2;
+            const int co = tile_row_channel(mt, r);
+            u32x4 v = {0, 0, 0, 0};
+            if (co < Co) v = *(const u32x4*)(idx + (int64_t)co * Ci + 32 * cb + k * 16);
+            *(u32x4*)(&il[r][k * 16]) = v;
+        }
+    } else {
+        const uint16_t* w16 = (const uint16_t*)w;
+        for (int c = threadIdx.x; c < 16 * 288; c += 256) {
+            const int r = c / 288, e = c % 288;
+            const int co = tile_row_channel(mt, r);
+            wl[r][e] = co < Co ? w16[((int64_t)co * Ci + 32 * cb) * 9 + e] : (uint16_t)0;
+        }
+        for (int c = threadIdx.x; c < 16 * 32; c += 256) {
+            const int r = c / 32, e = c % 32;
+            const int co = tile_row_channel(mt, r);
+            il[r][e] = co < Co ? idx[(int64_t)co * Ci + 32 * cb + e] : (uint8_t)0;
+        }
     }
     __syncthreads();
     // ---- assemble: item = (step 0..4, lane); 320 items, the last 64 by the first wave in a second pass ----

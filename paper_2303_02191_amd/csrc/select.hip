@@ -43,7 +43,10 @@ __device__ __forceinline__ void select_block(const T* __restrict__ w, int64_t G,
     static_assert(kSelGroupsPerBlock * 9 <= kSelBlock * EPV, "one vector per lane covers a block");
     {
         const int e0 = tid * EPV;
-        if (e0 + EPV <= n_elems) {
+        // (the interface asks for element alignment only: a span that does not start on a 16-byte boundary
+        // takes the element loop as a whole)
+        const bool vectors = (reinterpret_cast<uintptr_t>(span) & 15) == 0;
+        if (vectors && e0 + EPV <= n_elems) {
             T v[EPV];
             *(u32x4*)v = *(const u32x4*)(span + e0);
 #pragma unroll
@@ -52,7 +55,8 @@ __device__ __forceinline__ void select_block(const T* __restrict__ w, int64_t G,
                 sq[(e0 + i) % 9][(e0 + i) / 9] = d * d;
             }
         } else {
-            for (int e = e0; e < n_elems; ++e) {
+            const int e1 = e0 + EPV < n_elems ? e0 + EPV : n_elems;
+            for (int e = e0; e < e1; ++e) {
                 const double d = (double)to_f32(span[e]);
                 sq[e % 9][e / 9] = d * d;
             }

@@ -1,9 +1,11 @@
 """GPU parity: rtoss_pack's live-weight section vs the oracle's mask step, bit-exact."""
 import numpy as np
 import pytest
+import torch
 
 import oracle
 from paper_2303_02191_amd import binding as B
+from paper_2303_02191_amd import pipeline as pl
 from paper_2303_02191_amd import workloads as wl
 
 from gpu_util import GpuLayer, decode_live_section
@@ -58,3 +60,24 @@ def test_batched_pack_equals_single_packs():
     for (Co, Ci, ks), a, b in zip(shapes, single, batched):
         assert torch.equal(a.blob, b.blob), (Co, Ci, ks)
 
+
+
+def test_sparse_pack_of_tensors_aligned_to_their_element_only():
+    """Weights one element, indices one byte into their allocations: the blob equals the aligned one's."""
+    dt, k = wl.F16, 3
+    Co, Ci = 48, 64
+    masks = B.rtoss_pattern_dict(k)
+    rng = np.random.default_rng(12)
+    ws = wl.round_to_dtype(rng.standard_normal((Co, Ci, 3, 3)) * 0.05, dt)
+    w = pl.to_device(ws, dt)
+    idx = pl.select_patterns(w, dt, masks)
+    ref = pl.PackedLayer(Co, Ci, 3, k, dt, masks).pack(w, idx)
+    wbuf = torch.empty(w.numel() + 1, dtype=w.dtype, device="cuda")
+    wbuf[1:] = w.reshape(-1)
+    ibuf = torch.empty(idx.numel() + 1, dtype=torch.uint8, device="cuda")
+    ibuf[1:] = idx
+    w2, idx2 = wbuf[1:].reshape(w.shape), ibuf[1:]
+    assert w2.data_ptr() % 16 != 0 and idx2.data_ptr() % 16 != 0
+    got = pl.PackedLayer(Co, Ci, 3, k, dt, masks).pack(w2, idx2)
+    torch.cuda.synchronize()
+    assert torch.equal(got.blob, ref.blob)

@@ -1,9 +1,11 @@
 """GPU parity: rtoss_select_patterns vs the oracle, bit-exact (ties to the lowest index)."""
 import numpy as np
 import pytest
+import torch
 
 import oracle
 from paper_2303_02191_amd import binding as B
+from paper_2303_02191_amd import pipeline as pl
 from paper_2303_02191_amd import workloads as wl
 
 from gpu_util import gpu_select
@@ -138,3 +140,17 @@ def test_batched_select_matches_oracle_per_tensor(dt):
         want = oracle.select(v, masks) if n >= 9 else np.zeros(0, dtype=np.uint8)
         assert np.array_equal(g.cpu().numpy(), want), n
 
+
+
+@pytest.mark.parametrize("dt", [wl.F16, wl.F32])
+def test_select_weights_aligned_to_their_element_only(dt):
+    """The interface asks for element alignment: a tensor that starts one element into an allocation."""
+    masks = B.rtoss_pattern_dict(3)
+    n = 9 * 1000 + 5
+    store, vals = _draw(n, dt, seed=77 + dt)
+    buf = pl.to_device(np.concatenate([store[:1], store]), dt)
+    w = buf[1:]
+    assert w.data_ptr() % 16 != 0
+    idx = pl.select_patterns(w, dt, masks)
+    torch.cuda.synchronize()
+    assert np.array_equal(idx.cpu().numpy(), oracle.select(vals, masks))
