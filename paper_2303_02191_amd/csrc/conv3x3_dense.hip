@@ -11,7 +11,7 @@
 // Workgroup = 4 waves, output tile = 64 output channels x 16x16 positions; every wave owns all
 // 64 channels x 4 blocks of 4x4 positions.  K runs over stages of 32 input channels: the stage's
 // 4 x 9 weight fragments (one contiguous piece of the blob) and the activation tile with halo
-// (channels-last, 80-byte position pitch) are copied global -> LDS, then each of the 9 taps is
+// (channels-last, 64-byte position pitch at stride 1 and 80 at stride 2) are copied global -> LDS, then each of the 9 taps is
 // one v_mfma_f32_16x16x32 step per (channel fragment, position block) whose B operand is a plain
 // 16-byte read at the tap's offset.  The LDS is single-buffered; for stride 1 two workgroups
 // share a compute unit and hide each other's copy latency.
@@ -160,7 +160,7 @@ __global__ __launch_bounds__(256) void conv3x3_dense_kernel(const T* __restrict_
 #pragma unroll
     for (int k = 0; k < X_PER_WAVE; ++k) {
         const int c = (k * 4 + wave) * 64 + lane;
-        const int pos = c / 5, q = c % 5;
+        const int pos = c / G::kChunks, q = c % G::kChunks;
         const int pr = pos / G::LW, pc = pos % G::LW;
         const int ih = ih0 + pr, iw = iw0 + pc;
         const bool inside = q < 4 && pr < G::IH && pc < G::IW && ih >= 0 && ih < H && iw >= 0 && iw < W;
@@ -175,7 +175,7 @@ __global__ __launch_bounds__(256) void conv3x3_dense_kernel(const T* __restrict_
 #pragma unroll
     for (int j = 0; j < kTN; ++j) {
         const int blk = wave * kTN + j;
-        xb[j] = (((4 * (blk / CT) + pr) * S) * G::LW + (4 * (blk % CT) + pc) * S) * kXPosBytes + qq * 16;
+        xb[j] = (((4 * (blk / CT) + pr) * S) * G::LW + (4 * (blk % CT) + pc) * S) * G::kPos + qq * 16;
     }
 
     // The accumulators are never cleared: the first tap of the first stage multiplies onto the
@@ -199,7 +199,7 @@ __global__ __launch_bounds__(256) void conv3x3_dense_kernel(const T* __restrict_
             u32x4 b[kTN];
 #pragma unroll
             for (int j = 0; j < kTN; ++j)
-                b[j] = *(const u32x4*)(lds_x + xb[j] + ((t / 3) * G::LW + (t % 3)) * kXPosBytes);
+                b[j] = *(const u32x4*)(lds_x + xb[j] + ((t / 3) * G::LW + (t % 3)) * G::kPos);
 #pragma unroll
             for (int m = 0; m < TM; ++m) {
                 const u32x4 a = *(const u32x4*)(lds_a + (m * 9 + t) * kFrag + lane * 16);

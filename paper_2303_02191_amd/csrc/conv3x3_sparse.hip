@@ -26,7 +26,7 @@
 // (RT x CT) blocks of 4x4 output positions; every wave owns all 16*TM channels and TN of
 // the position blocks.  K runs over stages of 32 input channels: the stage's weight
 // fragments (one contiguous chunk of the packed blob) and its activation tile with halo
-// (channels-last, 32 channels per position, 80-byte position stride) are copied global ->
+// (channels-last, 32 channels per position, 64-byte position pitch at stride 1 and 80 at stride 2) are copied global ->
 // LDS without passing through registers.  B operands are read from LDS as 16-byte vectors
 // (8 channels of one tap) and the 4x4 (tap, channel) blocks are transposed in registers
 // with byte permutes so that one lane holds, for 4 channels, the 4 taps of a group.
@@ -302,7 +302,7 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
 #pragma unroll
     for (int k = 0; k < X_PER_WAVE; ++k) {
         const int c = (k * 4 + wave) * 64 + lane;
-        const int pos = c / 5, q = c % 5;
+        const int pos = c / G::kChunks, q = c % G::kChunks;
         const int xr = pos / G::LW, xc = pos % G::LW;
         const int ih = ih0 + xr, iw = iw0 + xc;
         const bool inside = q < 4 && xr < G::IH && xc < G::IW && ih >= 0 && ih < H && iw >= 0 && iw < W;
@@ -321,7 +321,7 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
     for (int j = 0; j < TN; ++j) {
         const int blk = wave * TN + j;
         const int br = blk / CT, bc = blk % CT;
-        xb[j] = (((4 * br + pr) * S) * G::LW + (4 * bc + pc) * S) * kXPosBytes + qq * 16;
+        xb[j] = (((4 * br + pr) * S) * G::LW + (4 * bc + pc) * S) * G::kPos + qq * 16;
     }
 
     f32x4 acc[TM][TN];
@@ -353,7 +353,7 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
 #pragma unroll
                 for (int f = 0; f < 4; ++f) {
                     const int t = group == 0 ? ((f & 1) * 2 + (f >> 1) * 6) : (2 * f + 1);
-                    rr[group][j][f] = *(const u32x4*)(lds_x + xb[j] + ((t / 3) * G::LW + (t % 3)) * kXPosBytes);
+                    rr[group][j][f] = *(const u32x4*)(lds_x + xb[j] + ((t / 3) * G::LW + (t % 3)) * G::kPos);
                 }
         };
         auto load_group_a = [&](int group, int m) {
@@ -406,7 +406,7 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
         };
         auto load_centre = [&]() {
 #pragma unroll
-            for (int j = 0; j < TN; ++j) bc[j] = *(const u32x4*)(lds_x + xb[j] + (G::LW + 1) * kXPosBytes);
+            for (int j = 0; j < TN; ++j) bc[j] = *(const u32x4*)(lds_x + xb[j] + (G::LW + 1) * G::kPos);
 #pragma unroll
             for (int m = 0; m < TM; ++m) ac[m] = *(const u32x4*)(lds_a + m * kTileBytes + 4 * kFragBytes + lane * 16);
         };
@@ -558,7 +558,7 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
 #pragma unroll
         for (int k = 0; k < X_PER_WAVE; ++k) {
             const int c = ((k * 4 + wave) * 64 + lane);
-            const int pos = c / 5, q = c % 5;
+            const int pos = c / G::kChunks, q = c % G::kChunks;
             const int pr = pos / G::LW, pc = pos % G::LW;
             const int ih = ih0 + pr, iw = iw0 + pc;
             const bool inside = q < 4 && pr < G::IH && pc < G::IW && ih >= 0 && ih < H && iw >= 0 && iw < W;
@@ -595,7 +595,7 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         const int blk = blk0 + j;
-        xb[j] = (((4 * (blk / CT) + pr) * S) * G::LW + (4 * (blk % CT) + pc) * S) * kXPosBytes + qq * 16;
+        xb[j] = (((4 * (blk / CT) + pr) * S) * G::LW + (4 * (blk % CT) + pc) * S) * G::kPos + qq * 16;
     }
 
     f32x4 acc[TM][TN];
@@ -609,7 +609,7 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
 #pragma unroll
         for (int f = 0; f < 4; ++f) {
             const int t = group == 0 ? ((f & 1) * 2 + (f >> 1) * 6) : (2 * f + 1);
-            rr[f] = *(const u32x4*)(X + xb[j] + ((t / 3) * G::LW + (t % 3)) * kXPosBytes);
+            rr[f] = *(const u32x4*)(X + xb[j] + ((t / 3) * G::LW + (t % 3)) * G::kPos);
         }
     };
     // Operand registers that cross stage boundaries: the reads a stage needs before its first matrix
@@ -622,7 +622,7 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
         const char* A = smem + par * REGION + lane * 16;
         const char* X = smem + par * REGION + A_BYTES;
 #pragma unroll
-        for (int j = 0; j < TN; ++j) bc[j] = *(const u32x4*)(X + xb[j] + (G::LW + 1) * kXPosBytes);
+        for (int j = 0; j < TN; ++j) bc[j] = *(const u32x4*)(X + xb[j] + (G::LW + 1) * G::kPos);
         a_nxt[0] = *(const u32x4*)(A + 4 * kFragBytes);
         a_nxt[1] = *(const u32x4*)(A + kTileBytes + 4 * kFragBytes);
         static_for<kJobs>([&](auto Q) {
