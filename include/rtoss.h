@@ -231,7 +231,8 @@ typedef struct {
     int N, H, W;         /* batch, input height, input width */
     int stride;          /* 1 or 2 (1 only for ksize 1) */
     int pad;             /* must equal ksize / 2 */
-    rtoss_layout layout; /* RTOSS_NHWC: x is [N][H][W][Ci], y is [N][Ho][Wo][Co] */
+    rtoss_layout layout; /* RTOSS_NHWC: x is [N][H][W][Ci], y is [N][Ho][Wo][Co];
+                            RTOSS_NCHW: x is [N][Ci][H][W], y is [N][Co][Ho][Wo] */
     rtoss_dtype out_dt;  /* the weight dtype, or RTOSS_F32 */
     int fuse_relu;       /* non-zero: y = max(y, 0) */
 } rtoss_cdesc;
@@ -249,8 +250,10 @@ typedef struct {
  *   y_dev       out: type cdesc->out_dt, 16-byte aligned
  * Products are accumulated in fp32 (inputs fp16/bf16/fp32 are multiplied exactly or in
  * fp32); the result is rounded once (nearest-even) when out_dt is a 16-bit type.
- * Errors: RTOSS_ELAYOUT for RTOSS_NCHW (not implemented: the kernels stream channels-last
- * tensors), RTOSS_ESHAPE, RTOSS_EDTYPE, RTOSS_EINVAL.
+ * Layouts: the matrix-core kernels stream channels-last tensors (RTOSS_NHWC), which is the fast
+ * path; RTOSS_NCHW tensors are served for every shape by the element-wise vector-ALU kernel
+ * (same results, far slower: convert once instead where speed matters).
+ * Errors: RTOSS_ESHAPE, RTOSS_EDTYPE, RTOSS_EINVAL (also for an unknown layout).
  */
 rtoss_status rtoss_conv2d_pattern(const rtoss_wdesc* desc, const rtoss_cdesc* cdesc,
                                   const uint16_t* masks_host, int P,
@@ -268,8 +271,18 @@ rtoss_status rtoss_conv2d_pattern(const rtoss_wdesc* desc, const rtoss_cdesc* cd
  *   act                  RTOSS_ACT_NONE, RTOSS_ACT_RELU (max(v, 0)) or RTOSS_ACT_SILU (v / (1 + exp(-v)))
  *   residual_dev         tensor of y's type and shape (device, 16-byte aligned), or NULL; may not
  *                        overlap y_dev
+ *   y_ld, residual_ld    channels-last only: number of elements from one position's first channel
+ *                        to the next position's, for y and for the residual; 0 means Co (a plain
+ *                        tensor).  A larger value makes the tensor a channel slice of a wider
+ *                        buffer: with y_dev = buffer + first_channel and y_ld = the buffer's channel
+ *                        count, the convolution writes its Co channels of every position straight
+ *                        into its place in a concatenation (the blocks of the detectors of Section V
+ *                        concatenate branch outputs along channels), and other slices of the buffer
+ *                        are left untouched.  Both must be multiples of 16 bytes and >= Co; the
+ *                        slice's first element keeps the 16-byte alignment of y_dev / residual_dev.
  * cdesc->fuse_relu must be 0 (use act).  All other arguments and errors as rtoss_conv2d_pattern;
- * RTOSS_EINVAL also for a bad act, misaligned pointers or fuse_relu != 0.
+ * RTOSS_EINVAL also for a bad act, misaligned pointers or pitches, or fuse_relu != 0; RTOSS_ESHAPE
+ * for a pitch below Co; RTOSS_ELAYOUT for a non-zero pitch with RTOSS_NCHW.
  */
 typedef enum { RTOSS_ACT_NONE = 0, RTOSS_ACT_RELU = 1, RTOSS_ACT_SILU = 2 } rtoss_act;
 typedef struct {
@@ -277,6 +290,8 @@ typedef struct {
     const float* bias_dev;
     rtoss_act act;
     const void* residual_dev;
+    int y_ld;
+    int residual_ld;
 } rtoss_epilogue;
 rtoss_status rtoss_conv2d_pattern_fused(const rtoss_wdesc* desc, const rtoss_cdesc* cdesc,
                                         const rtoss_epilogue* epilogue,

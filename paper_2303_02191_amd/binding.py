@@ -41,7 +41,7 @@ ACT_NONE, ACT_RELU, ACT_SILU = 0, 1, 2
 
 class EpilogueDesc(ctypes.Structure):
     _fields_ = [("scale_dev", ctypes.c_void_p), ("bias_dev", ctypes.c_void_p), ("act", ctypes.c_int),
-                ("residual_dev", ctypes.c_void_p)]
+                ("residual_dev", ctypes.c_void_p), ("y_ld", ctypes.c_int), ("residual_ld", ctypes.c_int)]
 
 
 class PackItemDesc(ctypes.Structure):

@@ -29,6 +29,36 @@ rtoss_status check_hip(hipError_t e, const char* what)
     return fail(RTOSS_EHIP, "%s: %s", what, hipGetErrorString(e));
 }
 
+rtoss_status current_device(DeviceInfo* out)
+{
+    constexpr int kSlots = 64;
+    static std::atomic<int> cus_of[kSlots];  // 0 = not asked yet
+    int dev = 0;
+    if (rtoss_status st = check_hip(hipGetDevice(&dev), "hipGetDevice")) return st;
+    int n = dev >= 0 && dev < kSlots ? cus_of[dev].load(std::memory_order_relaxed) : 0;
+    if (n == 0) {
+        if (rtoss_status st = check_hip(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev), "compute unit count"))
+            return st;
+        if (n < 1) return fail(RTOSS_EHIP, "device %d reports %d compute units", dev, n);
+        if (dev >= 0 && dev < kSlots) cus_of[dev].store(n, std::memory_order_relaxed);
+    }
+    out->device = dev;
+    out->cus = n;
+    return RTOSS_OK;
+}
+
+rtoss_status ensure_dynamic_lds(const void* kernel, size_t bytes, LaunchOnce& once, const char* what)
+{
+    int dev = 0;
+    if (rtoss_status st = check_hip(hipGetDevice(&dev), "hipGetDevice")) return st;
+    const bool tracked = dev >= 0 && dev < 64;
+    if (tracked && (once.done.load(std::memory_order_acquire) >> dev & 1u)) return RTOSS_OK;
+    if (rtoss_status st = check_hip(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes), what))
+        return st;
+    if (tracked) once.done.fetch_or((uint64_t)1 << dev, std::memory_order_release);
+    return RTOSS_OK;
+}
+
 // ---------------------------------------------------------------------------------------
 // Dictionary (Section IV.B): Eq. 1 candidates filtered by adjacency.
 // ---------------------------------------------------------------------------------------
@@ -354,8 +384,7 @@ static rtoss_status conv_impl(const rtoss_wdesc* desc, const rtoss_cdesc* c, con
     Dict dict;
     if (rtoss_status st = load_dict(masks_host, P, &dict)) return st;
     if (dict.k != desc->k) return fail(RTOSS_EINVAL, "dictionary keeps %d taps, descriptor says k=%d", dict.k, desc->k);
-    if (c->layout == RTOSS_NCHW) return fail(RTOSS_ELAYOUT, "NCHW activations are not implemented; pass channels-last tensors");
-    if (c->layout != RTOSS_NHWC) return fail(RTOSS_EINVAL, "unknown layout %d", (int)c->layout);
+    if (c->layout != RTOSS_NHWC && c->layout != RTOSS_NCHW) return fail(RTOSS_EINVAL, "unknown layout %d", (int)c->layout);
     if (c->stride != 1 && c->stride != 2) return fail(RTOSS_ESHAPE, "stride %d: only 1 and 2 are supported", c->stride);
     if (desc->ksize == 1 && c->stride != 1) return fail(RTOSS_ESHAPE, "1x1 convolution supports stride 1 only");
     if (c->pad != desc->ksize / 2) return fail(RTOSS_ESHAPE, "pad %d must equal ksize/2 = %d", c->pad, desc->ksize / 2);
@@ -370,26 +399,50 @@ static rtoss_status conv_impl(const rtoss_wdesc* desc, const rtoss_cdesc* c, con
     if (!packed_dev || !x_dev || !y_dev) return fail(RTOSS_EINVAL, "packed_dev, x_dev or y_dev is NULL");
     if (misaligned(packed_dev, 256)) return fail(RTOSS_EINVAL, "packed_dev is not 256-byte aligned");
     if (misaligned(x_dev, 16) || misaligned(y_dev, 16)) return fail(RTOSS_EINVAL, "x_dev and y_dev must be 16-byte aligned");
+    // Output / residual position pitch (channels-last): Co, or wider when the tensor is a channel slice of a
+    // larger buffer.  Runs of 16 bytes are stored at once, so the pitch keeps every position 16-byte aligned.
+    int ldy = desc->Co, ldr = desc->Co;
+    if (e) {
+        if (e->y_ld < 0 || e->residual_ld < 0) return fail(RTOSS_EINVAL, "y_ld and residual_ld must not be negative");
+        if ((e->y_ld || e->residual_ld) && c->layout != RTOSS_NHWC)
+            return fail(RTOSS_ELAYOUT, "y_ld / residual_ld describe channels-last tensors; they must be 0 for NCHW");
+        if (e->y_ld) ldy = e->y_ld;
+        if (e->residual_ld) ldr = e->residual_ld;
+        if (ldy < desc->Co || ldr < desc->Co)
+            return fail(RTOSS_ESHAPE, "y_ld=%d / residual_ld=%d is smaller than Co=%d", e->y_ld, e->residual_ld, desc->Co);
+        if ((size_t)ldy * elem_bytes(c->out_dt) % 16 || (size_t)ldr * elem_bytes(c->out_dt) % 16)
+            return fail(RTOSS_EINVAL, "y_ld and residual_ld must be multiples of 16 bytes");
+    }
+    const int64_t positions = (int64_t)c->N * Ho * Wo;
+    if (positions * std::max(ldy, ldr) >= (int64_t)1 << 40) return fail(RTOSS_ESHAPE, "activation tensor too large");
+    // bytes from a tensor's first element to just past its last (a slice ends Co elements into its last position)
+    const auto span = [&](int ld) { return ((size_t)(positions - 1) * ld + desc->Co) * elem_bytes(c->out_dt); };
     const size_t xb = (size_t)c->N * c->H * c->W * desc->Ci * elem_bytes(desc->dt);
-    const size_t yb = (size_t)c->N * Ho * Wo * desc->Co * elem_bytes(c->out_dt);
+    const size_t yb = span(ldy);
     const char *xa = (const char*)x_dev, *ya = (const char*)y_dev;
     if (xa < ya + yb && ya < xa + xb) return fail(RTOSS_EINVAL, "x and y overlap");
     ConvParams cp;
     static_cast<rtoss_cdesc&>(cp) = *c;
-    cp.ep = Epilogue{nullptr, nullptr, nullptr, c->fuse_relu ? 1 : 0};
+    cp.ep = Epilogue{nullptr, nullptr, nullptr, c->fuse_relu ? 1 : 0, ldy, ldr};
     if (e) {
         if (c->fuse_relu) return fail(RTOSS_EINVAL, "fuse_relu must be 0 when an epilogue is given (use its act)");
         if (e->act != RTOSS_ACT_NONE && e->act != RTOSS_ACT_RELU && e->act != RTOSS_ACT_SILU)
             return fail(RTOSS_EINVAL, "unknown activation %d", (int)e->act);
         if (misaligned(e->scale_dev, 16) || misaligned(e->bias_dev, 16) || misaligned(e->residual_dev, 16))
             return fail(RTOSS_EINVAL, "scale_dev, bias_dev and residual_dev must be 16-byte aligned");
+        // (two channel slices of one wider buffer interleave without sharing an element: the overlap test
+        // applies to plain tensors only)
         const char* ra = (const char*)e->residual_dev;
-        if (ra && ra < ya + yb && ya < ra + yb) return fail(RTOSS_EINVAL, "residual and y overlap");
-        cp.ep = Epilogue{e->scale_dev, e->bias_dev, e->residual_dev, (int)e->act};
+        if (ra && ldy == desc->Co && ldr == desc->Co && ra < ya + yb && ya < ra + yb)
+            return fail(RTOSS_EINVAL, "residual and y overlap");
+        cp.ep = Epilogue{e->scale_dev, e->bias_dev, e->residual_dev, (int)e->act, ldy, ldr};
     }
     BlobGeometry g;
     if (rtoss_status st = blob_geometry(desc, dict, &g)) return st;
     const char* blob = (const char*)packed_dev;
+    if (c->layout == RTOSS_NCHW)  // the element-wise kernel reads section 0 and takes any strides
+        return launch_conv_direct(*desc, cp, dict, blob + g.live_off, (const uint8_t*)(blob + g.idx_off), x_dev, y_dev,
+                                  (hipStream_t)hip_stream);
     if (g.format == kFormatSparse24)
         return launch_conv3x3_sparse(*desc, cp, blob + g.mat_off, x_dev, y_dev, (hipStream_t)hip_stream);
     if (g.format == kFormatStem)

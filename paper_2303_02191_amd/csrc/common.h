@@ -5,6 +5,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "rtoss.h"
 
 namespace rtoss {
@@ -57,6 +59,21 @@ rtoss_status blob_geometry(const rtoss_wdesc* d, const Dict& dict, BlobGeometry*
 // ----- error plumbing -----
 rtoss_status fail(rtoss_status st, const char* fmt, ...);
 rtoss_status check_hip(hipError_t e, const char* what);
+
+// ----- per-device launch state (api.hip) -----
+// The current device's ordinal and its number of compute units (queried once per device).
+struct DeviceInfo {
+    int device;
+    int cus;
+};
+rtoss_status current_device(DeviceInfo* out);
+// Raises a kernel's dynamic-LDS limit to `bytes` on the current device, once per (kernel instantiation,
+// device): `done` is the instantiation's own word, bit d = done on device d.  Safe to call from several
+// threads (the attribute call is idempotent; the word only saves repeating it).
+struct LaunchOnce {
+    std::atomic<uint64_t> done{0};
+};
+rtoss_status ensure_dynamic_lds(const void* kernel, size_t bytes, LaunchOnce& once, const char* what);
 
 // ----- launchers (one per kernel family; defined next to the kernels) -----
 rtoss_status launch_select(const void* w, rtoss_dtype dt, int64_t G, const Dict& dict, uint8_t* idx, hipStream_t s);

@@ -197,7 +197,7 @@ __global__ __launch_bounds__(256) void conv1x1_mma_kernel(const T* __restrict__ 
                         if (p_f < P && co4 < Co) {
                             float vv[4] = {v.x, v.y, v.z, v.w};
                             epi_scale_bias_act<4>(vv, ep, co4);
-                            epi_residual<TO, 4>(vv, ep, p_f * Co + co4);
+                            epi_residual<TO, 4>(vv, ep, p_f, co4);
                             v = f32x4{vv[0], vv[1], vv[2], vv[3]};
                         }
                     }
@@ -223,7 +223,7 @@ __global__ __launch_bounds__(256) void conv1x1_mma_kernel(const T* __restrict__ 
                 const int64_t p = p0 + wave * (TN * 16) + pl;
                 const int co = co_first + chunk * (16 / EB);
                 const u32x4 v = *(const u32x4*)(stage_out + pl * ROW + chunk * 16);
-                if (p < P && co < Co) *(u32x4*)(y + p * Co + co) = v;
+                if (p < P && co < Co) *(u32x4*)(y + p * ep.ldy + co) = v;
             }
         }
     }
@@ -241,13 +241,8 @@ rtoss_status launch_tm(const rtoss_wdesc& d, const ConvParams& c, const char* wf
     constexpr int stage_bytes = ((TM + 3) / 4) * 4096 + 2 * 4096;
     const size_t smem = (size_t)kRing * stage_bytes;
     auto kern = conv1x1_mma_kernel<T, TO, TM>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (rtoss_status st = check_hip(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem),
-                                        "conv1x1 shared memory attribute"))
-            return st;
-        attr_set = true;
-    }
+    static LaunchOnce lds_once;  // per instantiation
+    if (rtoss_status st = ensure_dynamic_lds((const void*)kern, smem, lds_once, "conv1x1 shared memory attribute")) return st;
     dim3 grid((unsigned)(work_per_xcd * 8)), block(256);
     kern<<<grid, block, smem, s>>>((const T*)x, (TO*)y, wfrag, wfrag + frag_bytes(d), P, d.Ci, d.Co, padded_tiles(d.Co),
                                    co_blocks, (int)total, work_per_xcd, c.ep);

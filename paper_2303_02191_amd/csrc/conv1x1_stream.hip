@@ -175,19 +175,6 @@ __global__ __launch_bounds__(256) void pack_stream1x1_batch_kernel(StreamPackBat
     pack_stream1x1_body<T>(b.a[t], dict, (int)blockIdx.x - b.first_block[t]);
 }
 
-template <typename T> struct Dense16;
-template <> struct Dense16<f16_t> {
-    static __device__ __forceinline__ f32x4 mma(u32x4 a, u32x4 b, f32x4 c)
-    {
-        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, a), __builtin_bit_cast(h8, b), c, 0, 0, 0);
-    }
-};
-template <> struct Dense16<bf16_t> {
-    static __device__ __forceinline__ f32x4 mma(u32x4 a, u32x4 b, f32x4 c)
-    {
-        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(b8, a), __builtin_bit_cast(b8, b), c, 0, 0, 0);
-    }
-};
 
 template <typename T, typename TO, int KS, int WM>
 __global__ __launch_bounds__(320) void conv1x1_stream_kernel(const T* __restrict__ x, TO* __restrict__ y,
@@ -325,14 +312,14 @@ __global__ __launch_bounds__(320) void conv1x1_stream_kernel(const T* __restrict
         for (int j = 0; j < NB; ++j) {
             const int64_t p = b * PB + 16 * (wn + WN * j) + nn;
             if (p >= P || co_lane >= Co) continue;  // Co is a multiple of 16 and the run is 16-aligned: all in or all out
-            TO* yp = y + p * Co + co_lane;
+            TO* yp = y + p * ep.ldy + co_lane;
             float v[4 * MT];
 #pragma unroll
             for (int m = 0; m < MT; ++m)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) v[4 * m + e] = acc[m][j][e];
             epi_scale_bias_act<4 * MT>(v, ep, co_lane);
-            epi_residual<TO, 4 * MT>(v, ep, yp - y);
+            epi_residual<TO, 4 * MT>(v, ep, p, co_lane);
             if constexpr (EB == 4) {
 #pragma unroll
                 for (int g = 0; g < MT; ++g) *(f32x4*)(yp + 4 * g) = f32x4{v[4 * g], v[4 * g + 1], v[4 * g + 2], v[4 * g + 3]};
@@ -366,23 +353,21 @@ rtoss_status launch_plan(const rtoss_wdesc& d, const ConvParams& c, const char* 
     const int co_blocks = co_blocks_of(KS, d.Co);
     const size_t smem = (size_t)PL::RING * PL::BUF;
     auto kern = conv1x1_stream_kernel<T, TO, KS, WM>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (rtoss_status st = check_hip(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem),
-                                        "conv1x1 shared memory attribute"))
-            return st;
-        attr_set = true;
-    }
+    static LaunchOnce lds_once;  // per instantiation
+    if (rtoss_status st = ensure_dynamic_lds((const void*)kern, smem, lds_once, "conv1x1 shared memory attribute")) return st;
     // Persistent workgroups: as many as are resident at once, but no fewer than 2 buffers each: every
     // workgroup loads its weight fragments once, which for deep layers is more bytes than a buffer.
-    static int resident = 0;  // per instantiation
-    if (resident == 0) {
-        int dev = 0, cus = 0, per_cu = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 8)
-            cus = 256;
+    // (workgroups per compute unit depend on the instantiation's registers and LDS only: asked once; the
+    // number of compute units is the current device's)
+    static std::atomic<int> per_cu_cached{0};  // per instantiation
+    int per_cu = per_cu_cached.load(std::memory_order_relaxed);
+    if (per_cu == 0) {
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)kern, 320, smem) != hipSuccess || per_cu < 1) per_cu = 1;
-        resident = cus * per_cu;
+        per_cu_cached.store(per_cu, std::memory_order_relaxed);
     }
+    DeviceInfo dev;
+    if (rtoss_status st = current_device(&dev)) return st;
+    const int resident = std::max(8, dev.cus) * per_cu;
     const int64_t by_work = std::max<int64_t>(1, (nbuf + 1) / 2);
     const int wgs_per_cb = (int)std::max<int64_t>(1, std::min<int64_t>(by_work, resident / co_blocks));
     const int total = wgs_per_cb * co_blocks;

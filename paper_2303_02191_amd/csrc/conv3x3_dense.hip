@@ -101,30 +101,6 @@ __global__ __launch_bounds__(256) void pack_dense3x3_kernel(const T* __restrict_
     *(u32x4*)(out + item * 16) = pk;
 }
 
-template <typename T> struct Dense16;
-template <> struct Dense16<f16_t> {
-    static __device__ __forceinline__ f32x4 mma(u32x4 a, u32x4 b, f32x4 c)
-    {
-        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, a), __builtin_bit_cast(h8, b), c, 0, 0, 0);
-    }
-};
-template <> struct Dense16<bf16_t> {
-    static __device__ __forceinline__ f32x4 mma(u32x4 a, u32x4 b, f32x4 c)
-    {
-        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(b8, a), __builtin_bit_cast(b8, b), c, 0, 0, 0);
-    }
-};
-template <> struct Dense16<float> {  // 16 channels: four K = 4 steps, step s on element s of every lane's 16 bytes
-    static __device__ __forceinline__ f32x4 mma(u32x4 a, u32x4 b, f32x4 c)
-    {
-        const f32x4 af = __builtin_bit_cast(f32x4, a), bf = __builtin_bit_cast(f32x4, b);
-        c = __builtin_amdgcn_mfma_f32_16x16x4f32(af.x, bf.x, c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_16x16x4f32(af.y, bf.y, c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_16x16x4f32(af.z, bf.z, c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_16x16x4f32(af.w, bf.w, c, 0, 0, 0);
-        return c;
-    }
-};
 
 // TM channel fragments (of the blob's blocks of 4) and RT x CT position blocks per workgroup.
 template <typename T, typename TO, int S, int TM, int RT, int CT>
@@ -221,14 +197,15 @@ __global__ __launch_bounds__(256) void conv3x3_dense_kernel(const T* __restrict_
         const int blk = wave * kTN + j;
         const int oh = oh0 + 4 * (blk / CT) + pr, ow = ow0 + 4 * (blk % CT) + pc;
         if (oh >= Ho || ow >= Wo || co_lane >= Co) continue;  // Co is a multiple of 16: a run is all in or all out
-        TO* yp = y + (((int64_t)n_img * Ho + oh) * Wo + ow) * Co + co_lane;
+        const int64_t pos = ((int64_t)n_img * Ho + oh) * Wo + ow;
+        TO* yp = y + pos * ep.ldy + co_lane;
         float v[RUN];
 #pragma unroll
         for (int m = 0; m < TM; ++m)
 #pragma unroll
             for (int e = 0; e < 4; ++e) v[4 * m + e] = acc[m][j][e];
         epi_scale_bias_act<RUN>(v, ep, co_lane);
-        epi_residual<TO, RUN>(v, ep, yp - y);
+        epi_residual<TO, RUN>(v, ep, pos, co_lane);
         if constexpr (EB == 4) {
 #pragma unroll
             for (int g = 0; g < TM; ++g) *(f32x4*)(yp + 4 * g) = f32x4{v[4 * g], v[4 * g + 1], v[4 * g + 2], v[4 * g + 3]};
@@ -262,13 +239,8 @@ rtoss_status launch_shape(const rtoss_wdesc& d, const ConvParams& c, const char*
     constexpr int a_copies_per_wave = (TM * 9 + 3) / 4;
     const size_t smem = (size_t)(a_copies_per_wave + x_copies_per_wave) * 4096;
     auto kern = conv3x3_dense_kernel<T, TO, S, TM, RT, CT>;
-    static bool attr_set = false;  // per instantiation
-    if (!attr_set) {
-        if (rtoss_status st = check_hip(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem),
-                                        "conv3x3 dense shared memory attribute"))
-            return st;
-        attr_set = true;
-    }
+    static LaunchOnce lds_once;  // per instantiation
+    if (rtoss_status st = ensure_dynamic_lds((const void*)kern, smem, lds_once, "conv3x3 dense shared memory attribute")) return st;
     const int ygrid = cblocks * (kTM / TM);
     if (c.N > 65535 || ygrid > 65535) return fail(RTOSS_ESHAPE, "conv: batch or channel count too large");
     dim3 grid((unsigned)(tiles_r * tiles_c), (unsigned)ygrid, (unsigned)c.N), block(256);

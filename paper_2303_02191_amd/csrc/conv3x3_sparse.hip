@@ -454,7 +454,8 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
         const int blk = wave * TN + j;
         const int oh = oh0 + 4 * (blk / CT) + pr, ow = ow0 + 4 * (blk % CT) + pc;
         if (oh >= Ho || ow >= Wo) continue;
-        TO* yp = y + (((int64_t)n_img * Ho + oh) * Wo + ow) * Co;
+        const int64_t pos = ((int64_t)n_img * Ho + oh) * Wo + ow;
+        TO* yp = y + pos * ep.ldy;
 #pragma unroll
         for (int mg = 0; mg < TM; mg += 4) {
             const int co = 16 * mt0 + tile_quarter_offset(mg, qq);
@@ -465,7 +466,7 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
 #pragma unroll
                 for (int e = 0; e < 4; ++e) vv[4 * m + e] = acc[mg + m][j][e];
             epi_scale_bias_act<16>(vv, ep, co);
-            epi_residual<TO, 16>(vv, ep, (yp - y) + co);
+            epi_residual<TO, 16>(vv, ep, pos, co);
             if constexpr (sizeof(TO) == 4) {
 #pragma unroll
                 for (int g = 0; g < 4; ++g) *(f32x4*)(yp + co + 4 * g) = f32x4{vv[4 * g], vv[4 * g + 1], vv[4 * g + 2], vv[4 * g + 3]};
@@ -779,7 +780,8 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
         asm volatile("" : "+v"(lane_e));
         const int nn_e = lane_e & 15, qq_e = lane_e >> 4;
         // 64-bit address of the tile's first output element once; everything else is 32-bit
-        TO* const y_tile = y + (((int64_t)t_n * Ho + t_oh0) * Wo + t_ow0) * Co;
+        const int64_t pos_tile = ((int64_t)t_n * Ho + t_oh0) * Wo + t_ow0;  // position number of the tile's first output
+        TO* const y_tile = y + pos_tile * ep.ldy;
         const float relu_floor = ep.act == 1 ? 0.f : -__builtin_inff();
         if constexpr (kDirectEpilogue && EB == 2 && !FUSED) {
             // straight from the accumulators: 16 consecutive channels (32 bytes) per lane and group of 4 tiles
@@ -789,7 +791,7 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
                 const int blk = blk0 + j;
                 const int dr = 4 * (blk / CT) + pr_e, dc = 4 * (blk % CT) + pc_e;
                 const bool inside = t_oh0 + dr < Ho && t_ow0 + dc < Wo;
-                TO* yp = y_tile + (dr * Wo + dc) * Co + 16 * t_mt0 + 16 * qq_e;
+                TO* yp = y_tile + (dr * Wo + dc) * ep.ldy + 16 * t_mt0 + 16 * qq_e;
 #pragma unroll
                 for (int mg = 0; mg < TM; mg += 4) {
                     uint32_t o[8];
@@ -826,14 +828,14 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
                     const int blk_f = blk0 + j;
                     const int dr_f = 4 * (blk_f / CT) + (nn_e >> 2), dc_f = 4 * (blk_f % CT) + (nn_e & 3);
                     const bool inside_f = t_oh0 + dr_f < Ho && t_ow0 + dc_f < Wo;
-                    const int64_t pos_f = (y_tile - y) + (int64_t)(dr_f * Wo + dc_f) * Co;
+                    const int64_t pos_f = pos_tile + dr_f * Wo + dc_f;
 #pragma unroll
                     for (int mm = 0; mm < TMH; ++mm) {
                         const int co4 = 16 * (t_mt0 + h * TMH) + tile_quarter_offset(mm, qq_e);
                         if (inside_f && co4 < Co) {
                             float vv[4] = {vals[mm].x, vals[mm].y, vals[mm].z, vals[mm].w};
                             epi_scale_bias_act<4>(vv, ep, co4);
-                            epi_residual<TO, 4>(vv, ep, pos_f + co4);
+                            epi_residual<TO, 4>(vv, ep, pos_f, co4);
                             vals[mm] = f32x4{vv[0], vv[1], vv[2], vv[3]};
                         }
                     }
@@ -879,7 +881,7 @@ __global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restr
                 const int dr = 4 * (blk / CT) + (n >> 2), dc = 4 * (blk % CT) + (n & 3);
                 const u32x4 v = *(const u32x4*)(stage_out + p * ROW + chunk * 16);
                 if (t_oh0 + dr < Ho && t_ow0 + dc < Wo && co < Co)  // Co is a multiple of 16: a chunk is all in or all out
-                    *(u32x4*)(y_tile + (dr * Wo + dc) * Co + co) = v;
+                    *(u32x4*)(y_tile + (dr * Wo + dc) * ep.ldy + co) = v;
             }
           }
         }
@@ -914,26 +916,16 @@ rtoss_status launch_variant_f(const rtoss_wdesc& d, const ConvParams& c, const c
     constexpr int x_copies_per_wave = ((G::x_bytes / 16 + 63) / 64 + 3) / 4;
     const size_t smem = 2 * ((size_t)TM * kTileBytes + (size_t)x_copies_per_wave * 4096);
     auto kern = conv3x3_sparse_kernel<T, TO, S, TM, TN, RT, CT, FUSED>;
-    static bool attr_set = false;  // per instantiation
-    if (!attr_set) {
-        if (rtoss_status st = check_hip(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem),
-                                        "conv3x3 shared memory attribute"))
-            return st;
-        attr_set = true;
-    }
+    static LaunchOnce lds_once;  // per instantiation
+    if (rtoss_status st = ensure_dynamic_lds((const void*)kern, smem, lds_once, "conv3x3 shared memory attribute")) return st;
     const int64_t total = (int64_t)tiles_r * tiles_c * co_blocks * c.N;
     if (total > 0x3fffffff) return fail(RTOSS_ESHAPE, "conv: too many tiles");
     if ((int64_t)c.N * c.H * c.W * d.Ci / 8 > 0x7fffffff) return fail(RTOSS_ESHAPE, "conv: input too large for 32-bit chunk offsets");
     const int work_per_xcd = (int)((total + 7) / 8);
     // one workgroup per compute unit (a workgroup owns nearly all of a unit's LDS), at most one per work item
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8)
-            n = 256;
-        cus = n;
-    }
-    const int slots_per_xcd = std::max(1, std::min(work_per_xcd, cus / 8));
+    DeviceInfo dev;
+    if (rtoss_status st = current_device(&dev)) return st;
+    const int slots_per_xcd = std::max(1, std::min(work_per_xcd, std::max(8, dev.cus) / 8));
     dim3 grid((unsigned)(slots_per_xcd * 8)), block(256);
     const char* zeros = wfrag + fragment_bytes(d);
     kern<<<grid, block, smem, s>>>((const T*)x, (TO*)y, wfrag, zeros, c.H, c.W, d.Ci, d.Co, Ho, Wo, m_tiles_total,
@@ -963,13 +955,8 @@ rtoss_status launch_variant_sb(const rtoss_wdesc& d, const ConvParams& c, const 
     constexpr int x_copies_per_wave = ((G::x_bytes / 16 + 63) / 64 + 3) / 4;
     const size_t smem = (size_t)TM * kTileBytes + (size_t)x_copies_per_wave * 4096;
     auto kern = conv3x3_sparse_sb_kernel<T, TO, S, TM, TN, RT, CT, AHEAD>;
-    static bool attr_set = false;  // per instantiation
-    if (!attr_set) {
-        if (rtoss_status st = check_hip(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem),
-                                        "conv3x3 shared memory attribute"))
-            return st;
-        attr_set = true;
-    }
+    static LaunchOnce lds_once;  // per instantiation
+    if (rtoss_status st = ensure_dynamic_lds((const void*)kern, smem, lds_once, "conv3x3 shared memory attribute")) return st;
     const int64_t total = (int64_t)tiles_r * tiles_c * co_blocks * c.N;
     if (total > 0x3fffffff) return fail(RTOSS_ESHAPE, "conv: too many tiles");
     if ((int64_t)c.N * c.H * c.W * d.Ci / 8 > 0x7fffffff) return fail(RTOSS_ESHAPE, "conv: input too large for 32-bit chunk offsets");
@@ -1005,7 +992,9 @@ rtoss_status launch_typed(const rtoss_wdesc& d, const ConvParams& c, const char*
         const int64_t co_blocks = ((d.Co + 15) / 16 + 7) / 8;
         const int64_t t4 = (int64_t)((Ho + 15) / 16) * ((Wo + 15) / 16) * co_blocks * c.N;
         const int64_t t5 = (int64_t)((Ho + 19) / 20) * ((Wo + 15) / 16) * co_blocks * c.N;
-        const int64_t slots = 256;
+        DeviceInfo dev;
+        if (rtoss_status st = current_device(&dev)) return st;
+        const int64_t slots = std::max(8, dev.cus) / 8 * 8;  // persistent workgroups of the pipelined kernel
         const double cost4 = (double)((t4 + slots - 1) / slots) * 4.0, cost5 = (double)((t5 + slots - 1) / slots) * 4.85;
         // (with few stages per tile the taller tile's longer prologue and epilogue outweigh the saved round)
         if (cost5 < cost4 && d.Ci >= 128 && !needs_fused_stage(c)) return launch_variant<T, TO, 1, 8, 5, 5, 4>(d, c, wfrag, x, y, s);

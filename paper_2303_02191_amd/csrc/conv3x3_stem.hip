@@ -22,19 +22,6 @@ namespace {
 
 constexpr int kTH = 8, kTW = 32;  // output tile: 8 rows x 32 columns = 16 blocks of 16 positions
 
-template <typename T> struct Dense16;
-template <> struct Dense16<f16_t> {
-    static __device__ __forceinline__ f32x4 mma(u32x4 a, u32x4 b, f32x4 c)
-    {
-        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, a), __builtin_bit_cast(h8, b), c, 0, 0, 0);
-    }
-};
-template <> struct Dense16<bf16_t> {
-    static __device__ __forceinline__ f32x4 mma(u32x4 a, u32x4 b, f32x4 c)
-    {
-        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(b8, a), __builtin_bit_cast(b8, b), c, 0, 0, 0);
-    }
-};
 
 template <typename T>
 __global__ __launch_bounds__(256) void pack_stem_kernel(const T* __restrict__ w, const uint8_t* __restrict__ idx, Dict dict,
@@ -141,7 +128,8 @@ __global__ __launch_bounds__(256, TM == 2 ? 8 : 4) void conv3x3_stem_kernel(cons
         b.w = bv[6] | ((uint32_t)bv[7] << 16);
         const int oh = oh0 + r, ow = ow0 + c;
         const bool inside = oh < Ho && ow < Wo;
-        TO* yp = y + (((int64_t)n_img * Ho + oh) * Wo + ow) * Co;
+        const int64_t pos = ((int64_t)n_img * Ho + oh) * Wo + ow;
+        TO* yp = y + pos * ep.ldy;
         static_assert(TM % 2 == 0, "pairs of channel tiles");
 #pragma unroll
         for (int mp = 0; mp < TM; mp += 2) {
@@ -151,7 +139,7 @@ __global__ __launch_bounds__(256, TM == 2 ? 8 : 4) void conv3x3_stem_kernel(cons
             if (inside && co < Co) {
                 float vv[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
                 epi_scale_bias_act<8>(vv, ep, co);
-                epi_residual<TO, 8>(vv, ep, (yp - y) + co);
+                epi_residual<TO, 8>(vv, ep, pos, co);
                 if constexpr (sizeof(TO) == 4) {
                     *(f32x4*)(yp + co) = f32x4{vv[0], vv[1], vv[2], vv[3]};
                     *(f32x4*)(yp + co + 4) = f32x4{vv[4], vv[5], vv[6], vv[7]};

@@ -1,7 +1,8 @@
 // Direct pattern-sparse convolution on the vector ALUs (fp32 accumulate).
 //
 // This is the path for layers the matrix cores do not fit: fp32 tensors, very small
-// channel counts, and any shape the fragment layouts do not cover.  It multiplies only
+// channel counts, any shape the fragment layouts do not cover, and NCHW activations (the
+// matrix-core kernels stream channels-last tensors).  It multiplies only
 // the k surviving taps of every kernel (Section II.B: zero weights are skipped).
 //
 // Mapping: a workgroup owns an 8x8 tile of output positions (one position per lane) and a
@@ -26,6 +27,15 @@ constexpr int kCoPerBlock = kCoPerWave * kWaves;
 constexpr int kChunk = 16;      // input channels staged per round
 constexpr int kPairs = kCoPerBlock * kChunk;
 
+// Element strides of the activation tensors: the kernel reads and writes one element at a time, so it serves
+// both layouts of the interface (channels-last, and NCHW) and channel slices of wider channels-last buffers.
+struct TensorStrides {
+    int64_t n, h, w, c;
+};
+struct DirectStrides {
+    TensorStrides x, y, r;  // input, output, residual
+};
+
 template <int KS, int S> struct Halo {
     static constexpr int side = (kTile - 1) * S + KS;
     static constexpr int count = side * side;
@@ -38,7 +48,7 @@ template <typename T, typename TO, int KS, int S, int KK>
 __global__ __launch_bounds__(256) void conv_direct_kernel(const T* __restrict__ x, TO* __restrict__ y,
                                                           const T* __restrict__ live, const uint8_t* __restrict__ lidx,
                                                           Dict dict, int N, int H, int W, int Ci, int Co, int Ho, int Wo,
-                                                          int tiles_w, Epilogue ep, int64_t G)
+                                                          int tiles_w, Epilogue ep, int64_t G, DirectStrides st)
 {
     using HL = Halo<KS, S>;
     constexpr int WS = KS == 1 ? 1 : (KK ? KK : 9);  // weights (and offsets) stored per pair
@@ -78,12 +88,15 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(const T* __restrict__ 
     for (int ci0 = 0; ci0 < Ci; ci0 += kChunk) {
         const int nch = Ci - ci0 < kChunk ? Ci - ci0 : kChunk;
         __syncthreads();  // previous chunk fully consumed (also orders the table writes above)
+        // (consecutive lanes read consecutive addresses: channels when they are contiguous, else positions)
+        const bool channels_fastest = st.x.c == 1;
         for (int e = tid; e < HL::count * kChunk; e += 256) {
-            const int ch = e % kChunk, pos = e / kChunk;
+            const int ch = channels_fastest ? e % kChunk : e / HL::count;
+            const int pos = channels_fastest ? e / kChunk : e % HL::count;
             const int ih = ih0 + pos / HL::side, iw = iw0 + pos % HL::side;
             float v = 0.f;
             if (ch < nch && ih >= 0 && ih < H && iw >= 0 && iw < W)
-                v = to_f32(x[(((int64_t)n * H + ih) * W + iw) * Ci + ci0 + ch]);
+                v = to_f32(x[n * st.x.n + ih * st.x.h + iw * st.x.w + (ci0 + ch) * st.x.c]);
             xs[ch * HL::padded + pos] = v;
         }
         // Weights of this chunk.  Pairs outside the layer (channel tails) get weight 0 at
@@ -138,7 +151,8 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(const T* __restrict__ 
 
     const int oh = oh0 + r, ow = ow0 + c;
     if (oh < Ho && ow < Wo) {
-        TO* yp = y + (((int64_t)n * Ho + oh) * Wo + ow) * Co;
+        TO* yp = y + n * st.y.n + oh * st.y.h + ow * st.y.w;
+        const TO* rp = (const TO*)ep.residual + n * st.r.n + oh * st.r.h + ow * st.r.w;
 #pragma unroll
         for (int i = 0; i < kCoPerWave; ++i) {
             const int co = co_block + wave * kCoPerWave + i;
@@ -147,8 +161,8 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(const T* __restrict__ 
                 if (ep.scale) v *= ep.scale[co];
                 if (ep.bias) v += ep.bias[co];
                 v = epi_act(v, ep.act);
-                if (ep.residual) v += to_f32(((const TO*)ep.residual)[(yp - y) + co]);
-                store_from_f32<TO>(yp + co, v);
+                if (ep.residual) v += to_f32(rp[co * st.r.c]);
+                store_from_f32<TO>(yp + co * st.y.c, v);
             }
         }
     }
@@ -166,9 +180,19 @@ static rtoss_status launch_typed(const rtoss_wdesc& d, const ConvParams& c, cons
         return fail(RTOSS_ESHAPE, "conv: batch or channel count too large for the direct kernel");
     dim3 grid((unsigned)(tiles_h * tiles_w), (unsigned)((d.Co + kCoPerBlock - 1) / kCoPerBlock), (unsigned)c.N);
     dim3 block(256);
+    DirectStrides st;
+    if (c.layout == RTOSS_NCHW) {
+        st.x = TensorStrides{(int64_t)d.Ci * c.H * c.W, c.W, 1, (int64_t)c.H * c.W};
+        st.y = TensorStrides{(int64_t)d.Co * Ho * Wo, Wo, 1, (int64_t)Ho * Wo};
+        st.r = st.y;
+    } else {
+        st.x = TensorStrides{(int64_t)c.H * c.W * d.Ci, (int64_t)c.W * d.Ci, d.Ci, 1};
+        st.y = TensorStrides{(int64_t)Ho * Wo * c.ep.ldy, (int64_t)Wo * c.ep.ldy, c.ep.ldy, 1};
+        st.r = TensorStrides{(int64_t)Ho * Wo * c.ep.ldr, (int64_t)Wo * c.ep.ldr, c.ep.ldr, 1};
+    }
 #define RTOSS_LAUNCH(KS, S, KK)                                                                                  \
     conv_direct_kernel<T, TO, KS, S, KK><<<grid, block, 0, s>>>((const T*)x, (TO*)y, (const T*)live, lidx, dict, c.N, \
-                                                                c.H, c.W, d.Ci, d.Co, Ho, Wo, tiles_w, c.ep, G)
+                                                                c.H, c.W, d.Ci, d.Co, Ho, Wo, tiles_w, c.ep, G, st)
 #define RTOSS_LAUNCH3(S)                  \
     switch (dict.k) {                     \
     case 2: RTOSS_LAUNCH(3, S, 2); break; \

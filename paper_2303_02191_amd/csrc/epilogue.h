@@ -14,6 +14,11 @@ struct Epilogue {
     const float* bias;     // [Co] or nullptr (= 0); 16-byte aligned
     const void* residual;  // tensor of the output's type and shape, or nullptr
     int act;               // rtoss_act: 0 none, 1 ReLU, 2 SiLU
+    // Channels-last tensors: elements from one position's channel 0 to the next position's.  Co for a plain
+    // tensor; larger when the convolution writes (or the shortcut reads) a channel slice of a wider buffer,
+    // e.g. its part of a concatenation (the slice's first channel is folded into the pointer).
+    int ldy;               // of the output
+    int ldr;               // of the residual
 };
 
 struct ConvParams : rtoss_cdesc {
@@ -58,13 +63,13 @@ template <int N> __device__ __forceinline__ void epi_scale_bias_act(float (&v)[N
     }
 }
 
-// Adds the residual's N consecutive elements that start `elem` elements into the tensor (8-byte
-// aligned runs for 16-bit types, 16-byte aligned for fp32).
-template <typename TO, int N> __device__ __forceinline__ void epi_residual(float (&v)[N], const Epilogue& ep, int64_t elem)
+// Adds the residual's N consecutive channels, starting at channel co, of position number `pos` (n, oh, ow
+// flattened) (8-byte aligned runs for 16-bit types, 16-byte aligned for fp32).
+template <typename TO, int N> __device__ __forceinline__ void epi_residual(float (&v)[N], const Epilogue& ep, int64_t pos, int co)
 {
     static_assert(N % 4 == 0, "runs of 4 elements");
     if (!ep.residual) return;
-    const TO* r = (const TO*)ep.residual + elem;
+    const TO* r = (const TO*)ep.residual + pos * ep.ldr + co;
 #pragma unroll
     for (int g = 0; g < N / 4; ++g) {
         if constexpr (sizeof(TO) == 4) {

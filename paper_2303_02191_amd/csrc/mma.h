@@ -66,6 +66,34 @@ RTOSS_MAT_STRUCT(MatV, f16_t, "f16", "+v", "=v")
 RTOSS_MAT_STRUCT(MatV, bf16_t, "bf16", "+v", "=v")
 #undef RTOSS_MAT_STRUCT
 
+// Dense step D = A * B + C over one 16-byte operand per lane, accumulator wherever the compiler keeps it
+// (the compiler-scheduled kernels): 32 channels of a 16-bit type in one instruction, or 16 fp32 channels
+// in four K = 4 steps, step s on element s of every lane's 16 bytes.
+template <typename T> struct Dense16;
+template <> struct Dense16<f16_t> {
+    static __device__ __forceinline__ f32x4 mma(u32x4 a, u32x4 b, f32x4 c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, a), __builtin_bit_cast(h8, b), c, 0, 0, 0);
+    }
+};
+template <> struct Dense16<bf16_t> {
+    static __device__ __forceinline__ f32x4 mma(u32x4 a, u32x4 b, f32x4 c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(b8, a), __builtin_bit_cast(b8, b), c, 0, 0, 0);
+    }
+};
+template <> struct Dense16<float> {
+    static __device__ __forceinline__ f32x4 mma(u32x4 a, u32x4 b, f32x4 c)
+    {
+        const f32x4 af = __builtin_bit_cast(f32x4, a), bf = __builtin_bit_cast(f32x4, b);
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(af.x, bf.x, c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(af.y, bf.y, c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(af.z, bf.z, c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(af.w, bf.w, c, 0, 0, 0);
+        return c;
+    }
+};
+
 // One 16-byte global -> LDS copy per lane without passing through registers: lane i of the
 // wave writes LDS address lds_wave_base + 16 * i (the base must be wave-uniform).
 __device__ __forceinline__ void copy16_to_lds(const void* gsrc, char* lds_wave_base)

@@ -116,11 +116,11 @@ __global__ __launch_bounds__(kSelBlock) void select_batch_kernel(SelectBatch bat
 
 rtoss_status launch_select_batch(const rtoss_select_item* items, int n, rtoss_dtype dt, const Dict& dict, hipStream_t s)
 {
-    for (int base = 0; base < n; base += kSelectBatchMax) {
+    for (int i = 0; i < n;) {  // i runs on across launches: tensors without a whole group take no table entry
         SelectBatch b;
         b.n = 0;
         int64_t blocks = 0;
-        for (int i = base; i < n && b.n < kSelectBatchMax; ++i) {
+        for (; i < n && b.n < kSelectBatchMax; ++i) {
             const int64_t G = items[i].n_elems / 9;
             if (G == 0) continue;
             b.w[b.n] = items[i].w_dev;

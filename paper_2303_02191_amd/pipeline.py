@@ -107,33 +107,50 @@ class PackedLayer:
         pad = ks // 2
         return (N, (H + 2 * pad - ks) // stride + 1, (W + 2 * pad - ks) // stride + 1, self.wdesc.Co)
 
-    def conv(self, x, stride=1, relu=False, out_dt=None, y=None):
-        """x: channels-last cuda tensor [N, H, W, Ci] of the layer's dtype. Returns y [N, Ho, Wo, Co]."""
-        assert x.is_cuda and x.is_contiguous() and x.shape[3] == self.wdesc.Ci
+    def conv(self, x, stride=1, relu=False, out_dt=None, y=None, layout=B.NHWC):
+        """x: cuda tensor of the layer's dtype, channels-last [N, H, W, Ci] (or [N, Ci, H, W] with layout=B.NCHW).
+        Returns y [N, Ho, Wo, Co] (or [N, Co, Ho, Wo])."""
+        assert x.is_cuda and x.is_contiguous()
         out_dt = self.dt if out_dt is None else out_dt
+        if layout == B.NCHW:
+            N, C, H, W = x.shape
+            shape = self.out_shape((N, H, W, C), stride)
+            shape = (shape[0], shape[3], shape[1], shape[2])
+        else:
+            N, H, W, C = x.shape
+            shape = self.out_shape(x.shape, stride)
+        assert C == self.wdesc.Ci
         if y is None:
-            y = torch.empty(self.out_shape(x.shape, stride), dtype=TORCH_DTYPE[out_dt], device=x.device)
-        N, H, W, _ = x.shape
-        cdesc = B.CDesc(N, H, W, stride, self.wdesc.ksize // 2, B.NHWC, out_dt, int(bool(relu)))
+            y = torch.empty(shape, dtype=TORCH_DTYPE[out_dt], device=x.device)
+        cdesc = B.CDesc(N, H, W, stride, self.wdesc.ksize // 2, layout, out_dt, int(bool(relu)))
         B.rtoss_conv2d_pattern(self.wdesc, cdesc, self.masks, self.blob.data_ptr(), x.data_ptr(), y.data_ptr(),
                                _stream())
         return y
 
     def conv_fused(self, x, stride=1, scale=None, bias=None, act=B.ACT_NONE, residual=None, out_dt=None, y=None):
         """y = act(scale[co] * conv + bias[co]) + residual.  scale/bias: float32 cuda tensors [Co] or None;
-        residual: cuda tensor of y's dtype and shape or None."""
+        residual: cuda tensor of y's dtype and shape or None.  y and residual may be channel slices
+        buf[..., c0:c0+Co] of wider channels-last buffers (a concatenation the layer writes its part of)."""
         assert x.is_cuda and x.is_contiguous() and x.shape[3] == self.wdesc.Ci
         out_dt = self.dt if out_dt is None else out_dt
         if y is None:
             y = torch.empty(self.out_shape(x.shape, stride), dtype=TORCH_DTYPE[out_dt], device=x.device)
         for t in (scale, bias):
             assert t is None or (t.is_cuda and t.dtype == torch.float32 and t.numel() == self.wdesc.Co)
-        assert residual is None or (residual.is_cuda and residual.is_contiguous() and residual.shape == y.shape
-                                    and residual.dtype == y.dtype)
+
+        def pitch(t):  # position pitch of a channels-last tensor or channel slice of one (0: plain)
+            n, h, w, c = t.shape
+            ld = t.stride(2)
+            assert t.stride(3) == 1 and t.stride(1) == w * ld and t.stride(0) == h * w * ld, "not a channel slice"
+            return 0 if ld == c else ld
+
+        assert tuple(y.shape) == self.out_shape(x.shape, stride) and y.dtype == TORCH_DTYPE[out_dt]
+        assert residual is None or (residual.is_cuda and residual.shape == y.shape and residual.dtype == y.dtype)
         N, H, W, _ = x.shape
         cdesc = B.CDesc(N, H, W, stride, self.wdesc.ksize // 2, B.NHWC, out_dt, 0)
         ep = B.EpilogueDesc(scale.data_ptr() if scale is not None else None, bias.data_ptr() if bias is not None else None,
-                            int(act), residual.data_ptr() if residual is not None else None)
+                            int(act), residual.data_ptr() if residual is not None else None,
+                            pitch(y), pitch(residual) if residual is not None else 0)
         B.rtoss_conv2d_pattern_fused(self.wdesc, cdesc, ep, self.masks, self.blob.data_ptr(), x.data_ptr(), y.data_ptr(),
                                      _stream())
         return y

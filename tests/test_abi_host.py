@@ -100,7 +100,7 @@ def test_conv_argument_errors():
         return B.CDesc(a["N"], a["H"], a["W"], a["stride"], a["pad"], a["layout"], a["out_dt"], a["fuse_relu"])
 
     call = B.rtoss_conv2d_pattern
-    assert _status(call, d, cd(layout=B.NCHW), masks, fake_p, fake_x, fake_y) == B.ELAYOUT
+    assert _status(call, d, cd(layout=7), masks, fake_p, fake_x, fake_y) == B.EINVAL  # unknown layout
     assert _status(call, d, cd(stride=3), masks, fake_p, fake_x, fake_y) == B.ESHAPE
     assert _status(call, d, cd(pad=0), masks, fake_p, fake_x, fake_y) == B.ESHAPE
     assert _status(call, d, cd(N=0), masks, fake_p, fake_x, fake_y) == B.ESHAPE
@@ -187,6 +187,18 @@ def test_fused_conv_argument_errors():
     with pytest.raises(B.RtossError) as e:  # residual overlapping the output
         B.rtoss_conv2d_pattern_fused(wd, ok, B.EpilogueDesc(None, None, 0, (1 << 20) + 64), masks, 256, 512, 1 << 20)
     assert e.value.status == B.EINVAL
+    # output / residual pitches (channel slices of wider buffers)
+    for ep, want in [(B.EpilogueDesc(None, None, 0, None, 16, 0), B.ESHAPE),      # below Co
+                     (B.EpilogueDesc(None, None, 0, None, 0, 24), B.ESHAPE),
+                     (B.EpilogueDesc(None, None, 0, None, 36, 0), B.EINVAL),      # not a multiple of 16 bytes
+                     (B.EpilogueDesc(None, None, 0, None, -8, 0), B.EINVAL)]:
+        with pytest.raises(B.RtossError) as e:
+            B.rtoss_conv2d_pattern_fused(wd, ok, ep, masks, 256, 512, 1 << 20)
+        assert e.value.status == want
+    with pytest.raises(B.RtossError) as e:  # pitches describe channels-last tensors
+        B.rtoss_conv2d_pattern_fused(wd, B.CDesc(1, 8, 8, 1, 1, B.NCHW, B.F16, 0), B.EpilogueDesc(None, None, 0, None, 64, 0),
+                                     masks, 256, 512, 1 << 20)
+    assert e.value.status == B.ELAYOUT
 
 
 def test_batched_pack_argument_errors():

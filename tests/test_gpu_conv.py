@@ -275,20 +275,33 @@ def _sample_points(rng, N, Co, Ho, Wo, n):
     return np.concatenate([pts, np.array(extra)]).astype(np.int32)
 
 
-def _check_layer_sampled(cfg, L, xs, xv, ws, wv, masks, relu, npts, seed):
-    """Full-size layer: selection bit-exact, conv checked on sampled outputs + rms bound from them."""
+# The oracle's direct loop does about 1.4 G multiply-adds per second and core; a layer whose whole output
+# would take it longer than this (on the cores it has) is checked on sampled outputs instead.
+ORACLE_BUDGET_S = 20.0
+
+
+def _oracle_seconds(N, L):
+    return N * L.Ho * L.Wo * L.Co * L.Ci * L.ksize * L.ksize / (1.2e9 * max(1, oracle.threads()))
+
+
+def _check_layer_full(cfg, L, xs, xv, ws, wv, masks, relu, seed, npts=4000):
+    """Full-size layer in the benchmarked launch shape: selection bit-exact; EVERY output element compared
+    with the oracle's direct convolution (sampled outputs only when the whole tensor would exceed
+    ORACLE_BUDGET_S of oracle time)."""
     idx = oracle.select(wv, masks)
     wm = oracle.mask(wv, masks, idx)
     g = GpuLayer(ws, cfg.dtype, masks, cfg.k)
     assert np.array_equal(g.idx_host(), idx)
     y32 = g.conv_nchw(xs, stride=L.stride, relu=relu, out_dt=wl.F32)
-    pts = _sample_points(np.random.default_rng(seed), xs.shape[0], L.Co, L.Ho, L.Wo, npts)
-    ref = oracle.conv2d_points(xv, wm, pts, stride=L.stride, relu=relu)
-    got = y32[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]].astype(np.float64)
-    err = np.max(np.abs(got - ref))
-    bound = 1e-5 * np.max(np.abs(ref)) if cfg.dtype == wl.F32 else 2e-3 * np.sqrt(np.mean(ref ** 2))
-    assert err <= bound, "max err %.3e > bound %.3e" % (err, bound)
     assert np.isfinite(y32).all()
+    if _oracle_seconds(xs.shape[0], L) <= ORACLE_BUDGET_S:
+        ref = oracle.conv2d(xv, wm, stride=L.stride, relu=relu)
+        assert y32.shape == ref.shape
+        check(y32, ref, cfg.dtype)
+    else:
+        pts = _sample_points(np.random.default_rng(seed), xs.shape[0], L.Co, L.Ho, L.Wo, npts)
+        ref = oracle.conv2d_points(xv, wm, pts, stride=L.stride, relu=relu)
+        check(y32[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]], ref, cfg.dtype)
     return g, y32
 
 
@@ -300,7 +313,10 @@ def test_cfg2_full_layers():
     for i, L in enumerate(cfg.layers):
         xs, xv = wl.draw_x(rng, cfg, L)
         ws, wv = wl.draw_w(rng, cfg, L)
-        _check_layer_sampled(cfg, L, xs, xv, ws, wv, masks, False, 4000, seed=i)
+        assert _oracle_seconds(cfg.N, L) <= ORACLE_BUDGET_S  # whole tensors
+        g, y32 = _check_layer_full(cfg, L, xs, xv, ws, wv, masks, False, seed=i)
+        y16 = g.conv_nchw(xs, stride=L.stride)
+        assert np.array_equal(y16, wl.round_to_dtype(y32.astype(np.float64), cfg.dtype))
 
 
 def test_cfg3_full():
@@ -311,12 +327,15 @@ def test_cfg3_full():
     assert masks.size == 12
     xs, xv = wl.draw_x(rng, cfg, L)
     ws, wv = wl.draw_w(rng, cfg, L)
-    _check_layer_sampled(cfg, L, xs, xv, ws, wv, masks, False, 20000, seed=3)
+    assert _oracle_seconds(cfg.N, L) <= ORACLE_BUDGET_S  # whole tensor
+    g, y32 = _check_layer_full(cfg, L, xs, xv, ws, wv, masks, False, seed=3)
+    y16 = g.conv_nchw(xs)
+    assert np.array_equal(y16, wl.round_to_dtype(y32.astype(np.float64), cfg.dtype))
 
 
 def test_cfg4_full_chain():
-    """Four stacked 3x3 layers with ReLU between; each layer is checked against the oracle fed
-    with the GPU's own stored (bf16) output of the previous layer."""
+    """Four stacked 3x3 layers with ReLU between; every output element of each layer is checked against the
+    oracle fed with the GPU's own stored (bf16) output of the previous layer."""
     cfg = wl.get_config(4)
     rng = wl.make_rng(cfg)
     masks = B.rtoss_pattern_dict(cfg.k)
@@ -324,36 +343,62 @@ def test_cfg4_full_chain():
     weights = [wl.draw_w(rng, cfg, L) for L in cfg.layers]
     for i, L in enumerate(cfg.layers):
         ws, wv = weights[i]
-        g, y32 = _check_layer_sampled(cfg, L, xs, xv, ws, wv, masks, L.relu, 3000, seed=40 + i)
+        assert _oracle_seconds(cfg.N, L) <= ORACLE_BUDGET_S  # whole tensors
+        g, y32 = _check_layer_full(cfg, L, xs, xv, ws, wv, masks, L.relu, seed=40 + i)
         y16 = g.conv_nchw(xs, stride=1, relu=L.relu)
         assert np.array_equal(y16, wl.round_to_dtype(y32.astype(np.float64), cfg.dtype))
         xs, xv = y16, wl.to_f64(y16, cfg.dtype)
 
 
-def test_cfg5_layers_reduced_batch():
-    """Every distinct layer shape of the YOLOv5s-shaped set at full spatial size and batch 2
-    (sampled outputs); the batch-16 launch configuration is covered by test_cfg5_batch16_launch."""
+def test_cfg5_all_layers_batch16():
+    """All 57 layers of the YOLOv5s-shaped set at batch 16, the benchmarked launch shape: whole output tensors
+    against the oracle (every layer fits the oracle budget on the test machine's cores; the helper falls back
+    to sampled outputs where one would not)."""
     cfg = wl.get_config(5)
     masks = B.rtoss_pattern_dict(cfg.k)
-    seen = set()
     rng = wl.make_rng(cfg)
+    sampled = []
     for i, L in enumerate(cfg.layers):
-        key = (L.Ci, L.Co, L.H, L.ksize, L.stride)
-        if key in seen:
-            continue
-        seen.add(key)
-        xs, xv = wl.draw_x(rng, cfg, L, N=2)
-        ws, wv = wl.draw_w(rng, cfg, L)
-        _check_layer_sampled(cfg, L, xs, xv, ws, wv, masks, False, 1500, seed=500 + i)
-
-
-def test_cfg5_batch16_launch():
-    """Batch 16 (the benchmarked launch shape) on three representative layers."""
-    cfg = wl.get_config(5)
-    masks = B.rtoss_pattern_dict(cfg.k)
-    rng = np.random.default_rng(55)
-    for li in (1, 9, 36):
-        L = cfg.layers[li]
         xs, xv = wl.draw_x(rng, cfg, L)
         ws, wv = wl.draw_w(rng, cfg, L)
-        _check_layer_sampled(cfg, L, xs, xv, ws, wv, masks, False, 1500, seed=li)
+        if _oracle_seconds(cfg.N, L) > ORACLE_BUDGET_S:
+            sampled.append(i)
+        _check_layer_full(cfg, L, xs, xv, ws, wv, masks, i % 2 == 0, seed=500 + i)
+        print("cfg5 layer %d (%d->%d @%d %dx%d s%d) ok" % (i, L.Ci, L.Co, L.H, L.ksize, L.ksize, L.stride), flush=True)
+    assert len(sampled) <= 4, "layers checked on samples only: %r" % (sampled,)
+
+
+NCHW_CASES = [
+    # dt, N, Ci, Co, H, W, ks, stride, k, relu: shapes that take the matrix-core kernels when channels-last,
+    # and shapes of the element-wise kernel
+    (wl.F16, 2, 64, 64, 17, 23, 3, 1, 3, False),
+    (wl.BF16, 1, 128, 144, 20, 24, 3, 2, 2, True),
+    (wl.F16, 2, 256, 64, 9, 11, 1, 1, 2, False),
+    (wl.F32, 1, 16, 24, 14, 15, 3, 1, 4, True),
+    (wl.F16, 1, 3, 32, 20, 20, 3, 2, 3, False),
+    (wl.BF16, 3, 5, 7, 8, 8, 1, 1, 2, False),
+]
+
+
+@pytest.mark.parametrize("case", NCHW_CASES)
+def test_conv_nchw_layout(case):
+    """RTOSS_NCHW activations ([N][C][H][W] in and out): same results as the oracle, and for 16-bit tensors
+    exactly the channels-last call's output, transposed."""
+    import torch
+    from paper_2303_02191_amd import pipeline as pl
+    dt, N, Ci, Co, H, W, ks, stride, k, relu = case
+    rng = np.random.default_rng(7000 + Ci + Co + ks)
+    masks = B.rtoss_pattern_dict(k)
+    xs = wl.round_to_dtype(rng.standard_normal((N, Ci, H, W)), dt)
+    ws = wl.round_to_dtype(rng.standard_normal((Co, Ci, ks, ks)) * 0.05, dt)
+    g = GpuLayer(ws, dt, masks, k)
+    ref = oracle.conv2d(wl.to_f64(xs, dt), oracle.mask(wl.to_f64(ws, dt), masks, g.idx_host()), stride=stride, relu=relu)
+    x_nchw = pl.to_device(np.ascontiguousarray(xs), dt)
+    y32 = g.layer.conv(x_nchw, stride=stride, relu=relu, out_dt=wl.F32, layout=B.NCHW)
+    torch.cuda.synchronize()
+    assert tuple(y32.shape) == ref.shape
+    check(pl.to_host(y32), ref, dt)
+    if dt != wl.F32:
+        y16 = g.layer.conv(x_nchw, stride=stride, relu=relu, layout=B.NCHW)
+        torch.cuda.synchronize()
+        assert np.array_equal(pl.to_host(y16), wl.round_to_dtype(pl.to_host(y32).astype(np.float64), dt))
