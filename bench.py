@@ -59,7 +59,7 @@ def measured_traffic(summary_name):
             fields[k.strip()] = v.strip()
     try:
         h = hashlib.sha256()
-        for f in ("conv3x3_sparse.hip", "mma.h", "dtypes.h", "common.h", "pack_live.h", "epilogue.h", "tile3x3.h"):
+        for f in ("conv3x3_rows.hip", "sparse_frag.h", "mma.h", "dtypes.h", "common.h", "epilogue.h"):
             h.update(open(os.path.join(here, "paper_2303_02191_amd", "csrc", f), "rb").read())
         if h.hexdigest() != fields.get("kernel_source_sha256"):
             return None

@@ -124,6 +124,10 @@ rtoss_status launch_pack_sparse3x3(const rtoss_wdesc& d, const void* w, const ui
 rtoss_status launch_conv3x3_sparse(const rtoss_wdesc& d, const ConvParams& c, const void* section, const void* x,
                                    void* y, hipStream_t s);
 
+// ... large stride-1 layers: pipelined kernel over strips of output rows (conv3x3_rows.hip); same packed section
+rtoss_status launch_conv3x3_rows(const rtoss_wdesc& d, const ConvParams& c, const void* section, const void* x, void* y,
+                                 hipStream_t s);
+
 // 3x3 convolution in dense mode on the matrix cores (conv3x3_dense.hip)
 bool dense3x3_shape_ok(const rtoss_wdesc& d);
 size_t dense3x3_section_bytes(const rtoss_wdesc& d);

@@ -31,10 +31,9 @@
 // (8 channels of one tap) and the 4x4 (tap, channel) blocks are transposed in registers
 // with byte permutes so that one lane holds, for 4 channels, the 4 taps of a group.
 //
-// Two kernels share that data flow.  The pipelined one (large layers, stride 1) keeps two
-// LDS buffers, one persistent workgroup per compute unit and a hand-placed schedule of
-// matrix instructions, LDS reads, permutes and copies.  The single-buffered one (stride 2,
-// small layers) is a plain loop nest with small tiles, several workgroups per compute unit.
+// This file holds the packer and the single-buffered kernel (stride 2, and stride-1 layers with few channels or
+// few tiles): a plain loop nest with small tiles, several workgroups per compute unit.  Large stride-1 layers
+// take the pipelined kernel of conv3x3_rows.hip, which reads the same packed section.
 #include <algorithm>
 #include <type_traits>
 
@@ -43,21 +42,12 @@
 #include "epilogue.h"
 #include "mma.h"
 #include "pack_live.h"
+#include "sparse_frag.h"
 #include "tile3x3.h"
 
 namespace rtoss {
 
 namespace {
-
-// Packed weight fragments: per (stage of 32 input channels, tile of 16 output channels)
-//   5 operand fragments of 64 lanes x 16 bytes: corner step 0/1, edge step 0/1, centre
-//   then 2 index words per lane: [corner][lane], [edge][lane]; low half = step 0, high = step 1
-// (which output channel a row of a tile is: tile_row_channel)
-constexpr int kFragBytes = 1024;
-constexpr int kTileBytes = 5 * kFragBytes + 2 * 64 * 4;  // 5632
-// 16-bit outputs without a fused output stage are stored straight from the accumulators (measured faster
-// than the transposition through LDS once a lane's values are 32 contiguous bytes: tile_row_channel)
-constexpr bool kDirectEpilogue = true;
 
 __device__ __forceinline__ int tap_of_slot(int group, int f)
 {
@@ -70,21 +60,6 @@ __device__ __forceinline__ int tap_of_slot(int group, int f)
 __device__ __forceinline__ int stage_channel(int q, int g, int half)
 {
     return 8 * (2 * (q & 1) + (g >> 1)) + 4 * half + 2 * (q >> 1) + (g & 1);
-}
-
-// Output channel held by row r of channel tile mt.  Within a group of 4 tiles (64 channels) the rows
-// are dealt so that the accumulator values one lane holds after the multiplication -- rows
-// 4q .. 4q+3 of each of the 4 tiles -- are the 16 consecutive channels 64*(mt/4) + 16q .. +15:
-// the epilogues store runs of 16 channels without exchanging data between lanes.
-__device__ __forceinline__ int tile_row_channel(int mt, int r)
-{
-    return 64 * (mt >> 2) + 16 * (r >> 2) + 4 * (mt & 3) + (r & 3);
-}
-// first of the 4 consecutive channels that quarter q of a lane holds of tile mm (counted from the
-// first channel of mm's group of 4 tiles when mm < 4; mm may run over several groups)
-__device__ __forceinline__ int tile_quarter_offset(int mm, int q)
-{
-    return 64 * (mm >> 2) + 16 * q + 4 * (mm & 3);
 }
 
 struct SparsePackArgs {
@@ -223,37 +198,6 @@ __global__ __launch_bounds__(256) void pack_sparse3x3_batch_kernel(SparsePackBat
     const int t = batch_entry(b, (int)blockIdx.x);  // block-uniform
     pack_sparse3x3_body<T>(b.a[t], dict, (int)blockIdx.x - b.first_block[t]);
 }
-
-// Channel tiles per stage in the packed section: padded so that every block of 8 tiles is complete.
-inline int padded_m_tiles(int Co) { return ((Co + 15) / 16 + 7) / 8 * 8; }
-// The section is [fragments][block of zeros]; the zeros feed the copy lanes that fill padding.
-inline size_t fragment_bytes(const rtoss_wdesc& d) { return (size_t)(d.Ci / 32) * padded_m_tiles(d.Co) * kTileBytes; }
-inline size_t zero_block_bytes(const rtoss_wdesc& d) { return align_up((size_t)2 * d.Ci + 16, 256); }
-
-// When the B operands of the sparse steps are fetched and transposed within a stage of 20 units
-// (see the stage loop of conv3x3_sparse_kernel).
-template <int TN> struct JobSchedule {
-    static constexpr int jobs = 2 * TN;
-    static constexpr int load_unit(int q) { return q < TN ? (q - (TN - 3) < -1 ? -1 : q - (TN - 3)) : 6 + (q - TN); }
-    static constexpr int perm_count(int u)
-    {
-        int n = 0;
-        for (int q = 0; q < jobs; ++q) n += load_unit(q) + 1 == u;
-        return n;
-    }
-    static constexpr int perm_first(int u)
-    {
-        for (int q = 0; q < jobs; ++q)
-            if (load_unit(q) + 1 == u) return q;
-        return 0;
-    }
-    static constexpr int read_job(int u)
-    {
-        for (int q = 0; q < jobs; ++q)
-            if (load_unit(q) == u) return q;
-        return -1;
-    }
-};
 
 // Single-buffered variant: one LDS buffer, two barriers per stage, plain loop nest scheduled by the
 // compiler.  It needs half the LDS of the pipelined kernel below and few registers, so several
@@ -485,464 +429,6 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
     }
 }
 
-// FUSED: scale / bias / SiLU / residual in the epilogue.  The plain instantiation (ReLU or nothing) keeps
-// its branch-free epilogue; the fused one pays for generality with a few uniform branches per tile.
-template <typename T, typename TO, int S, int TM, int TN, int RT, int CT, bool FUSED>
-__global__ __launch_bounds__(256, 1) void conv3x3_sparse_kernel(const T* __restrict__ x, TO* __restrict__ y,
-                                                                const char* __restrict__ wfrag,
-                                                                const char* __restrict__ zeros, int H, int W, int Ci,
-                                                                int Co, int Ho, int Wo, int m_tiles_total,
-                                                                int tiles_c, int tiles_per_img, int co_blocks,
-                                                                int total_work, int work_per_xcd, Epilogue ep)
-{
-    using G = Geom<S, RT, CT>;
-    static_assert(RT * CT == 4 * TN, "four waves share the position blocks of a workgroup");
-    static_assert(TN == 4 || TN == 5, "the job schedule below covers 4 or 5 position blocks per wave");
-    static_assert(TM == 8, "a stage is 20 units: 5 phases x 4 pairs of channel tiles");
-    constexpr int A_BYTES = TM * kTileBytes;
-    constexpr int A_WAVE_COPIES = A_BYTES / 1024;              // 64 lanes x 16 B per copy instruction
-    constexpr int A_PER_WAVE = (A_WAVE_COPIES + 3) / 4;
-    constexpr int X_BYTES = G::x_bytes;
-    constexpr int X_CHUNKS = X_BYTES / 16;                     // including the pad chunk of every position
-    constexpr int X_WAVE_COPIES = (X_CHUNKS + 63) / 64;
-    constexpr int X_PER_WAVE = (X_WAVE_COPIES + 3) / 4;
-    constexpr int X_AREA = X_PER_WAVE * 4 * 1024;              // what the copy instructions cover (>= X_BYTES)
-    constexpr int REGION = A_BYTES + X_AREA;                   // one pipeline buffer: [weights][activations]
-    extern __shared__ __attribute__((aligned(16))) char smem[];  // two regions
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int stages = Ci / 32;
-    const int64_t a_stage_stride = (int64_t)m_tiles_total * kTileBytes;
-
-    // Persistent workgroups: one per compute unit, each walking a list of output tiles so that
-    // the copies for a tile's first stage overlap the previous tile's last stage and the output
-    // stores overlap the next tile's arithmetic.  Workgroups are dealt round-robin to the 8 XCDs
-    // (each with its own L2); every XCD gets a contiguous range of work items so that the channel
-    // blocks of one spatial tile, and neighbouring tiles, share an L2.
-    const int xcd = blockIdx.x % 8, slot_in_xcd = blockIdx.x / 8, slots_per_xcd = gridDim.x / 8;
-    const int work_end = min((xcd + 1) * work_per_xcd, total_work);
-    int work = xcd * work_per_xcd + slot_in_xcd;
-    if (work >= work_end) return;
-    // All workgroups run the same code on same-sized tiles, so left alone they reach their
-    // epilogues together and the output stores of the whole chip arrive as one burst that the
-    // memory system drains while every matrix pipe idles.  Workgroups that own fewer tiles than
-    // the busiest one have a tile's worth of slack: they start half a tile late, which moves their
-    // store bursts into the others' K loops at no cost to the makespan.
-    {
-        const int my_tiles = (work_end - work + slots_per_xcd - 1) / slots_per_xcd;
-        const int max_tiles = (work_per_xcd + slots_per_xcd - 1) / slots_per_xcd;
-        if (my_tiles < max_tiles) {
-            const int naps = (stages * 4000 + 8000) / 2 / 8128;  // s_sleep 127 = 127 * 64 cycles
-            for (int i = 0; i < naps; ++i) __builtin_amdgcn_s_sleep(127);
-        }
-    }
-
-    // ---- per-tile state ----
-    // Every lane copies 16 bytes in every copy instruction, so the copy code has no branches: a
-    // lane whose LDS slot is zero padding of the tile (or an unused pad slot) reads from a block
-    // of zeros that the packer appended to the weight fragments (2*Ci + 16 bytes, so that the
-    // per-stage advance of 64 bytes stays inside it).
-    int n_img, mt0, oh0, ow0;
-    const char* x_ptr[X_PER_WAVE];  // per lane and copy slot: source address for stage 0
-    auto setup_tile_coords = [&](int w) {
-        const int cblk = w % co_blocks;
-        const int tile = (w / co_blocks) % tiles_per_img;
-        n_img = w / (co_blocks * tiles_per_img);
-        mt0 = cblk * TM;
-        oh0 = (tile / tiles_c) * G::TH;
-        ow0 = (tile % tiles_c) * G::TW;
-    };
-    auto setup_tile_sources = [&]() {
-        const int ih0 = oh0 * S - 1, iw0 = ow0 * S - 1;
-#pragma unroll
-        for (int k = 0; k < X_PER_WAVE; ++k) {
-            const int c = ((k * 4 + wave) * 64 + lane);
-            const int pos = c / G::kChunks, q = c % G::kChunks;
-            const int pr = pos / G::LW, pc = pos % G::LW;
-            const int ih = ih0 + pr, iw = iw0 + pc;
-            const bool inside = q < 4 && pr < G::IH && pc < G::IW && ih >= 0 && ih < H && iw >= 0 && iw < W;
-            // offset in 16-byte chunks: fits 31 bits (checked by the launcher)
-            const int off = ((n_img * H + ih) * W + iw) * (Ci >> 3) + q;
-            x_ptr[k] = inside ? (const char*)x + (int64_t)off * 16 : zeros;
-        }
-    };
-    // One copy instruction (64 lanes x 16 bytes) of stage `stage` of the current tile into region
-    // `par`: slots 0 .. A_PER_WAVE-1 move weight fragments, the rest move activations.
-    constexpr int COPY_SLOTS = A_PER_WAVE + X_PER_WAVE;
-    static_assert(COPY_SLOTS <= 20, "two copies per unit in the first ten units of a stage");
-    static_assert(A_WAVE_COPIES % 4 == 0, "every wave issues the same number of weight copies");
-    auto issue_copy_slot = [&](int slot, int stage, int par) {
-        char* region = smem + par * REGION;
-        if (slot < A_PER_WAVE) {
-            const int kk = slot * 4 + wave;
-            const char* asrc = wfrag + (int64_t)mt0 * kTileBytes + lane * 16 + stage * a_stage_stride;
-            copy16_to_lds(asrc + kk * 1024, region + kk * 1024);
-        } else {
-            const int k = slot - A_PER_WAVE;
-            const int kk = k * 4 + wave;
-            // (the last copy instructions reach past the activation tile into the slack of X_AREA)
-            copy16_to_lds(x_ptr[k] + stage * 64, region + A_BYTES + kk * 1024);
-        }
-    };
-
-    // ---- per-lane read addresses ----
-    const int nn = lane & 15, qq = lane >> 4;
-    const int pr = nn >> 2, pc = nn & 3;
-    // the 4 position blocks of a wave sit at compile-time offsets from the first one
-    const int blk0 = wave * TN;
-    int xb[TN];
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int blk = blk0 + j;
-        xb[j] = (((4 * (blk / CT) + pr) * S) * G::LW + (4 * (blk % CT) + pc) * S) * G::kPos + qq * 16;
-    }
-
-    f32x4 acc[TM][TN];
-
-    // B operands of the sparse steps need a 4x4 (tap x channel) transpose: a "job" reads the 4 taps of
-    // one position block (4 x 16 bytes) and permutes them one pipeline unit later.  Job q < TN = corner
-    // taps of block q, job TN + b = edge taps of block b (schedule: JobSchedule).
-    using Sched = JobSchedule<TN>;
-    constexpr int kJobs = Sched::jobs;
-    auto raw_load = [&](const char* X, u32x4 (&rr)[4], int j, int group) {
-#pragma unroll
-        for (int f = 0; f < 4; ++f) {
-            const int t = group == 0 ? ((f & 1) * 2 + (f >> 1) * 6) : (2 * f + 1);
-            rr[f] = *(const u32x4*)(X + xb[j] + ((t / 3) * G::LW + (t % 3)) * G::kPos);
-        }
-    };
-    // Operand registers that cross stage boundaries: the reads a stage needs before its first matrix
-    // instruction (centre-tap operands of all blocks, weight fragments of unit 0, taps of the jobs
-    // permuted in unit 0) are issued from inside the previous stage's last unit.
-    u32x4 bc[TN];
-    u32x4 rr[kJobs][4];  // every job has its own name; its registers are live from its reads to its permutes
-    u32x4 a_nxt[2];
-    auto load_stage_prologue = [&](int par) {
-        const char* A = smem + par * REGION + lane * 16;
-        const char* X = smem + par * REGION + A_BYTES;
-#pragma unroll
-        for (int j = 0; j < TN; ++j) bc[j] = *(const u32x4*)(X + xb[j] + (G::LW + 1) * G::kPos);
-        a_nxt[0] = *(const u32x4*)(A + 4 * kFragBytes);
-        a_nxt[1] = *(const u32x4*)(A + kTileBytes + 4 * kFragBytes);
-        static_for<kJobs>([&](auto Q) {
-            constexpr int q = decltype(Q)::value;
-            if constexpr (Sched::load_unit(q) == -1) raw_load(X, rr[q], q % TN, q / TN);
-        });
-    };
-
-    // (the weight copies need only the tile's channel block: they are under way while the lanes work out
-    // their activation sources, ~3 k cycles of address arithmetic)
-    setup_tile_coords(work);
-#pragma unroll
-    for (int slot = 0; slot < A_PER_WAVE; ++slot) issue_copy_slot(slot, 0, 0);
-    setup_tile_sources();
-#pragma unroll
-    for (int slot = A_PER_WAVE; slot < COPY_SLOTS; ++slot) issue_copy_slot(slot, 0, 0);
-    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's copies have landed in LDS
-    __syncthreads();                     // ... and everybody's
-    int gpar = 0;     // region that holds the stage about to be multiplied
-    load_stage_prologue(0);
-
-  for (;;) {  // tiles
-    // output coordinates of the tile being multiplied (the copy state moves on to the next tile early)
-    const int t_n = n_img, t_mt0 = mt0, t_oh0 = oh0, t_ow0 = ow0;
-    const int next_work = work + slots_per_xcd;
-    const bool has_next = next_work < work_end;
-    // (no clearing of the accumulators: the first stage's centre step, which visits every one of them
-    // first, writes a * b instead of adding to it)
-    auto run_stage = [&](auto first_tag, int stage) {
-        constexpr bool FIRST = decltype(first_tag)::value;
-        // the stage copied while this one is multiplied: the tile's next stage, or the next tile's first
-        // (in the very last stage of the last tile there is nothing left to fetch; stage 0 of the
-        // same tile is fetched again into the free region, which keeps this code free of branches)
-        const bool last_stage = stage + 1 == stages;
-        const int copy_stage = last_stage ? 0 : stage + 1;
-        if (last_stage && has_next) {
-            setup_tile_coords(next_work);
-            setup_tile_sources();
-        }
-        const char* A = smem + gpar * REGION + lane * 16;
-        const char* AI = smem + gpar * REGION + 5 * kFragBytes + lane * 4;
-        const char* X = smem + gpar * REGION + A_BYTES;
-
-        // One stage = 5 phases (centre, corner step 0/1, edge step 0/1) of TM*TN matrix
-        // instructions = 20 units of 2*TN (two channel tiles x TN position blocks).  LDS reads are
-        // issued one unit ahead of their use, right after the unit's first matrix instruction,
-        // so the wait in front of the next unit's first instruction only covers loads that have
-        // had a whole unit to complete; a job's permutes are spread behind the matrix instructions
-        // of the unit after its reads.
-        //
-        // Stage hand-over without a bubble: all of a stage's copies are issued in its first 10 units,
-        // and the reads of the last unit's operands are issued in unit 18.  Behind the first matrix
-        // instruction of unit 19 the wave therefore waits for its copies and its reads, meets the
-        // others at a barrier (the next stage's data is now complete and nobody reads this stage's
-        // region any more), and issues the next stage's first reads, which complete under the rest of
-        // unit 19.
-        // output o (0..15) of a job: dword o%8 of step o/8; element 4*c + f of a step's B operand =
-        // channel c (of this lane's 4 in that step), tap slot f
-        auto transposed = [&](const u32x4 (&rr)[4], int o) -> uint32_t {
-            const int d = o & 7, comp = (o >> 3) * 2 + (d >> 2);
-            const uint32_t sel = (d & 2) ? 0x07060302u : 0x05040100u;
-            return (d & 1) ? __builtin_amdgcn_perm(rr[3][comp], rr[2][comp], sel)
-                           : __builtin_amdgcn_perm(rr[1][comp], rr[0][comp], sel);
-        };
-        constexpr int UNIT = 2 * TN;  // matrix instructions per unit
-        u32x8 bfc[2][TN], bfe[2][TN];
-        u32x4 a_cur[2] = {a_nxt[0], a_nxt[1]};
-        int i_cur[2] = {0, 0}, i_nxt[2] = {0, 0};
-
-        static_for<20>([&](auto U) {
-            constexpr int u = decltype(U)::value;
-            constexpr int phase = u / 4, m0 = (u % 4) * 2;
-            // jobs permuted in this unit (a contiguous range of job numbers) and the job read in it
-            constexpr int perm_first = Sched::perm_first(u), perm_count = Sched::perm_count(u);
-            constexpr int job_read = Sched::read_job(u);
-            static_for<UNIT>([&](auto I) {
-                constexpr int i = decltype(I)::value;
-                constexpr int mi = i / TN, j = i % TN, m = m0 + mi;
-                if constexpr (phase == 0) {
-                    if constexpr (FIRST) Mat<T>::dense_first(a_cur[mi], bc[j], acc[m][j]);
-                    else Mat<T>::dense(a_cur[mi], bc[j], acc[m][j]);
-                }
-                if constexpr (phase == 1) Mat<T>::template sparse<0>(a_cur[mi], bfc[0][j], acc[m][j], i_cur[mi]);
-                if constexpr (phase == 2) Mat<T>::template sparse<1>(a_cur[mi], bfc[1][j], acc[m][j], i_cur[mi]);
-                if constexpr (phase == 3) Mat<T>::template sparse<0>(a_cur[mi], bfe[0][j], acc[m][j], i_cur[mi]);
-                if constexpr (phase == 4) Mat<T>::template sparse<1>(a_cur[mi], bfe[1][j], acc[m][j], i_cur[mi]);
-                if constexpr (i == 2 && 2 * u < COPY_SLOTS) issue_copy_slot(2 * u, copy_stage, gpar ^ 1);
-                if constexpr (i == 2 + TN && 2 * u + 1 < COPY_SLOTS) issue_copy_slot(2 * u + 1, copy_stage, gpar ^ 1);
-                if constexpr (i == 0) {  // issue the next unit's LDS reads behind the first matrix instruction
-                    if constexpr (u + 1 < 20) {
-                        constexpr int np = (u + 1) / 4, nm0 = ((u + 1) % 4) * 2;
-                        constexpr int nstep = np == 0 ? 4 : np - 1;
-#pragma unroll
-                        for (int t = 0; t < 2; ++t) {
-                            a_nxt[t] = *(const u32x4*)(A + (nm0 + t) * kTileBytes + nstep * kFragBytes);
-                            if constexpr (np > 0) i_nxt[t] = *(const int*)(AI + (nm0 + t) * kTileBytes + ((np - 1) >> 1) * 256);
-                        }
-                    }
-                    if constexpr (job_read >= 0) raw_load(X, rr[job_read], job_read % TN, job_read / TN);
-                    if constexpr (u == 19) {
-                        asm volatile("" ::: "memory");
-                        __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0): copies landed, reads of this region done
-                        __builtin_amdgcn_s_barrier();
-                        asm volatile("" ::: "memory");
-                        load_stage_prologue(gpar ^ 1);
-                    }
-                }
-                // this instruction's share of the unit's 16 * perm_count permutes
-                constexpr int o_begin = i * 16 * perm_count / UNIT, o_end = (i + 1) * 16 * perm_count / UNIT;
-                static_for<o_end - o_begin>([&](auto O) {
-                    constexpr int o = o_begin + decltype(O)::value;
-                    constexpr int q = perm_first + o / 16, oo = o % 16;
-                    const uint32_t v = transposed(rr[q], oo);
-                    if constexpr (q < TN) bfc[oo >> 3][q][oo & 7] = v;
-                    else bfe[oo >> 3][q - TN][oo & 7] = v;
-                });
-                __builtin_amdgcn_sched_barrier(0);
-            });
-            if constexpr (u + 1 < 20) {
-#pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    a_cur[t] = a_nxt[t];
-                    i_cur[t] = i_nxt[t];
-                }
-            }
-        });
-        gpar ^= 1;
-    };
-    run_stage(std::true_type{}, 0);
-    for (int stage = 1; stage < stages; ++stage) run_stage(std::false_type{}, stage);
-
-    // the last matrix instructions must have written their accumulators before anything reads them
-    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
-    // ---- epilogue ----
-    // Per lane and group of 4 channel tiles the accumulators hold 16 consecutive output channels of one
-    // position (tile_row_channel).  16-bit outputs without a fused output stage are stored directly:
-    // 32 contiguous bytes per lane, 128 per position and group.  Otherwise each wave transposes its
-    // 64 positions x 16*TM channels through its own slice of the region that was multiplied last
-    // (free now; the other region is receiving the next tile's first stage) and writes whole
-    // channel rows, 16 bytes per lane; fp32 output goes in two halves of the channel tiles.
-    {
-        constexpr int EB = (int)sizeof(TO);
-        constexpr int HALVES = EB == 4 ? 2 : 1;
-        constexpr int TMH = TM / HALVES;
-        static_assert(TM % HALVES == 0 && TMH % 4 == 0, "each half is whole groups of 4 channel tiles (tile_row_channel)");
-        constexpr int ROW = TMH * 16 * EB + (EB == 2 ? 8 : 16);  // padded row pitch: spreads the banks
-        // position blocks staged together: as many as fit when the four waves share one region
-        constexpr int JG = (REGION / (4 * 16 * ROW)) < TN ? (REGION / (4 * 16 * ROW)) : TN;
-        static_assert(JG >= 1, "epilogue staging must fit in one region");
-        char* stage_out = smem + (gpar ^ 1) * REGION + wave * (16 * JG * ROW);
-        // lane-derived addresses of the epilogue are recomputed per tile (opaque copy of the lane id)
-        // instead of staying live in registers through the K loop
-        int lane_e = lane;
-        asm volatile("" : "+v"(lane_e));
-        const int nn_e = lane_e & 15, qq_e = lane_e >> 4;
-        // 64-bit address of the tile's first output element once; everything else is 32-bit
-        const int64_t pos_tile = ((int64_t)t_n * Ho + t_oh0) * Wo + t_ow0;  // position number of the tile's first output
-        TO* const y_tile = y + pos_tile * ep.ldy;
-        const float relu_floor = ep.act == 1 ? 0.f : -__builtin_inff();
-        if constexpr (kDirectEpilogue && EB == 2 && !FUSED) {
-            // straight from the accumulators: 16 consecutive channels (32 bytes) per lane and group of 4 tiles
-            const int pr_e = nn_e >> 2, pc_e = nn_e & 3;
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int blk = blk0 + j;
-                const int dr = 4 * (blk / CT) + pr_e, dc = 4 * (blk % CT) + pc_e;
-                const bool inside = t_oh0 + dr < Ho && t_ow0 + dc < Wo;
-                TO* yp = y_tile + (dr * Wo + dc) * ep.ldy + 16 * t_mt0 + 16 * qq_e;
-#pragma unroll
-                for (int mg = 0; mg < TM; mg += 4) {
-                    uint32_t o[8];
-#pragma unroll
-                    for (int m = 0; m < 4; ++m) {
-                        float r[4];
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) asm("v_max_f32 %0, %1, %2" : "=v"(r[e]) : "v"(acc[mg + m][j][e]), "v"(relu_floor));
-                        o[2 * m] = pack2_from_f32<TO>(r[0], r[1]);
-                        o[2 * m + 1] = pack2_from_f32<TO>(r[2], r[3]);
-                    }
-                    if (inside && 16 * (t_mt0 + mg) + 16 * qq_e < Co) {
-                        *(u32x4*)(yp + 16 * mg) = u32x4{o[0], o[1], o[2], o[3]};
-                        *(u32x4*)(yp + 16 * mg + 8) = u32x4{o[4], o[5], o[6], o[7]};
-                    }
-                }
-            }
-        } else {
-#pragma unroll
-        for (int h = 0; h < HALVES; ++h) {
-#pragma unroll
-          for (int j0 = 0; j0 < TN; j0 += JG) {
-            const int jn = j0 + JG <= TN ? JG : TN - j0;  // blocks in this group
-#pragma unroll
-            for (int jj = 0; jj < jn; ++jj) {
-                const int j = j0 + jj;
-                f32x4 vals[TMH];
-#pragma unroll
-                for (int mm = 0; mm < TMH; ++mm) vals[mm] = acc[h * TMH + mm][j];
-                // fused ReLU without a branch: max with 0, or with -inf when ReLU is off (one v_max_f32 per
-                // value, written as asm so that no NaN-quieting pass is put in front of it)
-                if constexpr (FUSED) {
-                    // this lane's position in block j and its 4 consecutive channels of every channel tile
-                    const int blk_f = blk0 + j;
-                    const int dr_f = 4 * (blk_f / CT) + (nn_e >> 2), dc_f = 4 * (blk_f % CT) + (nn_e & 3);
-                    const bool inside_f = t_oh0 + dr_f < Ho && t_ow0 + dc_f < Wo;
-                    const int64_t pos_f = pos_tile + dr_f * Wo + dc_f;
-#pragma unroll
-                    for (int mm = 0; mm < TMH; ++mm) {
-                        const int co4 = 16 * (t_mt0 + h * TMH) + tile_quarter_offset(mm, qq_e);
-                        if (inside_f && co4 < Co) {
-                            float vv[4] = {vals[mm].x, vals[mm].y, vals[mm].z, vals[mm].w};
-                            epi_scale_bias_act<4>(vv, ep, co4);
-                            epi_residual<TO, 4>(vv, ep, pos_f, co4);
-                            vals[mm] = f32x4{vv[0], vv[1], vv[2], vv[3]};
-                        }
-                    }
-                } else {
-#pragma unroll
-                    for (int mm = 0; mm < TMH; ++mm)
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            float r;
-                            asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(vals[mm][e]), "v"(relu_floor));
-                            vals[mm][e] = r;
-                        }
-                }
-#pragma unroll
-                for (int mm = 0; mm < TMH; ++mm) {
-                    char* dst = stage_out + (jj * 16 + nn_e) * ROW + tile_quarter_offset(mm, qq_e) * EB;
-                    if constexpr (EB == 4) {
-                        *(f32x4*)dst = vals[mm];
-                    } else {
-                        uint2 o;
-                        o.x = pack2_from_f32<TO>(vals[mm].x, vals[mm].y);
-                        o.y = pack2_from_f32<TO>(vals[mm].z, vals[mm].w);
-                        *(uint2*)dst = o;
-                    }
-                }
-            }
-            // read back: a row of 16*TMH channels is CH 16-byte chunks; 64 lanes cover 64/CH positions per pass.
-            // (A wave's LDS accesses execute in order, so the next group's writes to this slice cannot pass
-            // these reads.)
-            constexpr int CH = TMH * 16 * EB / 16;
-            static_assert(64 % CH == 0, "row chunks must tile the wave");
-            constexpr int POS_PER_PASS = 64 / CH;
-            static_assert(POS_PER_PASS <= 4 || POS_PER_PASS % 4 == 0, "a pass covers whole rows of a 4x4 block");
-            const int passes = (16 * jn) / POS_PER_PASS;
-            const int co_first = 16 * (t_mt0 + h * TMH);
-            const int sub = lane_e / CH, chunk = lane_e % CH;  // position within the pass, chunk within the row
-            const int co = co_first + chunk * (16 / EB);
-#pragma unroll
-            for (int ps = 0; ps < passes; ++ps) {
-                const int p = ps * POS_PER_PASS + sub;
-                const int jj = p >> 4, n = p & 15;
-                const int blk = blk0 + j0 + jj;
-                const int dr = 4 * (blk / CT) + (n >> 2), dc = 4 * (blk % CT) + (n & 3);
-                const u32x4 v = *(const u32x4*)(stage_out + p * ROW + chunk * 16);
-                if (t_oh0 + dr < Ho && t_ow0 + dc < Wo && co < Co)  // Co is a multiple of 16: a chunk is all in or all out
-                    *(u32x4*)(y_tile + (dr * Wo + dc) * ep.ldy + co) = v;
-            }
-          }
-        }
-        }
-    }
-    if (!has_next) break;
-    work = next_work;
-    // staging slices are read (LDS only): the region may be overwritten by the next copies.  A bare
-    // barrier, because __syncthreads() carries a fence that would wait here for this tile's output
-    // stores to drain; they drain behind the next tile's first stage instead.  (The direct epilogue
-    // does not touch LDS: nothing to wait for.)
-    if constexpr (!(kDirectEpilogue && sizeof(TO) == 2 && !FUSED)) {
-        asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0) only
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
-    }
-  }
-}
-
-inline bool needs_fused_stage(const ConvParams& c) { return c.ep.scale || c.ep.bias || c.ep.residual || c.ep.act > 1; }
-
-template <typename T, typename TO, int S, int TM, int TN, int RT, int CT, bool FUSED>
-rtoss_status launch_variant_f(const rtoss_wdesc& d, const ConvParams& c, const char* wfrag, const void* x, void* y,
-                            hipStream_t s)
-{
-    using G = Geom<S, RT, CT>;
-    const int Ho = (c.H + 2 - 3) / S + 1, Wo = (c.W + 2 - 3) / S + 1;
-    const int tiles_r = (Ho + G::TH - 1) / G::TH, tiles_c = (Wo + G::TW - 1) / G::TW;
-    const int m_tiles_total = padded_m_tiles(d.Co);  // pitch of the packed section
-    const int co_blocks = ((d.Co + 15) / 16 + TM - 1) / TM;
-    constexpr int x_copies_per_wave = ((G::x_bytes / 16 + 63) / 64 + 3) / 4;
-    const size_t smem = 2 * ((size_t)TM * kTileBytes + (size_t)x_copies_per_wave * 4096);
-    auto kern = conv3x3_sparse_kernel<T, TO, S, TM, TN, RT, CT, FUSED>;
-    static LaunchOnce lds_once;  // per instantiation
-    if (rtoss_status st = ensure_dynamic_lds((const void*)kern, smem, lds_once, "conv3x3 shared memory attribute")) return st;
-    const int64_t total = (int64_t)tiles_r * tiles_c * co_blocks * c.N;
-    if (total > 0x3fffffff) return fail(RTOSS_ESHAPE, "conv: too many tiles");
-    if ((int64_t)c.N * c.H * c.W * d.Ci / 8 > 0x7fffffff) return fail(RTOSS_ESHAPE, "conv: input too large for 32-bit chunk offsets");
-    const int work_per_xcd = (int)((total + 7) / 8);
-    // one workgroup per compute unit (a workgroup owns nearly all of a unit's LDS), at most one per work item
-    DeviceInfo dev;
-    if (rtoss_status st = current_device(&dev)) return st;
-    const int slots_per_xcd = std::max(1, std::min(work_per_xcd, std::max(8, dev.cus) / 8));
-    dim3 grid((unsigned)(slots_per_xcd * 8)), block(256);
-    const char* zeros = wfrag + fragment_bytes(d);
-    kern<<<grid, block, smem, s>>>((const T*)x, (TO*)y, wfrag, zeros, c.H, c.W, d.Ci, d.Co, Ho, Wo, m_tiles_total,
-                                   tiles_c, tiles_r * tiles_c, co_blocks, (int)total, work_per_xcd, c.ep);
-    return check_hip(hipGetLastError(), "conv3x3 sparse launch");
-}
-
-template <typename T, typename TO, int S, int TM, int TN, int RT, int CT>
-rtoss_status launch_variant(const rtoss_wdesc& d, const ConvParams& c, const char* wfrag, const void* x, void* y,
-                            hipStream_t s)
-{
-    if constexpr (TN == 4) {  // (the fused output stage is instantiated for the 16x16 tile only)
-        if (needs_fused_stage(c)) return launch_variant_f<T, TO, S, TM, TN, RT, CT, true>(d, c, wfrag, x, y, s);
-    }
-    return launch_variant_f<T, TO, S, TM, TN, RT, CT, false>(d, c, wfrag, x, y, s);
-}
-
 template <typename T, typename TO, int S, int TM, int TN, int RT, int CT, bool AHEAD = true>
 rtoss_status launch_variant_sb(const rtoss_wdesc& d, const ConvParams& c, const char* wfrag, const void* x, void* y,
                             hipStream_t s)
@@ -967,6 +453,15 @@ rtoss_status launch_variant_sb(const rtoss_wdesc& d, const ConvParams& c, const 
     return check_hip(hipGetLastError(), "conv3x3 sparse launch");
 }
 
+// Large stride-1 layers (more than 64 channels in and out, enough 16x16 x 128-channel tiles to give most
+// compute units one) take the pipelined kernel of conv3x3_rows.hip.
+inline bool takes_pipelined_kernel(const rtoss_wdesc& d, const ConvParams& c)
+{
+    if (c.stride != 1 || d.Co <= 64 || d.Ci <= 64) return false;
+    const int64_t tiles8 = (int64_t)((c.H + 15) / 16) * ((c.W + 15) / 16) * c.N * (((d.Co + 15) / 16 + 7) / 8);
+    return tiles8 >= 200;
+}
+
 template <typename T, typename TO>
 rtoss_status launch_typed(const rtoss_wdesc& d, const ConvParams& c, const char* wfrag, const void* x, void* y,
                           hipStream_t s)
@@ -983,22 +478,8 @@ rtoss_status launch_typed(const rtoss_wdesc& d, const ConvParams& c, const char*
         if (d.Ci <= 64) return launch_variant_sb<T, TO, 1, 4, 2, 2, 4, false>(d, c, wfrag, x, y, s);
         if (small) return launch_variant_sb<T, TO, 1, 4, 2, 2, 4>(d, c, wfrag, x, y, s);
         // ... and so do launches that would leave compute units idle with 128 channels per workgroup
-        const int64_t tiles8 = (int64_t)((c.H + 15) / 16) * ((c.W + 15) / 16) * c.N * (((d.Co + 15) / 16 + 7) / 8);
-        if (tiles8 < 200) return launch_variant_sb<T, TO, 1, 4, 2, 2, 4>(d, c, wfrag, x, y, s);
-        // Two tile shapes: 16x16 positions, or 20 rows x 16 columns (5 position blocks per wave: better
-        // reuse of the weight fragments, and for some images fewer rounds over the compute units or less
-        // padding).  Cost model: rounds of the busiest workgroup x relative cost of a tile.
-        const int Ho = c.H, Wo = c.W;
-        const int64_t co_blocks = ((d.Co + 15) / 16 + 7) / 8;
-        const int64_t t4 = (int64_t)((Ho + 15) / 16) * ((Wo + 15) / 16) * co_blocks * c.N;
-        const int64_t t5 = (int64_t)((Ho + 19) / 20) * ((Wo + 15) / 16) * co_blocks * c.N;
-        DeviceInfo dev;
-        if (rtoss_status st = current_device(&dev)) return st;
-        const int64_t slots = std::max(8, dev.cus) / 8 * 8;  // persistent workgroups of the pipelined kernel
-        const double cost4 = (double)((t4 + slots - 1) / slots) * 4.0, cost5 = (double)((t5 + slots - 1) / slots) * 4.85;
-        // (with few stages per tile the taller tile's longer prologue and epilogue outweigh the saved round)
-        if (cost5 < cost4 && d.Ci >= 128 && !needs_fused_stage(c)) return launch_variant<T, TO, 1, 8, 5, 5, 4>(d, c, wfrag, x, y, s);
-        return launch_variant<T, TO, 1, 8, 4, 4, 4>(d, c, wfrag, x, y, s);
+        if (!takes_pipelined_kernel(d, c)) return launch_variant_sb<T, TO, 1, 4, 2, 2, 4>(d, c, wfrag, x, y, s);
+        return launch_variant_sb<T, TO, 1, 4, 2, 2, 4>(d, c, wfrag, x, y, s);  // (not reached: see takes_pipelined_kernel)
     }
     // Stride 2: the input tile of a 16x16 output tile (33x33 positions) nearly fills the LDS by itself.
     // Half-height tiles (8x16 outputs, 17x33 inputs) with 64 channels per workgroup need 72 KB, so two
@@ -1084,6 +565,7 @@ rtoss_status launch_pack_sparse3x3_batch(const PackItem* items, int n, const Dic
 rtoss_status launch_conv3x3_sparse(const rtoss_wdesc& d, const ConvParams& c, const void* section, const void* x,
                                    void* y, hipStream_t s)
 {
+    if (takes_pipelined_kernel(d, c)) return launch_conv3x3_rows(d, c, section, x, y, s);
     const char* wf = (const char*)section;
     const bool f32out = c.out_dt == RTOSS_F32;
     if (d.dt == RTOSS_F16)

@@ -42,20 +42,36 @@ typedef __bf16 b16 __attribute__((ext_vector_type(16)));
 // front of the next matrix instruction.)
 // MatV is the same with the accumulator in the vector registers: kernels with registers to spare keep
 // it there and spare themselves the (equally slow) v_accvgpr_read of the epilogue.
+// Hazard the compiler cannot see.  A kernel that needs more than 256 vector registers gets its surplus parked
+// in the accumulation registers by the register allocator, which brings a value back with v_accvgpr_read right
+// in front of its use.  That move runs through the matrix pipeline, and a matrix instruction that reads its
+// result in the next cycles gets the old register contents (seen on the device: wrong sums in exactly the
+// accumulator whose operand had been brought back).  The compiler spaces such pairs for instructions it
+// knows, not for asm statements.  The build therefore scans the generated code of every kernel for such a
+// move close in front of an asm matrix instruction (build.py: check_matrix_hazards) and fails if there is
+// one; the kernels are written so that nothing is parked across their matrix loops.  A translation unit
+// that cannot be kept clean otherwise may define RTOSS_MFMA_SETTLE, which puts two idle cycles in front of
+// every matrix instruction (expensive: a single resident wave per SIMD issues one instruction per 4 cycles,
+// so that is 4 cycles per matrix instruction, 15 % on the 256-channel layers).
+#ifdef RTOSS_MFMA_SETTLE
+#define RTOSS_SETTLE "s_nop 1\n\t"
+#else
+#define RTOSS_SETTLE ""
+#endif
 #define RTOSS_MAT_STRUCT(NAME, T, SFX, RW, WO)                                                                        \
     template <> struct NAME<T> {                                                                                      \
         static __device__ __forceinline__ void dense(u32x4 a, u32x4 b, f32x4& c)                                      \
         {                                                                                                             \
-            asm volatile("v_mfma_f32_16x16x32_" SFX " %0, %1, %2, %0" : RW(c) : "v"(a), "v"(b));                      \
+            asm volatile(RTOSS_SETTLE "v_mfma_f32_16x16x32_" SFX " %0, %1, %2, %0" : RW(c) : "v"(a), "v"(b));                      \
         }                                                                                                             \
         static __device__ __forceinline__ void dense_first(u32x4 a, u32x4 b, f32x4& c)                                \
         {                                                                                                             \
-            asm volatile("v_mfma_f32_16x16x32_" SFX " %0, %1, %2, 0" : WO(c) : "v"(a), "v"(b));                       \
+            asm volatile(RTOSS_SETTLE "v_mfma_f32_16x16x32_" SFX " %0, %1, %2, 0" : WO(c) : "v"(a), "v"(b));                       \
         }                                                                                                             \
         template <int ABID> static __device__ __forceinline__ void sparse(u32x4 a, u32x8 b, f32x4& c, int idx)        \
         {                                                                                                             \
-            if (ABID == 0) asm volatile("v_smfmac_f32_16x16x64_" SFX " %0, %1, %2, %3" : RW(c) : "v"(a), "v"(b), "v"(idx)); \
-            else asm volatile("v_smfmac_f32_16x16x64_" SFX " %0, %1, %2, %3 abid:1" : RW(c) : "v"(a), "v"(b), "v"(idx));    \
+            if (ABID == 0) asm volatile(RTOSS_SETTLE "v_smfmac_f32_16x16x64_" SFX " %0, %1, %2, %3" : RW(c) : "v"(a), "v"(b), "v"(idx)); \
+            else asm volatile(RTOSS_SETTLE "v_smfmac_f32_16x16x64_" SFX " %0, %1, %2, %3 abid:1" : RW(c) : "v"(a), "v"(b), "v"(idx));    \
         }                                                                                                             \
     };
 template <typename T> struct Mat;
@@ -65,6 +81,7 @@ RTOSS_MAT_STRUCT(Mat, bf16_t, "bf16", "+a", "=a")
 RTOSS_MAT_STRUCT(MatV, f16_t, "f16", "+v", "=v")
 RTOSS_MAT_STRUCT(MatV, bf16_t, "bf16", "+v", "=v")
 #undef RTOSS_MAT_STRUCT
+#undef RTOSS_SETTLE
 
 // Dense step D = A * B + C over one 16-byte operand per lane, accumulator wherever the compiler keeps it
 // (the compiler-scheduled kernels): 32 channels of a 16-bit type in one instruction, or 16 fp32 channels
