@@ -155,10 +155,10 @@ rtoss_status blob_geometry(const rtoss_wdesc* d, const Dict& dict, BlobGeometry*
     g->format = kFormatNone;
     g->mat_off = 0;
     g->mat_bytes = 0;
-    if (sparse3x3_shape_ok(*d) && sparse3x3_dictionary_ok(dict)) {
+    if (sparse3x3_shape_ok(*d) && sparse3x3_layout(dict) >= 0) {
         g->format = kFormatSparse24;
         g->mat_off = end;
-        g->mat_bytes = sparse3x3_section_bytes(*d);
+        g->mat_bytes = sparse3x3_section_bytes(*d, sparse3x3_layout(dict));
         end = align_up(end + g->mat_bytes, 256);
     } else if (stem3x3_shape_ok(*d)) {
         g->format = kFormatStem;
@@ -444,7 +444,7 @@ static rtoss_status conv_impl(const rtoss_wdesc* desc, const rtoss_cdesc* c, con
         return launch_conv_direct(*desc, cp, dict, blob + g.live_off, (const uint8_t*)(blob + g.idx_off), x_dev, y_dev,
                                   (hipStream_t)hip_stream);
     if (g.format == kFormatSparse24)
-        return launch_conv3x3_sparse(*desc, cp, blob + g.mat_off, x_dev, y_dev, (hipStream_t)hip_stream);
+        return launch_conv3x3_sparse(*desc, cp, sparse3x3_layout(dict), blob + g.mat_off, x_dev, y_dev, (hipStream_t)hip_stream);
     if (g.format == kFormatStem)
         return launch_conv3x3_stem(*desc, cp, blob + g.mat_off, x_dev, y_dev, (hipStream_t)hip_stream);
     if (g.format == kFormatDense3x3)

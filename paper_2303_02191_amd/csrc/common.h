@@ -116,12 +116,13 @@ rtoss_status launch_pack_sparse3x3_batch(const PackItem* items, int n, const Dic
 rtoss_status launch_pack_stream1x1_batch(const PackItem* items, int n, const Dict& dict, hipStream_t s);
 
 // 3x3 convolution on the sparse matrix instruction (conv3x3_sparse.hip)
-bool sparse3x3_dictionary_ok(const Dict& dict);
+// which tap layout (sparse_frag.h) fits every pattern of the dictionary, cheapest first; -1: none
+int sparse3x3_layout(const Dict& dict);
 bool sparse3x3_shape_ok(const rtoss_wdesc& d);
-size_t sparse3x3_section_bytes(const rtoss_wdesc& d);
+size_t sparse3x3_section_bytes(const rtoss_wdesc& d, int layout);
 rtoss_status launch_pack_sparse3x3(const rtoss_wdesc& d, const void* w, const uint8_t* idx, const Dict& dict,
                                    void* section, void* live_values, uint8_t* live_idx, hipStream_t s);
-rtoss_status launch_conv3x3_sparse(const rtoss_wdesc& d, const ConvParams& c, const void* section, const void* x,
+rtoss_status launch_conv3x3_sparse(const rtoss_wdesc& d, const ConvParams& c, int layout, const void* section, const void* x,
                                    void* y, hipStream_t s);
 
 // ... large stride-1 layers: pipelined kernel over strips of output rows (conv3x3_rows.hip); same packed section

@@ -49,12 +49,6 @@ namespace rtoss {
 
 namespace {
 
-__device__ __forceinline__ int tap_of_slot(int group, int f)
-{
-    // group 0: corners {0,2,6,8}; group 1: edge midpoints {1,3,5,7}
-    return group == 0 ? ((f & 1) * 2 + (f >> 1) * 6) : (f == 0 ? 1 : f == 1 ? 3 : f == 2 ? 5 : 7);
-}
-
 // Input channel (within a 32-channel stage) that pair g of lane-quarter q refers to in
 // sparse step `half`.
 __device__ __forceinline__ int stage_channel(int q, int g, int half)
@@ -67,22 +61,23 @@ struct SparsePackArgs {
     const uint8_t* idx;
     char* out;
     int Co, Ci, m_tiles, zero_items;
-    int64_t total_items;
+    int64_t total_items;  // 64 * fragments per tile * tiles
     LiveJob job;
 };
 
 // One workgroup of one layer (`block` counts from the layer's first block): the first blocks write the
 // public section, then comes one block per (stage, channel tile) and last the block of zeros.
 // A tile's 16 x 32 kernels (16 rows of 576 contiguous bytes) and their pattern indices are staged in LDS with
-// coalesced 16-byte loads; the 5 x 64 fragment pieces are then assembled from LDS.
+// coalesced 16-byte loads; the fragment pieces (64 per fragment) are then assembled from LDS.
 template <typename T>
-__device__ __forceinline__ void pack_sparse3x3_body(const SparsePackArgs& a, const Dict& dict, int block)
+__device__ __forceinline__ void pack_sparse3x3_body(const SparsePackArgs& a, const TapLayout& lay, const Dict& dict, int block)
 {
     const T* __restrict__ w = (const T*)a.w;
     const uint8_t* __restrict__ idx = a.idx;
     char* __restrict__ out = a.out;
     const int Co = a.Co, Ci = a.Ci, m_tiles = a.m_tiles, zero_items = a.zero_items;
     const LiveJob job = a.job;
+    const int frags = layout_fragments(lay), tile_bytes = layout_tile_bytes(lay);
     __shared__ uint16_t masks[256];
     __shared__ __attribute__((aligned(16))) uint16_t wl[16][32 * 9];  // [row][channel][tap]
     __shared__ __attribute__((aligned(16))) uint8_t il[16][32];       // [row][channel]
@@ -92,11 +87,11 @@ __device__ __forceinline__ void pack_sparse3x3_body(const SparsePackArgs& a, con
         pack_live_block<T>(w, idx, masks, dict.k, job, block);
         return;
     }
-    const int n_tiles = (int)(a.total_items / 320);
+    const int n_tiles = (int)(a.total_items / (64 * frags));
     const int tile = block - job.blocks;  // stage * m_tiles + m_tile
     if (tile >= n_tiles) {  // the blocks behind the fragments write the block of zeros, 16 bytes per lane
         const int item = (tile - n_tiles) * 256 + (int)threadIdx.x;
-        if (item < zero_items) *(u32x4*)(out + (size_t)n_tiles * kTileBytes + (size_t)item * 16) = u32x4{0, 0, 0, 0};
+        if (item < zero_items) *(u32x4*)(out + (size_t)n_tiles * tile_bytes + (size_t)item * 16) = u32x4{0, 0, 0, 0};
         return;
     }
     const int mt = tile % m_tiles, cb = tile / m_tiles;
@@ -132,14 +127,14 @@ __device__ __forceinline__ void pack_sparse3x3_body(const SparsePackArgs& a, con
         }
     }
     __syncthreads();
-    // ---- assemble: item = (step 0..4, lane); 320 items, the last 64 by the first wave in a second pass ----
-    char* tile_out = out + (size_t)tile * kTileBytes;
-    for (int item = threadIdx.x; item < 320; item += 256) {
+    // ---- assemble: item = (fragment, lane) ----
+    char* tile_out = out + (size_t)tile * tile_bytes;
+    for (int item = threadIdx.x; item < 64 * frags; item += 256) {
         const int lane = item % 64, step = item / 64;
         const int r = lane % 16, q = lane / 16;
         const bool row_live = tile_row_channel(mt, r) < Co;
         uint16_t vals[8];
-        if (step == 4) {  // dense centre tap: K = 8q + j
+        if (step == 2 * lay.groups) {  // dense centre tap: K = 8q + j
             for (int j = 0; j < 8; ++j) {
                 const int c = 8 * q + j;
                 vals[j] = (row_live && ((masks[il[r][c]] >> 4) & 1u)) ? wl[r][c * 9 + 4] : (uint16_t)0;
@@ -155,8 +150,8 @@ __device__ __forceinline__ void pack_sparse3x3_body(const SparsePackArgs& a, con
                     const unsigned m = masks[il[r][c]];
                     int n = 0;
                     for (int sl = 0; sl < 4; ++sl) {
-                        const int t = tap_of_slot(group, sl);
-                        if (((m >> t) & 1u) && n < 2) {
+                        const int t = lay.tap[group][sl];
+                        if (t >= 0 && ((m >> t) & 1u) && n < 2) {
                             v[n] = wl[r][c * 9 + t];
                             f[n] = sl;
                             ++n;
@@ -168,7 +163,7 @@ __device__ __forceinline__ void pack_sparse3x3_body(const SparsePackArgs& a, con
                 vals[2 * g + 1] = v[1];
                 fields |= (unsigned)(f[0] | (f[1] << 2)) << (4 * g);
             }
-            uint16_t* ip = (uint16_t*)(tile_out + 5 * kFragBytes + (group * 64 + lane) * 4 + half * 2);
+            uint16_t* ip = (uint16_t*)(tile_out + frags * kFragBytes + (group * 64 + lane) * 4 + half * 2);
             *ip = (uint16_t)fields;
         }
         u32x4 pk;
@@ -181,22 +176,23 @@ __device__ __forceinline__ void pack_sparse3x3_body(const SparsePackArgs& a, con
 }
 
 template <typename T>
-__global__ __launch_bounds__(256) void pack_sparse3x3_kernel(SparsePackArgs a, Dict dict)
+__global__ __launch_bounds__(256) void pack_sparse3x3_kernel(SparsePackArgs a, TapLayout lay, Dict dict)
 {
-    pack_sparse3x3_body<T>(a, dict, (int)blockIdx.x);
+    pack_sparse3x3_body<T>(a, lay, dict, (int)blockIdx.x);
 }
 
 struct SparsePackBatch {
     SparsePackArgs a[kPackBatchMax];
     int first_block[kPackBatchMax + 1];
     int n;
+    TapLayout layout;  // (one dictionary per batch: one layout)
 };
 
 template <typename T>
 __global__ __launch_bounds__(256) void pack_sparse3x3_batch_kernel(SparsePackBatch b, Dict dict)
 {
     const int t = batch_entry(b, (int)blockIdx.x);  // block-uniform
-    pack_sparse3x3_body<T>(b.a[t], dict, (int)blockIdx.x - b.first_block[t]);
+    pack_sparse3x3_body<T>(b.a[t], b.layout, dict, (int)blockIdx.x - b.first_block[t]);
 }
 
 // Single-buffered variant: one LDS buffer, two barriers per stage, plain loop nest scheduled by the
@@ -204,7 +200,9 @@ __global__ __launch_bounds__(256) void pack_sparse3x3_batch_kernel(SparsePackBat
 // workgroups share a compute unit and hide each other's copy latency and epilogue.  Used for stride 2
 // (whose activation tile is too large to keep twice in LDS) and for layers too small for the
 // pipelined kernel's 128-channel, 8-stage appetite: TM = 4 covers 64 output channels per workgroup.
-template <typename T, typename TO, int S, int TM, int TN, int RT, int CT, bool AHEAD>
+// LAY: tap layout (sparse_frag.h).  Layout 1 (4-entry dictionaries) has three tap groups and no dense centre
+// step; it always takes the one-group-at-a-time schedule.
+template <typename T, typename TO, int S, int TM, int TN, int RT, int CT, bool AHEAD, int LAY = 0>
 __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restrict__ x, TO* __restrict__ y,
                                                                 const char* __restrict__ wfrag,
                                                                 const char* __restrict__ zeros, int H, int W, int Ci,
@@ -214,7 +212,9 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
 {
     using G = Geom<S, RT, CT>;
     static_assert(RT * CT == 4 * TN, "four waves share the position blocks of a workgroup");
-    constexpr int A_BYTES = TM * kTileBytes;
+    constexpr TapLayout LY = kLayouts[LAY];
+    constexpr int NG = LY.groups, FR = layout_fragments(LY), TILE = layout_tile_bytes(LY);
+    constexpr int A_BYTES = TM * TILE;
     constexpr int A_WAVE_COPIES = A_BYTES / 1024;            // 64 lanes x 16 B per copy instruction
     constexpr int A_PER_WAVE = (A_WAVE_COPIES + 3) / 4;
     constexpr int X_CHUNKS = G::x_bytes / 16;                // including the pad chunk of every position
@@ -254,8 +254,8 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
         const int off = ((n_img * H + ih) * W + iw) * (Ci >> 3) + q;
         x_ptr[k] = inside ? (const char*)x + (int64_t)off * 16 : zeros;
     }
-    const char* a_src = wfrag + (int64_t)mt0 * kTileBytes + lane * 16;
-    const int64_t a_stage_stride = (int64_t)m_tiles_total * kTileBytes;
+    const char* a_src = wfrag + (int64_t)mt0 * TILE + lane * 16;
+    const int64_t a_stage_stride = (int64_t)m_tiles_total * TILE;
 
     // ---- per-lane read addresses of the B operand ----
     const int nn = lane & 15, qq = lane >> 4;
@@ -289,20 +289,21 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
         // This hides the LDS latency inside a workgroup; shallow layers over large images, which live on
         // hiding HBM latency across workgroups, do better without it and with the registers it costs.
         u32x4 bc[TN], ac[TM];
-        u32x4 rr[2][TN][4], as[2][TM][2];
-        int iw2[2][TM];
+        u32x4 rr[NG][TN][4], as[NG][TM][2];
+        int iw2[NG][TM];
         auto load_group_x = [&](int group) {
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
                 for (int f = 0; f < 4; ++f) {
-                    const int t = group == 0 ? ((f & 1) * 2 + (f >> 1) * 6) : (2 * f + 1);
+                    // (an empty slot carries weight 0: it reads the group's first tap, any finite value does)
+                    const int t = LY.tap[group][f] >= 0 ? LY.tap[group][f] : LY.tap[group][0];
                     rr[group][j][f] = *(const u32x4*)(lds_x + xb[j] + ((t / 3) * G::LW + (t % 3)) * G::kPos);
                 }
         };
         auto load_group_a = [&](int group, int m) {
-            const char* at = lds_a + m * kTileBytes;
-            iw2[group][m] = *(const int*)(at + 5 * kFragBytes + (group * 64 + lane) * 4);
+            const char* at = lds_a + m * TILE;
+            iw2[group][m] = *(const int*)(at + FR * kFragBytes + (group * 64 + lane) * 4);
             as[group][m][0] = *(const u32x4*)(at + (group * 2 + 0) * kFragBytes + lane * 16);
             as[group][m][1] = *(const u32x4*)(at + (group * 2 + 1) * kFragBytes + lane * 16);
         };
@@ -352,7 +353,7 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
 #pragma unroll
             for (int j = 0; j < TN; ++j) bc[j] = *(const u32x4*)(lds_x + xb[j] + (G::LW + 1) * G::kPos);
 #pragma unroll
-            for (int m = 0; m < TM; ++m) ac[m] = *(const u32x4*)(lds_a + m * kTileBytes + 4 * kFragBytes + lane * 16);
+            for (int m = 0; m < TM; ++m) ac[m] = *(const u32x4*)(lds_a + m * TILE + 2 * NG * kFragBytes + lane * 16);
         };
         auto run_centre = [&]() {  // centre tap: dense step over the 32 channels of the stage
 #pragma unroll
@@ -363,7 +364,7 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
                     else MatV<T>::dense(ac[m], bc[j], acc[m][j]);
                 }
         };
-        if constexpr (AHEAD) {
+        if constexpr (AHEAD && LAY == 0) {
             load_centre();
             load_group(0);
             run_centre();
@@ -371,10 +372,17 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
             run_group(0);
             run_group(1);
         } else {  // few operands live at a time: fewer registers, one more workgroup per compute unit
-            load_centre();
-            run_centre();
+            if constexpr (LY.centre) {
+                load_centre();
+                run_centre();
+            } else if constexpr (FIRST) {  // (no dense step that could write the first product: clear)
 #pragma unroll
-            for (int group = 0; group < 2; ++group) {
+                for (int m = 0; m < TM; ++m)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) acc[m][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+            for (int group = 0; group < NG; ++group) {
                 load_group_x(group);
                 permute_group(group);
 #pragma unroll
@@ -429,7 +437,7 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
     }
 }
 
-template <typename T, typename TO, int S, int TM, int TN, int RT, int CT, bool AHEAD = true>
+template <typename T, typename TO, int S, int TM, int TN, int RT, int CT, bool AHEAD = true, int LAY = 0>
 rtoss_status launch_variant_sb(const rtoss_wdesc& d, const ConvParams& c, const char* wfrag, const void* x, void* y,
                             hipStream_t s)
 {
@@ -439,8 +447,8 @@ rtoss_status launch_variant_sb(const rtoss_wdesc& d, const ConvParams& c, const 
     const int m_tiles_total = padded_m_tiles(d.Co);  // pitch of the packed section
     const int co_blocks = ((d.Co + 15) / 16 + TM - 1) / TM;
     constexpr int x_copies_per_wave = ((G::x_bytes / 16 + 63) / 64 + 3) / 4;
-    const size_t smem = (size_t)TM * kTileBytes + (size_t)x_copies_per_wave * 4096;
-    auto kern = conv3x3_sparse_sb_kernel<T, TO, S, TM, TN, RT, CT, AHEAD>;
+    const size_t smem = (size_t)TM * layout_tile_bytes(kLayouts[LAY]) + (size_t)x_copies_per_wave * 4096;
+    auto kern = conv3x3_sparse_sb_kernel<T, TO, S, TM, TN, RT, CT, AHEAD, LAY>;
     static LaunchOnce lds_once;  // per instantiation
     if (rtoss_status st = ensure_dynamic_lds((const void*)kern, smem, lds_once, "conv3x3 shared memory attribute")) return st;
     const int64_t total = (int64_t)tiles_r * tiles_c * co_blocks * c.N;
@@ -448,7 +456,7 @@ rtoss_status launch_variant_sb(const rtoss_wdesc& d, const ConvParams& c, const 
     if ((int64_t)c.N * c.H * c.W * d.Ci / 8 > 0x7fffffff) return fail(RTOSS_ESHAPE, "conv: input too large for 32-bit chunk offsets");
     const int work_per_xcd = (int)((total + 7) / 8);
     dim3 grid((unsigned)(work_per_xcd * 8)), block(256);
-    kern<<<grid, block, smem, s>>>((const T*)x, (TO*)y, wfrag, wfrag + fragment_bytes(d), c.H, c.W, d.Ci, d.Co, Ho, Wo,
+    kern<<<grid, block, smem, s>>>((const T*)x, (TO*)y, wfrag, wfrag + fragment_bytes(d, LAY), c.H, c.W, d.Ci, d.Co, Ho, Wo,
                                    m_tiles_total, tiles_c, tiles_r * tiles_c, co_blocks, (int)total, work_per_xcd, c.ep);
     return check_hip(hipGetLastError(), "conv3x3 sparse launch");
 }
@@ -460,6 +468,16 @@ inline bool takes_pipelined_kernel(const rtoss_wdesc& d, const ConvParams& c)
     if (c.stride != 1 || d.Co <= 64 || d.Ci <= 64) return false;
     const int64_t tiles8 = (int64_t)((c.H + 15) / 16) * ((c.W + 15) / 16) * c.N * (((d.Co + 15) / 16 + 7) / 8);
     return tiles8 >= 200;
+}
+
+// Layout 1 (three tap groups, 4-entry dictionaries): the single-buffered kernel for every shape.
+template <typename T, typename TO>
+rtoss_status launch_typed_layout1(const rtoss_wdesc& d, const ConvParams& c, const char* wfrag, const void* x, void* y,
+                                  hipStream_t s)
+{
+    if (c.stride == 1) return launch_variant_sb<T, TO, 1, 4, 2, 2, 4, false, 1>(d, c, wfrag, x, y, s);
+    if (d.Ci == 32) return launch_variant_sb<T, TO, 2, 4, 1, 1, 4, false, 1>(d, c, wfrag, x, y, s);
+    return launch_variant_sb<T, TO, 2, 4, 2, 2, 4, false, 1>(d, c, wfrag, x, y, s);
 }
 
 template <typename T, typename TO>
@@ -493,13 +511,19 @@ rtoss_status launch_typed(const rtoss_wdesc& d, const ConvParams& c, const char*
 
 // ---- host-visible entry points of this file ----
 
-bool sparse3x3_dictionary_ok(const Dict& dict)
+int sparse3x3_layout(const Dict& dict)
 {
-    for (int p = 0; p < dict.P; ++p) {
-        const unsigned m = dict.mask[p];
-        if (__builtin_popcount(m & 0x145u) > 2 || __builtin_popcount(m & 0x0aau) > 2) return false;
+    for (int l = 0; l < kNumLayouts; ++l) {
+        bool fits = true;
+        for (int g = 0; g < kLayouts[l].groups && fits; ++g) {
+            unsigned set = 0;
+            for (int f = 0; f < 4; ++f)
+                if (kLayouts[l].tap[g][f] >= 0) set |= 1u << kLayouts[l].tap[g][f];
+            for (int p = 0; p < dict.P && fits; ++p) fits = __builtin_popcount(dict.mask[p] & set) <= 2;
+        }
+        if (fits) return l;
     }
-    return true;
+    return -1;
 }
 
 bool sparse3x3_shape_ok(const rtoss_wdesc& d)
@@ -507,14 +531,15 @@ bool sparse3x3_shape_ok(const rtoss_wdesc& d)
     return d.ksize == 3 && (d.dt == RTOSS_F16 || d.dt == RTOSS_BF16) && d.Ci % 32 == 0 && d.Co % 16 == 0;
 }
 
-size_t sparse3x3_section_bytes(const rtoss_wdesc& d)
+size_t sparse3x3_section_bytes(const rtoss_wdesc& d, int layout)
 {
-    return fragment_bytes(d) + zero_block_bytes(d);
+    return fragment_bytes(d, layout) + zero_block_bytes(d);
 }
 
-static SparsePackArgs sparse_pack_args(const rtoss_wdesc& d, const void* w, const uint8_t* idx, void* section,
+static SparsePackArgs sparse_pack_args(const rtoss_wdesc& d, int layout, const void* w, const uint8_t* idx, void* section,
                                        void* live_values, uint8_t* live_idx, int* blocks)
 {
+    const int items_per_tile = 64 * layout_fragments(kLayouts[layout]);
     SparsePackArgs a;
     a.w = w;
     a.idx = idx;
@@ -522,10 +547,10 @@ static SparsePackArgs sparse_pack_args(const rtoss_wdesc& d, const void* w, cons
     a.Co = d.Co;
     a.Ci = d.Ci;
     a.m_tiles = padded_m_tiles(d.Co);
-    a.total_items = (int64_t)(d.Ci / 32) * a.m_tiles * 320;
+    a.total_items = (int64_t)(d.Ci / 32) * a.m_tiles * items_per_tile;
     a.zero_items = (int)(zero_block_bytes(d) / 16);
     a.job = make_live_job(live_values, live_idx, (int64_t)d.Co * d.Ci);
-    *blocks = (int)(a.job.blocks + a.total_items / 320 + (a.zero_items + 255) / 256);  // public section, tiles, zeros
+    *blocks = (int)(a.job.blocks + a.total_items / items_per_tile + (a.zero_items + 255) / 256);  // public section, tiles, zeros
     return a;
 }
 
@@ -533,23 +558,28 @@ rtoss_status launch_pack_sparse3x3(const rtoss_wdesc& d, const void* w, const ui
                                    void* section, void* live_values, uint8_t* live_idx, hipStream_t s)
 {
     int blocks = 0;
-    const SparsePackArgs a = sparse_pack_args(d, w, idx, section, live_values, live_idx, &blocks);
+    const int layout = sparse3x3_layout(dict);
+    if (layout < 0) return fail(RTOSS_EINVAL, "pack: the dictionary has no 2-of-4 tap layout");
+    const SparsePackArgs a = sparse_pack_args(d, layout, w, idx, section, live_values, live_idx, &blocks);
     dim3 grid((unsigned)blocks), block(256);
-    if (d.dt == RTOSS_F16) pack_sparse3x3_kernel<f16_t><<<grid, block, 0, s>>>(a, dict);
-    else pack_sparse3x3_kernel<bf16_t><<<grid, block, 0, s>>>(a, dict);
+    if (d.dt == RTOSS_F16) pack_sparse3x3_kernel<f16_t><<<grid, block, 0, s>>>(a, kLayouts[layout], dict);
+    else pack_sparse3x3_kernel<bf16_t><<<grid, block, 0, s>>>(a, kLayouts[layout], dict);
     return check_hip(hipGetLastError(), "pack sparse3x3 launch");
 }
 
 rtoss_status launch_pack_sparse3x3_batch(const PackItem* items, int n, const Dict& dict, hipStream_t s)
 {
+    const int layout = sparse3x3_layout(dict);
+    if (layout < 0) return fail(RTOSS_EINVAL, "pack: the dictionary has no 2-of-4 tap layout");
     for (int base = 0; base < n; base += kPackBatchMax) {
         SparsePackBatch b;
+        b.layout = kLayouts[layout];
         b.n = std::min(kPackBatchMax, n - base);
         int total = 0;
         for (int i = 0; i < b.n; ++i) {
             const PackItem& it = items[base + i];
             int blocks = 0;
-            b.a[i] = sparse_pack_args(it.d, it.w, it.idx, it.section, it.live, it.live_idx, &blocks);
+            b.a[i] = sparse_pack_args(it.d, layout, it.w, it.idx, it.section, it.live, it.live_idx, &blocks);
             b.first_block[i] = total;
             total += blocks;
         }
@@ -562,12 +592,18 @@ rtoss_status launch_pack_sparse3x3_batch(const PackItem* items, int n, const Dic
     return RTOSS_OK;
 }
 
-rtoss_status launch_conv3x3_sparse(const rtoss_wdesc& d, const ConvParams& c, const void* section, const void* x,
+rtoss_status launch_conv3x3_sparse(const rtoss_wdesc& d, const ConvParams& c, int layout, const void* section, const void* x,
                                    void* y, hipStream_t s)
 {
-    if (takes_pipelined_kernel(d, c)) return launch_conv3x3_rows(d, c, section, x, y, s);
     const char* wf = (const char*)section;
     const bool f32out = c.out_dt == RTOSS_F32;
+    if (layout == 1) {
+        if (d.dt == RTOSS_F16)
+            return f32out ? launch_typed_layout1<f16_t, float>(d, c, wf, x, y, s) : launch_typed_layout1<f16_t, f16_t>(d, c, wf, x, y, s);
+        return f32out ? launch_typed_layout1<bf16_t, float>(d, c, wf, x, y, s) : launch_typed_layout1<bf16_t, bf16_t>(d, c, wf, x, y, s);
+    }
+    if (layout != 0) return fail(RTOSS_EINVAL, "conv: unknown tap layout %d", layout);
+    if (takes_pipelined_kernel(d, c)) return launch_conv3x3_rows(d, c, section, x, y, s);
     if (d.dt == RTOSS_F16)
         return f32out ? launch_typed<f16_t, float>(d, c, wf, x, y, s) : launch_typed<f16_t, f16_t>(d, c, wf, x, y, s);
     return f32out ? launch_typed<bf16_t, float>(d, c, wf, x, y, s) : launch_typed<bf16_t, bf16_t>(d, c, wf, x, y, s);

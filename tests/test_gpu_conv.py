@@ -127,6 +127,33 @@ def test_conv3x3_dense_mode_shapes(dt, case):
     run_case(dt, N, Ci, Co, H, W, 3, stride, k, relu, seed=hash(case) % 10000 + dt, w_std=0.02, rule=rule)
 
 
+THREE_GROUP_LAYOUT = [
+    # 4-entry edge-connected patterns: the T shapes keep three edge midpoints, so the corner / edge-midpoint split
+    # does not fit them; the taps are laid out as three 2-of-4 groups {0,4,8}, {1,5,6}, {2,3,7} instead (6 sparse
+    # steps per 32 channels, no dense step).  Shapes for every tile variant of that path.
+    # N, Ci, Co,  H,  W, stride, relu
+    (1, 32, 16, 5, 7, 1, True),
+    (2, 64, 144, 33, 18, 1, False),
+    (3, 128, 128, 16, 35, 1, False),
+    (2, 256, 256, 40, 40, 1, True),
+    (1, 32, 64, 33, 37, 2, False),
+    (2, 64, 80, 37, 41, 2, True),
+    (2, 256, 272, 20, 24, 2, False),
+]
+
+
+@pytest.mark.parametrize("dt", [wl.F16, wl.BF16])
+@pytest.mark.parametrize("case", THREE_GROUP_LAYOUT)
+def test_conv3x3_four_entry_patterns_on_the_sparse_instruction(dt, case):
+    N, Ci, Co, H, W, stride, relu = case
+    masks = B.rtoss_pattern_dict(4)
+    # the packed blob must be the compressed format (6 fragments + 3 index words per tile), not the 9 dense ones
+    nbytes, _ = B.rtoss_pack_size(B.WDesc(Co, Ci, 3, 4, dt), masks)
+    tiles = (Ci // 32) * (((Co + 15) // 16 + 7) // 8 * 8)
+    assert nbytes < tiles * 7200 + Co * Ci * 9 + 8192
+    run_case(dt, N, Ci, Co, H, W, 3, stride, 4, relu, seed=hash(case) % 10000 + dt, w_std=0.02)
+
+
 FP32_MATRIX_CORE = [
     # fp32 tensors with Ci % 16 == 0 and Co % 16 == 0: dense mode on the fp32 matrix instruction, small
     # launches (16 channels x 4x16 positions per workgroup) and large ones (64 channels x 16x16)
