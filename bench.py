@@ -454,6 +454,41 @@ def main():
                       (L.Ci, L.Co, L.H, L.ksize, L.stride, a.elapsed_time(b) / 10 * 1e3), file=sys.stderr)
             del lay9, yd
 
+    # ---- block-shared patterns (layers that take over a parent's patterns, shared per run of 8 input channels):
+    # the same layers with such indices through the gather path on the dense instruction and through the
+    # 2-of-4 path, for comparison (bench only; not part of the timed step) ----
+    coherent = None
+    if not args.no_dense and cfg.dtype != wl.F32 and all(L.ksize == 3 and L.Ci % 32 == 0 and L.Co % 16 == 0 for L in cfg.layers):
+        rngc = np.random.default_rng(cfg.seed + 100)
+        t_gather = t_sparse = 0.0
+        steps_seen = set()
+        for L, w, x, y in zip(cfg.layers, w_dev, xs, ys):
+            idxc = np.repeat(rngc.integers(0, len(masks), L.Ci // 8), 8)[None, :].repeat(L.Co, 0).astype(np.uint8).reshape(-1)
+            idxc = torch.from_numpy(idxc).to(dev)
+            layc = pl.CoherentLayer(L.Co, L.Ci, cfg.k, cfg.dtype, masks).pack(w, idxc)
+            lays = pl.PackedLayer(L.Co, L.Ci, 3, cfg.k, cfg.dtype, masks).pack(w, idxc)
+            steps_seen |= set(np.unique(layc.steps()).tolist())
+            yd = torch.empty_like(y)
+            for lay, which in ((layc, "g"), (lays, "s")):
+                for _ in range(3):
+                    lay.conv(x, stride=L.stride, relu=L.relu, y=yd)
+                torch.cuda.synchronize()
+                a, b = ev(), ev()
+                a.record()
+                for _ in range(10):
+                    lay.conv(x, stride=L.stride, relu=L.relu, y=yd)
+                b.record()
+                torch.cuda.synchronize()
+                if which == "g":
+                    t_gather += a.elapsed_time(b) / 10
+                else:
+                    t_sparse += a.elapsed_time(b) / 10
+            del layc, lays, yd
+        coherent = {"patterns": "one per run of 8 input channels, shared by all output channels",
+                    "dense_steps_per_stage": sorted(int(v) for v in steps_seen),
+                    "gather_path_conv_ms": t_gather, "two_of_four_path_conv_ms": t_sparse,
+                    "gather_path_frac_of_peak": nz_flops / (t_gather * 1e-3) / 1e12 / PEAK_MFMA_16BIT_TFLOPS}
+
     # ---- the metric's second half: ms per YOLOv5s-shaped forward (cfg5), replayed from HIP graphs ----
     forward = None
     ok = parity.ok()
@@ -489,6 +524,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "parity": parity.report(),
+        "coherent_patterns": coherent,
         "yolo5s_forward": forward,
     }
     print(json.dumps(out))

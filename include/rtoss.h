@@ -299,6 +299,42 @@ rtoss_status rtoss_conv2d_pattern_fused(const rtoss_wdesc* desc, const rtoss_cde
                                         const void* packed_dev, const void* x_dev, void* y_dev,
                                         void* hip_stream);
 
+/*
+ * Layers whose kernels share their patterns in blocks (Section IV.A: the layers of a group take their
+ * kernel patterns from the group's parent layer; Section IV.C, closing sentences: kernels with the same
+ * pattern are processed together).  Where whole blocks of kernels -- 64 output channels x 8 consecutive
+ * input channels, the granularity at which the dense matrix instruction shares its operands -- keep the same
+ * taps, only those taps need a multiply at all: every multiply-add is then a non-zero one.
+ *
+ * rtoss_pack_coherent examines every block, records per (stage of 32 input channels, block of 64 output
+ * channels) the number of dense steps it needs -- the largest number of distinct live taps among the stage's
+ * four 8-channel runs: k when the patterns are shared, up to 9 when they are not -- and lays the weights out
+ * for exactly those steps.  rtoss_conv2d_pattern_coherent computes the same convolution as
+ * rtoss_conv2d_pattern from such a blob, for ANY index tensor; it is the faster call when the step counts
+ * are small (below 5 on the layers that would otherwise take the 2-of-4 layout).
+ *
+ *   desc          3x3 layers of RTOSS_F16 / RTOSS_BF16 with Ci % 32 == 0, Ci <= 2048 and Co % 16 == 0
+ *                 (RTOSS_ESHAPE / RTOSS_EDTYPE otherwise)
+ *   steps_offset  out, may be NULL: byte offset in the blob of the detection result, one 64-byte record per
+ *                 (stage, channel block), stage-major: uint32 steps; uint8 taps_per_run[4]; uint8 tap[4][9];
+ *                 uint8 pad[20].  A caller that wants to choose between the two paths packs both ways or reads
+ *                 these records back.
+ *   epilogue      as for rtoss_conv2d_pattern_fused, or NULL for none (cdesc->fuse_relu is honoured then)
+ * The blob's section 0 (survivors and indices) is the same as rtoss_pack's.  Channels-last tensors only
+ * (RTOSS_ELAYOUT otherwise).  All other arguments and errors as rtoss_pack_size / rtoss_pack /
+ * rtoss_conv2d_pattern_fused.
+ */
+rtoss_status rtoss_pack_size_coherent(const rtoss_wdesc* desc, const uint16_t* masks_host, int P,
+                                      size_t* packed_bytes, size_t* steps_offset);
+rtoss_status rtoss_pack_coherent(const rtoss_wdesc* desc, const void* w_dev, const uint8_t* idx_dev,
+                                 const uint16_t* masks_host, int P,
+                                 void* packed_dev, size_t packed_bytes, void* hip_stream);
+rtoss_status rtoss_conv2d_pattern_coherent(const rtoss_wdesc* desc, const rtoss_cdesc* cdesc,
+                                           const rtoss_epilogue* epilogue,
+                                           const uint16_t* masks_host, int P,
+                                           const void* packed_dev, const void* x_dev, void* y_dev,
+                                           void* hip_stream);
+
 /* Message for the last error on the calling thread ("" if none).  Static storage. */
 const char* rtoss_last_error(void);
 

@@ -54,7 +54,8 @@ class SelectItem(ctypes.Structure):
 
 
 EXPORTS = ["rtoss_pattern_dict", "rtoss_select_patterns", "rtoss_select_patterns_batch", "rtoss_pattern_histogram", "rtoss_reduce_dict",
-           "rtoss_pack_size", "rtoss_pack", "rtoss_pack_batch", "rtoss_conv2d_pattern", "rtoss_conv2d_pattern_fused", "rtoss_last_error"]
+           "rtoss_pack_size", "rtoss_pack", "rtoss_pack_batch", "rtoss_conv2d_pattern", "rtoss_conv2d_pattern_fused",
+           "rtoss_pack_size_coherent", "rtoss_pack_coherent", "rtoss_conv2d_pattern_coherent", "rtoss_last_error"]
 
 
 def lib():
@@ -94,6 +95,13 @@ def lib():
         L.rtoss_conv2d_pattern_fused.restype = i
         L.rtoss_conv2d_pattern_fused.argtypes = [ctypes.POINTER(WDesc), ctypes.POINTER(CDesc), ctypes.POINTER(EpilogueDesc),
                                                  u16p, i, vp, vp, vp, vp]
+        L.rtoss_pack_size_coherent.restype = i
+        L.rtoss_pack_size_coherent.argtypes = [ctypes.POINTER(WDesc), u16p, i, szp, szp]
+        L.rtoss_pack_coherent.restype = i
+        L.rtoss_pack_coherent.argtypes = [ctypes.POINTER(WDesc), vp, vp, u16p, i, vp, ctypes.c_size_t, vp]
+        L.rtoss_conv2d_pattern_coherent.restype = i
+        L.rtoss_conv2d_pattern_coherent.argtypes = [ctypes.POINTER(WDesc), ctypes.POINTER(CDesc), ctypes.POINTER(EpilogueDesc),
+                                                    u16p, i, vp, vp, vp, vp]
         _lib = L
     return _lib
 
@@ -186,6 +194,29 @@ def rtoss_conv2d_pattern_fused(wdesc, cdesc, epilogue, masks, packed_ptr, x_ptr,
                                             ctypes.byref(cdesc) if cdesc is not None else None,
                                             ctypes.byref(epilogue) if epilogue is not None else None, mp, P,
                                             packed_ptr, x_ptr, y_ptr, stream))
+
+
+def rtoss_pack_size_coherent(wdesc, masks):
+    """(packed bytes, byte offset of the per-(stage, channel block) step records)."""
+    mp, P, _keep = _masks_arg(masks)
+    a, b = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    _check(lib().rtoss_pack_size_coherent(ctypes.byref(wdesc) if wdesc is not None else None, mp, P, ctypes.byref(a),
+                                          ctypes.byref(b)))
+    return a.value, b.value
+
+
+def rtoss_pack_coherent(wdesc, w_ptr, idx_ptr, masks, packed_ptr, packed_bytes, stream=0):
+    mp, P, _keep = _masks_arg(masks)
+    _check(lib().rtoss_pack_coherent(ctypes.byref(wdesc) if wdesc is not None else None, w_ptr, idx_ptr, mp, P, packed_ptr,
+                                     packed_bytes, stream))
+
+
+def rtoss_conv2d_pattern_coherent(wdesc, cdesc, epilogue, masks, packed_ptr, x_ptr, y_ptr, stream=0):
+    mp, P, _keep = _masks_arg(masks)
+    _check(lib().rtoss_conv2d_pattern_coherent(ctypes.byref(wdesc) if wdesc is not None else None,
+                                               ctypes.byref(cdesc) if cdesc is not None else None,
+                                               ctypes.byref(epilogue) if epilogue is not None else None, mp, P,
+                                               packed_ptr, x_ptr, y_ptr, stream))
 
 
 def rtoss_pack_batch(items, masks, stream=0):

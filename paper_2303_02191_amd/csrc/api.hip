@@ -144,7 +144,7 @@ static rtoss_status check_wdesc(const rtoss_wdesc* d)
     return RTOSS_OK;
 }
 
-rtoss_status blob_geometry(const rtoss_wdesc* d, const Dict& dict, BlobGeometry* g)
+rtoss_status blob_geometry(const rtoss_wdesc* d, const Dict& dict, BlobGeometry* g, bool coherent)
 {
     std::memset(g, 0, sizeof *g);
     g->n_elems = (int64_t)d->Co * d->Ci * d->ksize * d->ksize;
@@ -155,7 +155,14 @@ rtoss_status blob_geometry(const rtoss_wdesc* d, const Dict& dict, BlobGeometry*
     g->format = kFormatNone;
     g->mat_off = 0;
     g->mat_bytes = 0;
-    if (sparse3x3_shape_ok(*d) && sparse3x3_layout(dict) >= 0) {
+    if (coherent) {
+        if (!gather3x3_shape_ok(*d))
+            return fail(RTOSS_ESHAPE, "the coherent path takes 3x3 layers of a 16-bit type with Ci %% 32 == 0, Ci <= 2048, Co %% 16 == 0");
+        g->format = kFormatGather3x3;
+        g->mat_off = end;
+        g->mat_bytes = gather3x3_section_bytes(*d);
+        end = align_up(end + g->mat_bytes, 256);
+    } else if (sparse3x3_shape_ok(*d) && sparse3x3_layout(dict) >= 0) {
         g->format = kFormatSparse24;
         g->mat_off = end;
         g->mat_bytes = sparse3x3_section_bytes(*d, sparse3x3_layout(dict));
@@ -292,11 +299,11 @@ rtoss_status rtoss_pack_size(const rtoss_wdesc* desc, const uint16_t* masks_host
 
 // Validation shared by rtoss_pack and rtoss_pack_batch; fills the geometry and the section pointers.
 static rtoss_status check_pack(const rtoss_wdesc* desc, const Dict& dict, const void* w_dev, const uint8_t* idx_dev,
-                               void* packed_dev, size_t packed_bytes, BlobGeometry* g, PackItem* item)
+                               void* packed_dev, size_t packed_bytes, BlobGeometry* g, PackItem* item, bool coherent = false)
 {
     if (rtoss_status st = check_wdesc(desc)) return st;
     if (dict.k != desc->k) return fail(RTOSS_EINVAL, "dictionary keeps %d taps, descriptor says k=%d", dict.k, desc->k);
-    if (rtoss_status st = blob_geometry(desc, dict, g)) return st;
+    if (rtoss_status st = blob_geometry(desc, dict, g, coherent)) return st;
     if (!packed_dev) return fail(RTOSS_EINVAL, "packed_dev is NULL");
     if (packed_bytes < g->total)
         return fail(RTOSS_ENOSPACE, "packed buffer has %zu bytes, %zu needed", packed_bytes, g->total);
@@ -377,7 +384,7 @@ rtoss_status rtoss_pack_batch(const rtoss_pack_item* items_host, int n_items, co
 
 static rtoss_status conv_impl(const rtoss_wdesc* desc, const rtoss_cdesc* c, const rtoss_epilogue* e,
                               const uint16_t* masks_host, int P, const void* packed_dev, const void* x_dev, void* y_dev,
-                              void* hip_stream)
+                              void* hip_stream, bool coherent = false)
 {
     if (rtoss_status st = check_wdesc(desc)) return st;
     if (!c) return fail(RTOSS_EINVAL, "conv descriptor is NULL");
@@ -438,8 +445,12 @@ static rtoss_status conv_impl(const rtoss_wdesc* desc, const rtoss_cdesc* c, con
         cp.ep = Epilogue{e->scale_dev, e->bias_dev, e->residual_dev, (int)e->act, ldy, ldr};
     }
     BlobGeometry g;
-    if (rtoss_status st = blob_geometry(desc, dict, &g)) return st;
+    if (rtoss_status st = blob_geometry(desc, dict, &g, coherent)) return st;
     const char* blob = (const char*)packed_dev;
+    if (coherent) {
+        if (c->layout != RTOSS_NHWC) return fail(RTOSS_ELAYOUT, "the coherent path takes channels-last tensors");
+        return launch_conv3x3_gather(*desc, cp, blob + g.mat_off, x_dev, y_dev, (hipStream_t)hip_stream);
+    }
     if (c->layout == RTOSS_NCHW)  // the element-wise kernel reads section 0 and takes any strides
         return launch_conv_direct(*desc, cp, dict, blob + g.live_off, (const uint8_t*)(blob + g.idx_off), x_dev, y_dev,
                                   (hipStream_t)hip_stream);
@@ -457,6 +468,40 @@ static rtoss_status conv_impl(const rtoss_wdesc* desc, const rtoss_cdesc* c, con
                               (hipStream_t)hip_stream);
 }
 
+
+rtoss_status rtoss_pack_size_coherent(const rtoss_wdesc* desc, const uint16_t* masks_host, int P, size_t* packed_bytes,
+                                      size_t* steps_offset)
+{
+    if (rtoss_status st = check_wdesc(desc)) return st;
+    if (!packed_bytes) return fail(RTOSS_EINVAL, "size output pointer is NULL");
+    Dict dict;
+    if (rtoss_status st = load_dict(masks_host, P, &dict)) return st;
+    if (dict.k != desc->k) return fail(RTOSS_EINVAL, "dictionary keeps %d taps, descriptor says k=%d", dict.k, desc->k);
+    BlobGeometry g;
+    if (rtoss_status st = blob_geometry(desc, dict, &g, true)) return st;
+    *packed_bytes = g.total;
+    if (steps_offset) *steps_offset = g.mat_off;
+    return RTOSS_OK;
+}
+
+rtoss_status rtoss_pack_coherent(const rtoss_wdesc* desc, const void* w_dev, const uint8_t* idx_dev, const uint16_t* masks_host,
+                                 int P, void* packed_dev, size_t packed_bytes, void* hip_stream)
+{
+    if (rtoss_status st = check_wdesc(desc)) return st;
+    Dict dict;
+    if (rtoss_status st = load_dict(masks_host, P, &dict)) return st;
+    BlobGeometry g;
+    PackItem it;
+    if (rtoss_status st = check_pack(desc, dict, w_dev, idx_dev, packed_dev, packed_bytes, &g, &it, true)) return st;
+    return launch_pack_gather3x3(it.d, it.w, it.idx, dict, it.section, it.live, it.live_idx, (hipStream_t)hip_stream);
+}
+
+rtoss_status rtoss_conv2d_pattern_coherent(const rtoss_wdesc* desc, const rtoss_cdesc* c, const rtoss_epilogue* epilogue,
+                                           const uint16_t* masks_host, int P, const void* packed_dev, const void* x_dev,
+                                           void* y_dev, void* hip_stream)
+{
+    return conv_impl(desc, c, epilogue, masks_host, P, packed_dev, x_dev, y_dev, hip_stream, true);
+}
 
 rtoss_status rtoss_conv2d_pattern(const rtoss_wdesc* desc, const rtoss_cdesc* c, const uint16_t* masks_host, int P,
                                   const void* packed_dev, const void* x_dev, void* y_dev, void* hip_stream)

@@ -39,7 +39,8 @@ enum MatrixFormat {
     kFormatSparse24 = 2, // 3x3: 2-of-4 compressed fragments + indices
     kFormatStem = 3,     // 3x3 with <= 3 input channels: one zero-filled fragment per 16 output channels
     kFormatDenseStream = 4,  // 1x1 with Ci = 32 * 2^n <= 1024: zero-filled fragments in the streaming kernel's order
-    kFormatDense3x3 = 5      // 3x3 whose dictionary has no 2-of-4 shape: zero-filled fragments, one per tap
+    kFormatDense3x3 = 5,     // 3x3 whose dictionary has no 2-of-4 shape: zero-filled fragments, one per tap
+    kFormatGather3x3 = 6     // 3x3, on request (rtoss_pack_coherent): per-block tap lists on the dense instruction
 };
 
 struct BlobGeometry {
@@ -54,7 +55,7 @@ struct BlobGeometry {
 };
 
 // Filled by host code in api.cpp.
-rtoss_status blob_geometry(const rtoss_wdesc* d, const Dict& dict, BlobGeometry* out);
+rtoss_status blob_geometry(const rtoss_wdesc* d, const Dict& dict, BlobGeometry* out, bool coherent = false);
 
 // ----- error plumbing -----
 rtoss_status fail(rtoss_status st, const char* fmt, ...);
@@ -128,6 +129,16 @@ rtoss_status launch_conv3x3_sparse(const rtoss_wdesc& d, const ConvParams& c, in
 // ... large stride-1 layers: pipelined kernel over strips of output rows (conv3x3_rows.hip); same packed section
 rtoss_status launch_conv3x3_rows(const rtoss_wdesc& d, const ConvParams& c, const void* section, const void* x, void* y,
                                  hipStream_t s);
+
+// 3x3 convolution with live taps gathered onto the dense matrix instruction, for block-shared patterns
+// (conv3x3_gather.hip); its own blob format, chosen by the caller (rtoss_pack_coherent)
+bool gather3x3_shape_ok(const rtoss_wdesc& d);
+size_t gather3x3_header_bytes(const rtoss_wdesc& d);
+size_t gather3x3_section_bytes(const rtoss_wdesc& d);
+rtoss_status launch_pack_gather3x3(const rtoss_wdesc& d, const void* w, const uint8_t* idx, const Dict& dict, void* section,
+                                   void* live_values, uint8_t* live_idx, hipStream_t s);
+rtoss_status launch_conv3x3_gather(const rtoss_wdesc& d, const ConvParams& c, const void* section, const void* x, void* y,
+                                   hipStream_t s);
 
 // 3x3 convolution in dense mode on the matrix cores (conv3x3_dense.hip)
 bool dense3x3_shape_ok(const rtoss_wdesc& d);

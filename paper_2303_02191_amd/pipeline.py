@@ -82,6 +82,41 @@ def reduce_dictionary(masks, w_random, dt, M):
     return out, kept, counts
 
 
+class CoherentLayer:
+    """A 3x3 layer packed for the dense-instruction gather path (block-shared patterns)."""
+
+    def __init__(self, Co, Ci, k, dt, masks, device="cuda"):
+        self.wdesc = B.WDesc(Co, Ci, 3, k, dt)
+        self.masks, self.dt = masks, dt
+        self.packed_bytes, self.steps_offset = B.rtoss_pack_size_coherent(self.wdesc, masks)
+        self.blob = torch.empty(self.packed_bytes, dtype=torch.uint8, device=device)
+
+    def pack(self, w, idx):
+        assert w.is_cuda and w.is_contiguous() and idx.is_cuda
+        B.rtoss_pack_coherent(self.wdesc, w.data_ptr(), idx.data_ptr(), self.masks, self.blob.data_ptr(), self.packed_bytes,
+                              _stream())
+        return self
+
+    def steps(self):
+        """Detection result: dense steps per (stage, block of 64 output channels), as a numpy array [stages, blocks]."""
+        stages, blocks = self.wdesc.Ci // 32, (self.wdesc.Co + 63) // 64
+        torch.cuda.synchronize()
+        rec = self.blob[self.steps_offset: self.steps_offset + stages * blocks * 64].cpu().numpy().reshape(stages, blocks, 64)
+        return rec[:, :, :4].copy().view("<u4").reshape(stages, blocks)
+
+    def conv(self, x, stride=1, relu=False, out_dt=None, y=None):
+        assert x.is_cuda and x.is_contiguous() and x.shape[3] == self.wdesc.Ci
+        out_dt = self.dt if out_dt is None else out_dt
+        N, H, W, _ = x.shape
+        if y is None:
+            y = torch.empty((N, (H - 1) // stride + 1, (W - 1) // stride + 1, self.wdesc.Co), dtype=TORCH_DTYPE[out_dt],
+                            device=x.device)
+        cdesc = B.CDesc(N, H, W, stride, 1, B.NHWC, out_dt, int(bool(relu)))
+        B.rtoss_conv2d_pattern_coherent(self.wdesc, cdesc, None, self.masks, self.blob.data_ptr(), x.data_ptr(), y.data_ptr(),
+                                        _stream())
+        return y
+
+
 class PackedLayer:
     """One layer's packed blob plus the descriptors the convolution call needs."""
 

@@ -218,3 +218,31 @@ def test_batched_pack_argument_errors():
     assert e.value.status == B.EINVAL
     B.rtoss_pack_batch([], masks)
 
+
+
+def test_coherent_path_argument_errors():
+    masks = B.rtoss_pattern_dict(3)
+    for bad in (B.WDesc(64, 32, 1, 3, B.F16), B.WDesc(64, 48, 3, 3, B.F16), B.WDesc(40, 32, 3, 3, B.F16),
+                B.WDesc(64, 4096, 3, 3, B.F16), B.WDesc(64, 32, 3, 3, B.F32)):
+        with pytest.raises(B.RtossError) as e:
+            B.rtoss_pack_size_coherent(bad, masks)
+        assert e.value.status == B.ESHAPE
+    d = B.WDesc(64, 64, 3, 3, B.BF16)
+    nbytes, off = B.rtoss_pack_size_coherent(d, masks)
+    assert nbytes % 256 == 0 and off % 256 == 0 and nbytes >= off + 2 * 64 + 2 * 9 * 4096
+    with pytest.raises(B.RtossError) as e:
+        B.rtoss_pack_size_coherent(B.WDesc(64, 64, 3, 2, B.BF16), masks)  # k != popcount
+    assert e.value.status == B.EINVAL
+    with pytest.raises(B.RtossError) as e:
+        B.rtoss_pack_coherent(d, 256, 512, masks, 1024, nbytes - 1)
+    assert e.value.status == B.ENOSPACE
+    with pytest.raises(B.RtossError) as e:
+        B.rtoss_pack_coherent(d, 0, 512, masks, 1024, nbytes)
+    assert e.value.status == B.EINVAL
+    ok = B.CDesc(1, 8, 8, 1, 1, B.NHWC, B.BF16, 0)
+    with pytest.raises(B.RtossError) as e:
+        B.rtoss_conv2d_pattern_coherent(d, B.CDesc(1, 8, 8, 1, 1, B.NCHW, B.BF16, 0), None, masks, 256, 512, 1 << 20)
+    assert e.value.status == B.ELAYOUT
+    with pytest.raises(B.RtossError) as e:
+        B.rtoss_conv2d_pattern_coherent(d, ok, None, masks, 0, 512, 1 << 20)
+    assert e.value.status == B.EINVAL
