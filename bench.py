@@ -147,6 +147,9 @@ def parse():
     ap.add_argument("--k", type=int, default=0,
                     help="entries kept per kernel instead of the workload's own (the axis of the sensitivity study, "
                          "Table 3)")
+    ap.add_argument("--dict-top", type=int, default=0,
+                    help="reduce the dictionary to its M most used patterns first (Section IV.B, second criterion: "
+                         "winners counted over 2^20 random kernels in [-1, 1]) and run the step with that")
     ap.add_argument("--per-layer", action="store_true", help="after the timed region, time every layer's conv alone (stderr)")
     return ap.parse_args()
 
@@ -154,7 +157,7 @@ def parse():
 class Workload:
     """Device-resident tensors of one configuration and the three phases of a step."""
 
-    def __init__(self, cfg, dev):
+    def __init__(self, cfg, dev, dict_top=0):
         import torch
         from paper_2303_02191_amd import binding as B
         from paper_2303_02191_amd import pipeline as pl
@@ -163,6 +166,14 @@ class Workload:
         self.cfg = cfg
         self.masks = B.rtoss_pattern_dict(cfg.k)
         self.tdt = pl.TORCH_DTYPE[cfg.dtype]
+        self.dict_counts = None
+        if dict_top:
+            g = torch.Generator(device=dev)
+            g.manual_seed(cfg.seed + 1000)
+            w_rand = (torch.rand((1 << 20) * 9, generator=g, device=dev, dtype=torch.float32) * 2 - 1).to(self.tdt)
+            self.masks, kept, counts = pl.reduce_dictionary(self.masks, w_rand, cfg.dtype, dict_top)
+            self.dict_counts = {"kept": [int(i) for i in kept], "wins": [int(c) for c in counts]}
+            del w_rand
         # ---- inputs: weights drawn on the host (seeded numpy), activations on the device (seeded torch) ----
         rng = np.random.default_rng(cfg.seed)
         gen = torch.Generator(device=dev)
@@ -364,7 +375,7 @@ def main():
         import dataclasses
         cfg = dataclasses.replace(cfg, k=args.k, name="%s_k%d" % (cfg.name, args.k))
     eb = wl.ELEM_BYTES[cfg.dtype]
-    work = Workload(cfg, dev)
+    work = Workload(cfg, dev, args.dict_top)
     masks = work.masks
     ev = lambda: torch.cuda.Event(enable_timing=True)
     use_graph = args.graph == "on" or (args.graph == "auto" and len(cfg.layers) > 8)
@@ -527,6 +538,8 @@ def main():
         "coherent_patterns": coherent,
         "yolo5s_forward": forward,
     }
+    if work.dict_counts:
+        out["config"]["dictionary_reduction"] = work.dict_counts
     print(json.dumps(out))
     if not ok:
         print("bench.py: PARITY FAILED: the numbers above describe a wrong result", file=sys.stderr)
