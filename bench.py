@@ -344,7 +344,7 @@ def roofline_of(cfg, wl, workload, conv_ms, k_override):
         r = {"bound": "mfma", "achieved": achieved, "peak": PEAK_MFMA_16BIT_TFLOPS, "unit": "TFLOP/s",
              "frac": achieved / PEAK_MFMA_16BIT_TFLOPS, "traffic": None}
     if workload == "cfg4" and not k_override:
-        r["traffic"] = measured_traffic("conv3x3_sparse_cfg4_hbm_traffic.txt")
+        r["traffic"] = measured_traffic("conv3x3_rows_cfg4_hbm_traffic.txt")
     r["kernel"] = "rtoss_conv2d_pattern"
     r["avg_launch_us"] = conv_launch_s * 1e6
     r["launches_per_step"] = n_conv
