@@ -376,7 +376,7 @@ def main():
         cfg = dataclasses.replace(cfg, k=args.k, name="%s_k%d" % (cfg.name, args.k))
     eb = wl.ELEM_BYTES[cfg.dtype]
     work = Workload(cfg, dev, args.dict_top)
-    masks = work.masks
+    masks, dict_counts = work.masks, work.dict_counts
     ev = lambda: torch.cuda.Event(enable_timing=True)
     use_graph = args.graph == "on" or (args.graph == "auto" and len(cfg.layers) > 8)
 
@@ -538,8 +538,8 @@ def main():
         "coherent_patterns": coherent,
         "yolo5s_forward": forward,
     }
-    if work.dict_counts:
-        out["config"]["dictionary_reduction"] = work.dict_counts
+    if dict_counts:
+        out["config"]["dictionary_reduction"] = dict_counts
     print(json.dumps(out))
     if not ok:
         print("bench.py: PARITY FAILED: the numbers above describe a wrong result", file=sys.stderr)
