@@ -24,26 +24,33 @@ def check_matrix_hazards(asm_path):
     """Scans the device assembly the compiler generated for one source file.
 
     The kernels issue their matrix instructions as asm statements, which the compiler's hazard handling does
-    not see.  One hazard slips through that way, and it was observed to corrupt results: a v_accvgpr_read (or
-    v_accvgpr_mov) -- the instruction with which the register allocator brings back a value it had parked in the
-    accumulation registers -- writing a vector register that an asm matrix instruction reads right afterwards.
-    Those moves run through the matrix pipeline, and nothing interlocks the matrix instruction's operand read
-    against them.  (Ordinary vector-ALU results, e.g. a v_perm_b32 directly in front of the matrix instruction
-    that consumes it, are interlocked: kernels with that pattern match the oracle bit for bit.)  Returns the
-    offending (writer, matrix instruction) pairs.  Two instructions in between were seen to be enough; the scan
-    flags anything closer than five instructions apart.
+    not see.  Two hazards slip through that way, and both were observed to corrupt results:
+    (1) a v_accvgpr_read (or v_accvgpr_mov) -- the instruction with which the register allocator brings back a
+        value it had parked in the accumulation registers -- writing a vector register that an asm matrix
+        instruction reads right afterwards.  Those moves run through the matrix pipeline, and nothing interlocks
+        the matrix instruction's operand read against them.  (Ordinary vector-ALU results, e.g. a v_perm_b32
+        directly in front of the matrix instruction that consumes it, are interlocked: kernels with that pattern
+        match the oracle bit for bit.)  Two instructions in between were seen to be enough; the scan flags anything
+        closer than five instructions apart.
+    (2) an accumulator move (v_accvgpr_read / _mov / _write, or a spill reload into accumulation registers) that
+        touches the destination of an asm matrix instruction issued fewer than 20 cycles before: the compiler
+        shuffles accumulators where control-flow paths with different register assignments join, and it does not
+        know that the asm statement in front is still writing them.  (The kernels' own reads of the accumulators
+        come behind two s_nop 15.)
+    Returns the offending (first, second) instruction pairs.
     """
     import re
 
-    def regs(tok):
+    def regs(tok, cls="v"):
         tok = tok.strip().split()[0] if tok.strip() else ""
-        m = re.match(r"v\[(\d+):(\d+)\]$", tok)
+        m = re.match(cls + r"\[(\d+):(\d+)\]$", tok)
         if m:
             return set(range(int(m.group(1)), int(m.group(2)) + 1))
-        m = re.match(r"v(\d+)$", tok)
+        m = re.match(cls + r"(\d+)$", tok)
         return {int(m.group(1))} if m else set()
 
     found, window, in_asm = [], [], False
+    recent_dest = []  # [cycles since issue, accumulator registers written, text] of asm matrix instructions
     for raw in open(asm_path, errors="replace"):
         line = raw.strip()
         if line.startswith(";;#ASMSTART"):
@@ -55,8 +62,27 @@ def check_matrix_hazards(asm_path):
         if not line or line[0] in ";." or line.endswith(":"):
             continue
         op = line.split()[0]
-        if in_asm and (op.startswith("v_mfma") or op.startswith("v_smfmac")):
+        cost = 1
+        if op == "s_nop":  # s_nop N idles N + 1 cycles
+            cost = (int(line.split()[1]) if len(line.split()) > 1 and line.split()[1].isdigit() else 0) + 1
+        is_asm_matrix = in_asm and (op.startswith("v_mfma") or op.startswith("v_smfmac"))
+        # ---- (2) accumulator moves behind an asm matrix instruction ----
+        touched = set()
+        if op.startswith("v_accvgpr") or (op.startswith("scratch_load") or op.startswith("global_load") or op.startswith("ds_read")):
+            for tok in line.split(None, 1)[1].split(",") if len(line.split(None, 1)) > 1 else []:
+                touched |= regs(tok, "a")
+        if touched and not is_asm_matrix:
+            for age, dest, text in recent_dest:
+                if age < 20 and (dest & touched):
+                    found.append((text, line))
+                    break
+        for entry in recent_dest:
+            entry[0] += cost
+        recent_dest = [e for e in recent_dest if e[0] < 20]
+        if is_asm_matrix:
             operands = line.split(None, 1)[1].split(",")
+            recent_dest.append([0, regs(operands[0], "a"), line])
+            # ---- (1) parked values restored in front of the instruction ----
             sources = set()
             for tok in operands[1:]:
                 sources |= regs(tok)
@@ -67,9 +93,8 @@ def check_matrix_hazards(asm_path):
                         found.append((prev, line))
             window = []  # (a matrix instruction in between is far more than two wait states)
             continue
-        if op == "s_nop":  # s_nop N idles N + 1 cycles
-            n = int(line.split()[1]) if len(line.split()) > 1 and line.split()[1].isdigit() else 0
-            window += ["s_nop"] * (n + 1)
+        if op == "s_nop":
+            window += ["s_nop"] * cost
         else:
             window.append(line)
         window = window[-4:]
@@ -87,8 +112,9 @@ def _compile_one(args):
         if f.startswith(stem + "-hip-amdgcn") and f.endswith(".s"):
             bad = check_matrix_hazards(os.path.join(os.path.dirname(obj), f))
             if bad:
-                raise RuntimeError("%s: %d matrix instruction(s) read a vector-ALU result too early, e.g. `%s` -> `%s`; "
-                                   "lower the register pressure of the kernel or define RTOSS_MFMA_SETTLE for this file"
+                raise RuntimeError("%s: %d register hazard(s) around asm matrix instructions, e.g. `%s` -> `%s`; "
+                                   "lower the register pressure of the kernel, keep accumulators out of control-flow joins, "
+                                   "or define RTOSS_MFMA_SETTLE for this file"
                                    % (os.path.basename(src), len(bad), bad[0][0], bad[0][1]))
     return obj
 

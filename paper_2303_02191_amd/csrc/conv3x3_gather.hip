@@ -27,6 +27,8 @@
 #include "epilogue.h"
 #include "mma.h"
 #include "pack_live.h"
+#include "rows_plan.h"
+#include "sparse_frag.h"
 #include "tile3x3.h"
 
 namespace rtoss {
@@ -101,7 +103,9 @@ __global__ __launch_bounds__(256) void pack_gather3x3_kernel(const T* __restrict
     // ---- fragments: [step][fragment m][lane]; row 4q'+i of fragment m is channel 16q' + 4m + i of the block, so that a
     // lane's 16 accumulator values are 16 consecutive channels (as in the dense-mode kernel) ----
     char* out = section + hdr_bytes + (size_t)b * kBlockBytes;
-    const int items = (int)hdr.steps * kTM * 64;
+    // (step 0 is always written, zeros when the block has no live tap at all: the pipelined kernel starts every
+    // accumulator with it)
+    const int items = (int)(hdr.steps ? hdr.steps : 1u) * kTM * 64;
     for (int item = threadIdx.x; item < items; item += 256) {
         const int lane = item % 64, m = (item / 64) % kTM, s = item / (64 * kTM);
         const int r = lane % 16, q = lane / 16;
@@ -256,6 +260,371 @@ __global__ __launch_bounds__(256) void conv3x3_gather_kernel(const T* __restrict
     }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// Pipelined variant over strips of rows: the tiling, persistent workgroups, double-buffered stages and direct
+// epilogue of conv3x3_rows.hip (stride 1, 128 output channels x 16 columns x 4*TN rows per workgroup, wave v owns
+// TN rows), around a much simpler stage: `steps` dense steps, each 8*TN matrix instructions on operands read
+// straight from LDS -- one 16-byte read per output row gives the B operand of all 8 channel fragments (the step's
+// tap is a per-quarter LDS offset), no transposes.  A workgroup covers two channel blocks of 64 with their own tap
+// lists; a block with fewer steps than its partner skips its half of the surplus steps.  Up to kGrSteps steps of
+// a stage live in LDS; a stage with more (patterns that are not shared after all) takes the rest of its weight
+// fragments from global memory, slowly but correctly.
+// ---------------------------------------------------------------------------------------------------------
+constexpr int kGrSteps = 5;
+__device__ __forceinline__ int c_cb0_of_tile(int cb0, int half, int cblocks) { return cb0 + (half && cb0 + 1 < cblocks ? 1 : 0); }
+constexpr int kGrABytes = kGrSteps * 2 * kStepBytes;  // [step][block of the pair][fragment]: 40 KB
+constexpr int kGrXChunks = (4 * kTall + 2) * kLW * 4;
+constexpr int kGrXPerWave = ((kGrXChunks + 63) / 64 + 3) / 4;
+constexpr int kGrXArea = kGrXPerWave * 4 * 1024;
+constexpr int kGrRegion = kGrABytes + kGrXArea;
+constexpr int kGrAPerWave = kGrABytes / 1024 / 4;
+constexpr int kGrCopySlots = kGrAPerWave + kGrXPerWave;
+constexpr int kGrOffPitch = 16;  // int16 entries per (stage, block, quarter): one 16-byte read fetches steps 0..7
+constexpr size_t kGrSmem = 2 * (size_t)kGrRegion + kMaxStages * 4 + (size_t)kMaxStages * 2 * 4 * kGrOffPitch * 2;
+static_assert(kGrCopySlots <= 3 * 2 * 3, "three copies per half-step must cover a stage within three steps");
+
+template <typename T, typename TO>
+__global__ __launch_bounds__(256, 1) void conv3x3_gather_rows_kernel(const T* __restrict__ x, TO* __restrict__ y,
+                                                                     const GatherHeader* __restrict__ headers,
+                                                                     const char* __restrict__ wfrag,
+                                                                     const char* __restrict__ zeros, int H, int W, int Ci,
+                                                                     int Co, int cblocks, RowPlan plan, float relu_floor, int ldy)
+{
+    static_assert(sizeof(TO) == 2, "direct epilogue: 16-bit output");
+    extern __shared__ __attribute__((aligned(16))) char smem[];  // two regions, then the tile's step counts and tap offsets
+    int* lds_steps = (int*)(smem + 2 * kGrRegion);               // [stage]: steps of block 0 | steps of block 1 << 8
+    int16_t* lds_off = (int16_t*)(lds_steps + kMaxStages);       // [stage][block][quarter][kGrOffPitch]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int stages = Ci / 32;
+    const int Ho = H, Wo = W;  // stride 1, padding 1
+
+    // ---- this workgroup's entries (as in conv3x3_rows.hip) ----
+    const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8, slots = gridDim.x / 8;
+    const int tall_end = min((xcd + 1) * plan.tall_per_xcd, plan.tall_total);
+    const int short_end = min((xcd + 1) * plan.short_per_xcd, plan.short_total);
+    int tall_next = xcd * plan.tall_per_xcd + slot;
+    int short_next = xcd * plan.short_per_xcd + (slots - 1 - slot);
+    if (tall_next >= tall_end && short_next >= short_end) return;
+
+    // steps of the two blocks of channel-block pair cb0 in stage `stage`, from the headers in global memory
+    auto pair_steps_lane = [&](int cb0, int stage) -> int {
+        const GatherHeader* h = headers + (size_t)stage * cblocks + cb0;
+        unsigned s0 = h->steps, s1 = cb0 + 1 < cblocks ? h[1].steps : 0u;
+        s0 = s0 > 9u ? 9u : s0;  // (a corrupt header cannot run the loops out of bounds)
+        s1 = s1 > 9u ? 9u : s1;
+        return (int)(s0 | (s1 << 8));
+    };
+    auto pair_steps = [&](int cb0, int stage) -> int {  // uniform arguments only
+        return __builtin_amdgcn_readfirstlane(pair_steps_lane(cb0, stage));
+    };
+    auto copies_of = [](int st, bool first_stage) {  // 1 KB pieces of the weight fragments of a stage kept in LDS
+        int n = max(st & 0xff, st >> 8);
+        if (first_stage) n = max(n, 1);
+        return min(n, kGrSteps) * 2 * kTM;
+    };
+
+    // ---- copy state: the tile whose stages are being fetched ----
+    int c_cb0 = 0;
+    const char* x_ptr[kGrXPerWave];
+    auto setup_tile_sources = [&](const TileCoord& t, int in_rows) {
+        c_cb0 = t.mt0 / kTM;
+        const int ih0 = t.oh0 - 1, iw0 = t.ow0 - 1;
+#pragma unroll
+        for (int k = 0; k < kGrXPerWave; ++k) {
+            const int c = ((k * 4 + wave) * 64 + lane);
+            const int pos = c >> 2, q = c & 3;
+            const int pr = pos / kLW, pc = pos - pr * kLW;
+            const int ih = ih0 + pr, iw = iw0 + pc;
+            const bool inside = pr < in_rows && ih >= 0 && ih < H && iw >= 0 && iw < W;
+            const int off = ((t.n_img * H + ih) * W + iw) * (Ci >> 3) + q;  // 16-byte chunks: fits 31 bits (launcher)
+            x_ptr[k] = inside ? (const char*)x + (int64_t)off * 16 : zeros;
+        }
+    };
+    // One copy instruction (64 lanes x 16 bytes) of stage `stage` of the copy state's tile into region `par`: slots
+    // 0 .. kGrAPerWave-1 move weight fragments (a_src0/1: the two blocks' fragments of that stage), the rest activations.
+    auto issue_copy_slot = [&](int cslot, int stage, int par, int a_count, const char* a_src0, const char* a_src1) {
+        char* region = smem + par * kGrRegion;
+        if (cslot < kGrAPerWave) {
+            // piece kk = 4 * cslot + wave of the region is (step, block, fragment) = (cslot / 2, cslot % 2, wave)
+            const int kk = cslot * 4 + wave;
+            if (kk < a_count)  // wave-uniform
+                copy16_to_lds(((cslot & 1) ? a_src1 : a_src0) + ((cslot >> 1) * kTM + wave) * kFrag, region + kk * 1024);
+        } else {
+            const int k = cslot - kGrAPerWave;
+            copy16_to_lds(x_ptr[k] + stage * 64, region + kGrABytes + (k * 4 + wave) * 1024);
+        }
+    };
+
+    const int nn = lane & 15, qq = lane >> 4;
+    f32x4 acc[2 * kTM][kTall];
+    u32x4 a_cur[kTM], a_nxt[kTM], b_cur[kTall], b_nxt[kTall];
+    int gpar = 0;  // region that holds the stage about to be multiplied
+
+    // ---- one tile of TN rows per wave ----
+    auto run_tile = [&](auto tn_tag, const TileCoord& cur, bool has_next, const TileCoord& nxt, bool nxt_tall) {
+        constexpr int TN = decltype(tn_tag)::value;
+        const int xrd = ((wave * TN) * kLW + nn) * kPosBytes + qq * 16;
+        const int nxt_in_rows = nxt_tall ? 4 * kTall + 2 : 4 * kShort + 2;
+        const int cb0 = cur.mt0 / kTM;
+
+        // the tile's step counts and tap offsets -> LDS (nobody reads the previous tile's any more: its last
+        // stage ended at a barrier)
+        for (int e = tid; e < stages * 80; e += 256) {
+            const int stage = e / 80, i = e % 80, half = i / 40, r = i % 40;
+            const bool there = half == 0 || cb0 + 1 < cblocks;
+            const GatherHeader* h = headers + (size_t)stage * cblocks + cb0 + (there ? half : 0);
+            if (r < 36) {
+                const int t = h->tap[r / 9][r % 9];
+                lds_off[((stage * 2 + half) * 4 + r / 9) * kGrOffPitch + r % 9] = (int16_t)(((t / 3) * kLW + (t % 3)) * kPosBytes);
+            } else if (r == 36 && half == 0) {
+                int st = pair_steps_lane(cb0, stage);
+                if (stage == 0) st = max(st & 0xff, 1) | (max(st >> 8, 1) << 8);  // every accumulator starts with step 0
+                lds_steps[stage] = st;
+            }
+        }
+        __syncthreads();
+
+        // A stage's tap offsets (steps 0..7 of both blocks, this lane's quarter) are read one stage ahead into
+        // registers, so that no operand read waits for a table look-up.
+        auto load_offsets = [&](int stage, u32x4 (&pk)[2]) {
+#pragma unroll
+            for (int half = 0; half < 2; ++half)
+                pk[half] = *(const u32x4*)(lds_off + ((stage * 2 + half) * 4 + qq) * kGrOffPitch);
+        };
+        auto offset_of = [](const u32x4 (&pk)[2], int half, int st) -> int {  // st < 8, compile-time after unrolling
+            return (int)((pk[half][st >> 1] >> ((st & 1) * 16)) & 0xffffu);
+        };
+        // operands of a half-step: the weight fragments of (step, block) and, per output row, this quarter's tap
+        auto load_operands = [&](int par, int st, int half, int off, u32x4 (&a)[kTM], u32x4 (&b)[kTall]) {
+            const char* A = smem + par * kGrRegion + lane * 16 + ((st * 2 + half) * kTM) * kFrag;
+            const char* X = smem + par * kGrRegion + kGrABytes + xrd + off;
+#pragma unroll
+            for (int m = 0; m < kTM; ++m) a[m] = *(const u32x4*)(A + m * kFrag);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) b[j] = *(const u32x4*)(X + j * kLW * kPosBytes);
+        };
+        u32x4 off_cur[2], off_nxt[2];
+        load_offsets(0, off_cur);
+        load_operands(gpar, 0, 0, offset_of(off_cur, 0, 0), a_cur, b_cur);
+
+        auto run_stage = [&](auto first_tag, auto body_tag, int stage) {
+            constexpr bool FIRST = decltype(first_tag)::value;
+            constexpr int BODY = decltype(body_tag)::value;  // steps of the branch-free body, 0: the general body
+            const int st = __builtin_amdgcn_readfirstlane(lds_steps[stage]);
+            const int st0 = st & 0xff, st1 = st >> 8, steps = max(st0, st1);
+            const bool last_stage = stage + 1 == stages;
+            const int copy_stage = last_stage ? 0 : stage + 1;
+            if (last_stage && has_next) setup_tile_sources(nxt, nxt_in_rows);
+            // (in the very last stage of the last tile nothing is left to fetch; stage 0 of the same tile is fetched
+            // again into the free region, which keeps this code free of branches)
+            const int a_count = copies_of(last_stage ? pair_steps(c_cb0, 0) : __builtin_amdgcn_readfirstlane(lds_steps[stage + 1]), last_stage);
+            if (!last_stage) load_offsets(stage + 1, off_nxt);
+            // sources of the next stage's weight fragments, per block of the pair (no second block: the first one
+            // again, never stored)
+            const char* const a_src0 = wfrag + ((int64_t)copy_stage * cblocks + c_cb0) * kBlockBytes + lane * 16;
+            const char* const a_src1 = a_src0 + (c_cb0 + 1 < cblocks ? kBlockBytes : 0);
+            auto multiply = [&](auto half_tag, auto first_step_tag, const u32x4 (&a)[kTM], const u32x4 (&b)[kTall]) {
+                constexpr int half = decltype(half_tag)::value;
+#pragma unroll
+                for (int m = 0; m < kTM; ++m)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        if constexpr (decltype(first_step_tag)::value) Mat<T>::dense_first(a[m], b[j], acc[half * kTM + m][j]);
+                        else Mat<T>::dense(a[m], b[j], acc[half * kTM + m][j]);
+                    }
+            };
+            // Stage hand-over: every copy of the next stage issued, this wave's landed and its reads of this region
+            // done, a bare barrier, then the next stage's first operands (they arrive under the matrix instructions
+            // that follow).  At a tile's end the next tile reads its own first operands (other tap lists).
+            auto hand_over = [&](int first_unissued) {
+                static_for<kGrCopySlots>([&](auto C) {
+                    constexpr int c = decltype(C)::value;
+                    if (c >= first_unissued) issue_copy_slot(c, copy_stage, gpar ^ 1, a_count, a_src0, a_src1);
+                });
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+                if (!last_stage) load_operands(gpar ^ 1, 0, 0, offset_of(off_nxt, 0, 0), a_cur, b_cur);
+            };
+            // A stage whose two blocks take the same number of steps, at most kGrSteps -- every stage, when the
+            // patterns are shared the way the packer hopes -- runs a body without a single branch: STEPS is a
+            // compile-time constant, the copies of the next stage are dealt over the half-steps before the last and
+            // the hand-over sits in front of the last half-step's matrix instructions.  (With branches between the
+            // half-steps the compiler's wait-count bookkeeping falls back to waiting for every outstanding LDS read in
+            // front of each block of matrix instructions, which exposes the operand reads' latency twelve times a
+            // stage.)
+            auto static_body = [&](auto steps_tag) {
+                constexpr int STEPS = decltype(steps_tag)::value;
+                constexpr int HS = 2 * STEPS - 1;  // half-steps that carry copies
+                // matrix instructions of one half-step with copy slots [c0, c1) issued between them
+                auto half_step = [&](auto half_tag, auto first_step_tag, auto c0_tag, auto c1_tag, const u32x4 (&a)[kTM],
+                                     const u32x4 (&b)[kTall]) {
+                    constexpr int half = decltype(half_tag)::value, c0 = decltype(c0_tag)::value, c1 = decltype(c1_tag)::value;
+                    constexpr int n = c1 - c0, total = kTM * TN;
+                    static_for<total>([&](auto I) {
+                        constexpr int i = decltype(I)::value, m = i / TN, j = i % TN;
+                        if constexpr (decltype(first_step_tag)::value) Mat<T>::dense_first(a[m], b[j], acc[half * kTM + m][j]);
+                        else Mat<T>::dense(a[m], b[j], acc[half * kTM + m][j]);
+                        // copy k of this half-step goes behind matrix instruction k * total / n (several per instruction
+                        // when a short stage has more copies than matrix instructions in a half-step)
+                        static_for<(n > 0 ? n : 0)>([&](auto K) {
+                            constexpr int k = decltype(K)::value;
+                            if constexpr (i == k * total / (n > 0 ? n : 1)) issue_copy_slot(c0 + k, copy_stage, gpar ^ 1, a_count, a_src0, a_src1);
+                        });
+                        __builtin_amdgcn_sched_barrier(0);
+                    });
+                };
+                static_for<STEPS>([&](auto S) {
+                    constexpr int s = decltype(S)::value;
+                    constexpr int h0 = 2 * s, h1 = 2 * s + 1;
+                    load_operands(gpar, s, 1, offset_of(off_cur, 1, s), a_nxt, b_nxt);
+                    half_step(std::integral_constant<int, 0>{}, std::integral_constant<bool, FIRST && s == 0>{},
+                              std::integral_constant<int, h0 * kGrCopySlots / HS>{}, std::integral_constant<int, (h0 + 1) * kGrCopySlots / HS>{},
+                              a_cur, b_cur);
+                    if constexpr (s + 1 == STEPS) {
+                        hand_over(kGrCopySlots);  // (every copy has been issued)
+                        half_step(std::integral_constant<int, 1>{}, std::integral_constant<bool, FIRST && s == 0>{},
+                                  std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, a_nxt, b_nxt);
+                    } else {
+                        load_operands(gpar, s + 1, 0, offset_of(off_cur, 0, s + 1), a_cur, b_cur);
+                        half_step(std::integral_constant<int, 1>{}, std::integral_constant<bool, FIRST && s == 0>{},
+                                  std::integral_constant<int, h1 * kGrCopySlots / HS>{}, std::integral_constant<int, (h1 + 1) * kGrCopySlots / HS>{},
+                                  a_nxt, b_nxt);
+                    }
+                });
+            };
+            // The general body, for tiles whose patterns are not shared the way the packer hopes (any step counts, up
+            // to 9, different between the blocks): plain and slow.  Every copy of the next stage first; then a loop
+            // over the steps with the weight fragments read from global memory (so that it does not matter how many
+            // of them the region holds) and the matrix instructions unconditional: a block that has no step s
+            // multiplies by zero, which keeps the accumulators out of every branch.
+            auto generic_body = [&]() {
+                static_for<kGrCopySlots>([&](auto C) { issue_copy_slot(decltype(C)::value, copy_stage, gpar ^ 1, a_count, a_src0, a_src1); });
+                const char* X = smem + gpar * kGrRegion + kGrABytes + xrd;
+                auto step = [&](auto first_step_tag, int st_i) {
+                    static_for<2>([&](auto HF) {
+                        constexpr int half = decltype(HF)::value;
+                        const int cb = c_cb0_of_tile(cb0, half, cblocks);
+                        const char* Ag = wfrag + ((int64_t)stage * cblocks + cb) * kBlockBytes + (st_i * kTM) * kFrag + lane * 16;
+                        u32x4 a[kTM], b[kTall];
+#pragma unroll
+                        for (int m = 0; m < kTM; ++m) a[m] = u32x4{0, 0, 0, 0};
+                        if (st_i < (half ? st1 : st0)) {  // uniform; fragments past a block's own steps are not written
+#pragma unroll
+                            for (int m = 0; m < kTM; ++m) a[m] = *(const u32x4*)(Ag + m * kFrag);
+                        }
+                        const int off = lds_off[((stage * 2 + half) * 4 + qq) * kGrOffPitch + st_i];
+#pragma unroll
+                        for (int j = 0; j < TN; ++j) b[j] = *(const u32x4*)(X + j * kLW * kPosBytes + off);
+                        multiply(HF, first_step_tag, a, b);
+                    });
+                };
+                step(std::integral_constant<bool, FIRST>{}, 0);
+                for (int st_i = 1; st_i < steps; ++st_i) step(std::false_type{}, st_i);
+                hand_over(kGrCopySlots);
+            };
+            if constexpr (BODY > 0) static_body(body_tag);
+            else generic_body();
+            off_cur[0] = off_nxt[0];
+            off_cur[1] = off_nxt[1];
+            gpar ^= 1;
+        };
+        // One path per tile: the stages and the epilogue for a given body.  (Choosing the body per stage would join
+        // the paths while the accumulators are live; the compiler then moves accumulators between the registers the
+        // paths happen to use, right behind matrix instructions whose latency it does not know.)
+        auto tile_path = [&](auto body_tag) {
+            run_stage(std::true_type{}, body_tag, 0);
+            for (int stage = 1; stage < stages; ++stage) run_stage(std::false_type{}, body_tag, stage);
+
+            // the last matrix instructions must have written their accumulators before anything reads them
+            asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+            // ---- epilogue: a lane holds, per block of 64 channels, 16 consecutive channels of column nn of each of
+            // its rows (the packer dealt the rows that way): 32 contiguous bytes per lane and block ----
+            {
+                int lane_e = lane;
+                asm volatile("" : "+v"(lane_e));
+                const int nn_e = lane_e & 15, qq_e = lane_e >> 4;
+                const int row_first = cur.oh0 + wave * TN;
+                const int64_t pos_tile = ((int64_t)cur.n_img * Ho + cur.oh0) * Wo + cur.ow0;
+                TO* const y_tile = y + pos_tile * ldy;
+                const bool col_inside = cur.ow0 + nn_e < Wo;
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const bool inside = col_inside && row_first + j < Ho;
+                    TO* yp = y_tile + ((wave * TN + j) * Wo + nn_e) * ldy + 16 * cur.mt0 + 16 * qq_e;
+#pragma unroll
+                    for (int half = 0; half < 2; ++half) {
+                        uint32_t o[8];
+#pragma unroll
+                        for (int m = 0; m < kTM; ++m) {
+                            float r[4];
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) asm("v_max_f32 %0, %1, %2" : "=v"(r[e]) : "v"(acc[half * kTM + m][j][e]), "v"(relu_floor));
+                            o[2 * m] = pack2_from_f32<TO>(r[0], r[1]);
+                            o[2 * m + 1] = pack2_from_f32<TO>(r[2], r[3]);
+                        }
+                        if (inside && 16 * (cur.mt0 + 4 * half) + 16 * qq_e < Co) {
+                            *(u32x4*)(yp + 64 * half) = u32x4{o[0], o[1], o[2], o[3]};
+                            *(u32x4*)(yp + 64 * half + 8) = u32x4{o[4], o[5], o[6], o[7]};
+                        }
+                    }
+                }
+            }
+        };
+        // every stage with the same number of steps in both blocks (one table entry per lane)?
+        const int st_first = __builtin_amdgcn_readfirstlane(lds_steps[0]);
+        const int st_mine = lds_steps[lane < stages ? lane : 0];
+        const bool uniform_steps = __ballot(st_mine != st_first) == 0 && (st_first & 0xff) == (st_first >> 8);
+        switch (uniform_steps ? (st_first & 0xff) : 0) {
+        case 1: tile_path(std::integral_constant<int, 1>{}); break;
+        case 2: tile_path(std::integral_constant<int, 2>{}); break;
+        case 3: tile_path(std::integral_constant<int, 3>{}); break;
+        case 4: tile_path(std::integral_constant<int, 4>{}); break;
+        case 5: tile_path(std::integral_constant<int, 5>{}); break;
+        default: tile_path(std::integral_constant<int, 0>{}); break;
+        }
+    };
+
+    // ---- walk the entries ----
+    bool cur_tall = tall_next < tall_end;
+    TileCoord cur = decode_entry(plan, cur_tall, cur_tall ? tall_next : short_next);
+    if (cur_tall) tall_next += slots;
+    else short_next += slots;
+    setup_tile_sources(cur, cur_tall ? 4 * kTall + 2 : 4 * kShort + 2);
+    {
+        const int a_count = copies_of(pair_steps(c_cb0, 0), true);
+        const char* const a_src0 = wfrag + (int64_t)c_cb0 * kBlockBytes + lane * 16;
+        const char* const a_src1 = a_src0 + (c_cb0 + 1 < cblocks ? kBlockBytes : 0);
+#pragma unroll
+        for (int c = 0; c < kGrCopySlots; ++c) issue_copy_slot(c, 0, 0, a_count, a_src0, a_src1);
+    }
+    bool first_tile = true;
+    for (;;) {
+        const bool nxt_tall = tall_next < tall_end;
+        const bool has_next = nxt_tall || short_next < short_end;
+        TileCoord nxt = cur;
+        if (has_next) {
+            nxt = decode_entry(plan, nxt_tall, nxt_tall ? tall_next : short_next);
+            if (nxt_tall) tall_next += slots;
+            else short_next += slots;
+        }
+        if (first_tile) {
+            __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's copies have landed in LDS
+            __syncthreads();                     // ... and everybody's
+            first_tile = false;
+        }
+        if (cur_tall) run_tile(std::integral_constant<int, kTall>{}, cur, has_next, nxt, nxt_tall);
+        else run_tile(std::integral_constant<int, kShort>{}, cur, has_next, nxt, nxt_tall);
+        if (!has_next) break;
+        cur = nxt;
+        cur_tall = nxt_tall;
+    }
+}
+
 template <typename T, typename TO, int S>
 rtoss_status launch_gather(const rtoss_wdesc& d, const ConvParams& c, const char* section, const void* x, void* y, hipStream_t s)
 {
@@ -277,9 +646,42 @@ rtoss_status launch_gather(const rtoss_wdesc& d, const ConvParams& c, const char
     return check_hip(hipGetLastError(), "conv3x3 gather launch");
 }
 
+// Large stride-1 layers with 16-bit output and no fused output stage beyond ReLU take the pipelined kernel (the
+// same test of size as for the pipelined 2-of-4 kernel: enough 128-channel tiles to give most compute units one).
+inline bool takes_pipelined_gather(const rtoss_wdesc& d, const ConvParams& c)
+{
+    if (c.stride != 1 || d.Co <= 64 || d.Ci <= 64 || c.out_dt == RTOSS_F32) return false;
+    if (c.ep.scale || c.ep.bias || c.ep.residual || c.ep.act > 1) return false;
+    const int64_t tiles8 = (int64_t)((c.H + 15) / 16) * ((c.W + 15) / 16) * c.N * (((d.Co + 15) / 16 + 7) / 8);
+    return tiles8 >= 200;
+}
+
+template <typename T>
+rtoss_status launch_gather_rows(const rtoss_wdesc& d, const ConvParams& c, const char* section, const void* x, void* y, hipStream_t s)
+{
+    auto kern = conv3x3_gather_rows_kernel<T, T>;
+    static LaunchOnce lds_once;  // per instantiation
+    if (rtoss_status st = ensure_dynamic_lds((const void*)kern, kGrSmem, lds_once, "conv3x3 gather shared memory attribute")) return st;
+    DeviceInfo dev;
+    if (rtoss_status st = current_device(&dev)) return st;
+    const int co_blocks = ((d.Co + 15) / 16 + kRowsTM - 1) / kRowsTM;
+    if ((int64_t)c.N * c.H * c.W * d.Ci / 8 > 0x7fffffff) return fail(RTOSS_ESHAPE, "conv: input too large for 32-bit chunk offsets");
+    if ((int64_t)c.N * ((c.W + 15) / 16) * ((c.H + 15) / 16 + 1) * co_blocks > 0x3fffffff) return fail(RTOSS_ESHAPE, "conv: too many tiles");
+    int slots = 0;
+    const RowPlan plan = plan_rows_for_device(c.N, c.H, c.W, co_blocks, d.Ci / 32, dev.cus, &slots);
+    const char* frags = section + header_bytes(d);
+    const float relu_floor = c.ep.act == 1 ? 0.f : -__builtin_inff();
+    dim3 grid((unsigned)(slots * 8)), block(256);
+    kern<<<grid, block, kGrSmem, s>>>((const T*)x, (T*)y, (const GatherHeader*)section, frags, frags + frag_bytes(d), c.H, c.W, d.Ci,
+                                      d.Co, channel_blocks(d.Co), plan, relu_floor, c.ep.ldy);
+    return check_hip(hipGetLastError(), "conv3x3 gather rows launch");
+}
+
 template <typename T, typename TO>
 rtoss_status launch_typed(const rtoss_wdesc& d, const ConvParams& c, const char* section, const void* x, void* y, hipStream_t s)
 {
+    if constexpr (std::is_same<T, TO>::value)
+        if (takes_pipelined_gather(d, c)) return launch_gather_rows<T>(d, c, section, x, y, s);
     if (c.stride == 1) return launch_gather<T, TO, 1>(d, c, section, x, y, s);
     return launch_gather<T, TO, 2>(d, c, section, x, y, s);
 }

@@ -34,56 +34,12 @@
 #include "dtypes.h"
 #include "epilogue.h"
 #include "mma.h"
+#include "rows_plan.h"
 #include "sparse_frag.h"
 
 namespace rtoss {
 
 namespace {
-
-constexpr int kTall = 5, kShort = 4;  // output rows per wave of the two tile classes
-constexpr int kTM = 8;                // channel tiles per workgroup (128 channels)
-constexpr int kLW = 18;               // LDS row pitch of the activation tile in positions: 16 columns + halo
-constexpr int kPosBytes = 64;         // one position of a stage: 32 channels x 2 bytes
-
-// How the rows of the strips are cut into tiles, and how the tiles are dealt to the workgroups.
-// A strip is 16 output columns of one image.  Strips [0, sa) are cut into a5 tall tiles followed by a4
-// short ones, the other strips into b5 tall and b4 short.  A list entry is (tile, channel block) with the
-// channel block fastest; each class has its own list, cut into 8 contiguous ranges, one per XCD, so that
-// the channel blocks of a tile, and neighbouring tiles, meet in one L2.
-struct RowPlan {
-    int col_strips, co_blocks, strips;
-    int sa, a5, a4, b5, b4;
-    int tall_total, tall_per_xcd, short_total, short_per_xcd;
-};
-
-struct TileCoord {
-    int n_img, mt0, oh0, ow0;
-};
-
-__device__ __forceinline__ TileCoord decode_entry(const RowPlan& p, bool tall, int e)
-{
-    const int na = tall ? p.a5 : p.a4, nb = tall ? p.b5 : p.b4;
-    const int first_a = na * p.co_blocks * p.sa;  // entries of the strips cut the first way
-    int strip, r, row0;
-    if (e < first_a) {
-        strip = e / (na * p.co_blocks);
-        r = e - strip * (na * p.co_blocks);
-        row0 = tall ? 0 : p.a5 * (4 * kTall);
-    } else {
-        const int e2 = e - first_a;
-        const int s2 = e2 / (nb * p.co_blocks);
-        strip = p.sa + s2;
-        r = e2 - s2 * (nb * p.co_blocks);
-        row0 = tall ? 0 : p.b5 * (4 * kTall);
-    }
-    const int tile = r / p.co_blocks, cblk = r - tile * p.co_blocks;
-    TileCoord t;
-    t.n_img = strip / p.col_strips;
-    t.ow0 = (strip - t.n_img * p.col_strips) * 16;
-    t.oh0 = row0 + tile * (tall ? 4 * kTall : 4 * kShort);
-    t.mt0 = cblk * kTM;
-    return t;
-}
 
 // Which unit of a stage reads and permutes what (TN = rows per wave).
 //   prologue (issued inside the previous stage's last unit): R[1..TN][1], R[0..3][0], R[0..3][2]
@@ -134,7 +90,7 @@ __global__ __launch_bounds__(256, 1) void conv3x3_rows_kernel(const T* __restric
                                                               const char* __restrict__ zeros, int H, int W, int Ci,
                                                               int Co, int m_tiles_total, RowPlan plan, Epilogue ep)
 {
-    constexpr int TM = kTM;
+    constexpr int TM = kRowsTM;
     constexpr int A_BYTES = TM * kTileBytes;
     constexpr int A_WAVE_COPIES = A_BYTES / 1024;  // 64 lanes x 16 B per copy instruction
     constexpr int A_PER_WAVE = A_WAVE_COPIES / 4;
@@ -526,12 +482,16 @@ __global__ __launch_bounds__(256, 1) void conv3x3_rows_kernel(const T* __restric
     }
 }
 
+}  // namespace
+
 // ---------------------------------------------------------------------------------------------------------
 // Host: cutting the rows into tiles.
 // ---------------------------------------------------------------------------------------------------------
 // Relative cost of one tile of TN rows per wave over `stages` stages: a stage costs a fixed part (weight
 // operand reads, hand-over) plus a part per row; the epilogue and the prologue of a tile scale with its
 // rows.  (Fitted to per-workgroup time stamps of both tile classes on a 256 -> 256 channel layer.)
+namespace {
+
 inline double tile_cost(int tn, int stages) { return stages * (tn + 0.7) + 1.5 * tn; }
 
 struct PlanKey {
@@ -578,6 +538,8 @@ RowPlan make_plan(int N, int H, int W, int co_blocks, int sa, int a5, int a4, in
     return p;
 }
 
+}  // namespace
+
 // Searches the cuts (n5 tall + n4 short tiles covering H rows with no tile to spare) for the two strip
 // classes and the number of strips of the first class; results are remembered per launch shape.
 RowPlan plan_rows(int N, int H, int W, int co_blocks, int stages, int slots)
@@ -622,25 +584,35 @@ RowPlan plan_rows(int N, int H, int W, int co_blocks, int stages, int slots)
     return best;
 }
 
+RowPlan plan_rows_for_device(int N, int H, int W, int co_blocks, int stages, int cus, int* slots_out)
+{
+    // one workgroup per compute unit (a workgroup owns nearly all of a unit's LDS)
+    const int full = std::max(8, cus) / 8;
+    RowPlan plan = plan_rows(N, H, W, co_blocks, stages, full);
+    // (fewer entries than workgroups: launch only as many slots per XCD as the longer list needs)
+    const int slots = std::max(1, std::min(full, std::max(plan.tall_per_xcd, plan.short_per_xcd)));
+    if (slots != full) plan = plan_rows(N, H, W, co_blocks, stages, slots);
+    *slots_out = slots;
+    return plan;
+}
+
+namespace {
+
 template <typename T, typename TO, bool FUSED>
 rtoss_status launch_rows(const rtoss_wdesc& d, const ConvParams& c, const char* wfrag, const void* x, void* y, hipStream_t s)
 {
     constexpr int x_copies_per_wave = ((((4 * kTall + 2) * kLW * 4 + 63) / 64) + 3) / 4;
-    const size_t smem = 2 * ((size_t)kTM * kTileBytes + (size_t)x_copies_per_wave * 4096);
+    const size_t smem = 2 * ((size_t)kRowsTM * kTileBytes + (size_t)x_copies_per_wave * 4096);
     auto kern = conv3x3_rows_kernel<T, TO, FUSED>;
     static LaunchOnce lds_once;  // per instantiation
     if (rtoss_status st = ensure_dynamic_lds((const void*)kern, smem, lds_once, "conv3x3 shared memory attribute")) return st;
     DeviceInfo dev;
     if (rtoss_status st = current_device(&dev)) return st;
-    const int co_blocks = ((d.Co + 15) / 16 + kTM - 1) / kTM;
+    const int co_blocks = ((d.Co + 15) / 16 + kRowsTM - 1) / kRowsTM;
     if ((int64_t)c.N * c.H * c.W * d.Ci / 8 > 0x7fffffff) return fail(RTOSS_ESHAPE, "conv: input too large for 32-bit chunk offsets");
     if ((int64_t)c.N * ((c.W + 15) / 16) * ((c.H + 15) / 16 + 1) * co_blocks > 0x3fffffff) return fail(RTOSS_ESHAPE, "conv: too many tiles");
-    // one workgroup per compute unit (a workgroup owns nearly all of a unit's LDS)
-    int slots = std::max(8, dev.cus) / 8;
-    RowPlan plan = plan_rows(c.N, c.H, c.W, co_blocks, d.Ci / 32, slots);
-    // (fewer entries than workgroups: launch only as many slots per XCD as the longer list needs)
-    slots = std::max(1, std::min(slots, std::max(plan.tall_per_xcd, plan.short_per_xcd)));
-    if (slots * 8 != std::max(8, dev.cus) / 8 * 8) plan = plan_rows(c.N, c.H, c.W, co_blocks, d.Ci / 32, slots);
+    int slots = 0;
+    const RowPlan plan = plan_rows_for_device(c.N, c.H, c.W, co_blocks, d.Ci / 32, dev.cus, &slots);
     dim3 grid((unsigned)(slots * 8)), block(256);
     kern<<<grid, block, smem, s>>>((const T*)x, (TO*)y, wfrag, wfrag + fragment_bytes(d), c.H, c.W, d.Ci, d.Co,
                                    padded_m_tiles(d.Co), plan, c.ep);

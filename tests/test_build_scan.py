@@ -38,3 +38,16 @@ def test_distance_other_registers_and_compiler_emitted_instructions_pass(tmp_pat
     assert _scan(tmp_path, plain) == []
     # the destination of the matrix instruction is not a source
     assert _scan(tmp_path, "\tv_accvgpr_read_b32 v0, a200\n" + MFMA) == []
+
+
+def test_accumulator_moves_right_behind_an_asm_matrix_instruction_are_flagged(tmp_path):
+    # the compiler copying an accumulator that the asm instruction in front is still writing
+    assert len(_scan(tmp_path, MFMA + "\ts_nop 0\n\tv_accvgpr_read_b32 v9, a2\n")) == 1
+    assert len(_scan(tmp_path, MFMA + "\tv_accvgpr_mov_b32 a200, a3\n")) == 1
+    assert len(_scan(tmp_path, MFMA + "\tv_accvgpr_write_b32 a0, v9\n")) == 1
+    assert len(_scan(tmp_path, MFMA + "\tscratch_load_dwordx4 a[0:3], off, off offset:660\n")) == 1
+    # other accumulators, or the same ones after the instruction has drained (two s_nop 15, as in front of the epilogues)
+    assert _scan(tmp_path, MFMA + "\tv_accvgpr_read_b32 v9, a8\n") == []
+    assert _scan(tmp_path, MFMA + "\ts_nop 15\n\ts_nop 15\n\tv_accvgpr_read_b32 v9, a2\n") == []
+    # the next matrix instruction on the same accumulator is the hardware's business
+    assert _scan(tmp_path, MFMA + MFMA) == []

@@ -22,6 +22,11 @@ def _indices(kind, rng, Co, Ci, P, w_parent64, masks):
         return np.repeat(np.repeat(blocks, 64, 0)[:Co], 8, 1)
     if kind == "filter":    # one pattern per output channel (not coherent in the sense of the kernel: up to 9 steps)
         return rng.integers(0, P, Co)[:, None].repeat(Ci, 1)
+    if kind == "uneven":    # even blocks of 64 output channels share per run, odd blocks have independent patterns
+        idx = np.repeat(rng.integers(0, P, Ci // 8), 8)[None, :].repeat(Co, 0)
+        for b0 in range(64, Co, 128):
+            idx[b0:b0 + 64] = rng.integers(0, P, idx[b0:b0 + 64].shape)
+        return idx
     if kind == "parent":    # the parent layer's own selection, kernel by kernel (independent patterns)
         return oracle.select(w_parent64, masks).reshape(Co, Ci)
     raise ValueError(kind)
@@ -34,10 +39,14 @@ CASES = [
     (wl.F16, 1, 256, 144, 20, 24, 1, 3, False),
     (wl.BF16, 2, 64, 128, 37, 41, 2, 3, True),
     (wl.F16, 1, 32, 16, 5, 7, 2, 4, False),
+    # large stride-1 layers: the pipelined kernel (tall and short tiles, ragged last strip, a channel-block pair
+    # without its second block; independent patterns run past the steps it keeps in LDS)
+    (wl.BF16, 13, 96, 144, 50, 64, 1, 3, True),
+    (wl.F16, 10, 160, 128, 52, 70, 1, 2, False),
 ]
 
 
-@pytest.mark.parametrize("kind", ["run", "block", "filter", "parent"])
+@pytest.mark.parametrize("kind", ["run", "block", "filter", "parent", "uneven"])
 @pytest.mark.parametrize("case", CASES, ids=lambda c: "dt%d_%d-%d_%dx%d_s%d_k%d" % (c[0], c[2], c[3], c[4], c[5], c[6], c[7]))
 def test_coherent_path_matches_the_oracle(case, kind):
     dt, N, Ci, Co, H, W, stride, k, relu = case
