@@ -279,9 +279,8 @@ constexpr int kGrXArea = kGrXPerWave * 4 * 1024;
 constexpr int kGrRegion = kGrABytes + kGrXArea;
 constexpr int kGrAPerWave = kGrABytes / 1024 / 4;
 constexpr int kGrCopySlots = kGrAPerWave + kGrXPerWave;
-constexpr int kGrOffPitch = 16;  // int16 entries per (stage, block, quarter): one 16-byte read fetches steps 0..7
+constexpr int kGrOffPitch = 8;  // int16 entries per (stage, block, quarter): steps 0..7, one 16-byte read
 constexpr size_t kGrSmem = 2 * (size_t)kGrRegion + kMaxStages * 4 + (size_t)kMaxStages * 2 * 4 * kGrOffPitch * 2;
-static_assert(kGrCopySlots <= 3 * 2 * 3, "three copies per half-step must cover a stage within three steps");
 
 template <typename T, typename TO>
 __global__ __launch_bounds__(256, 1) void conv3x3_gather_rows_kernel(const T* __restrict__ x, TO* __restrict__ y,
@@ -317,15 +316,6 @@ __global__ __launch_bounds__(256, 1) void conv3x3_gather_rows_kernel(const T* __
         s1 = s1 > 9u ? 9u : s1;
         return (int)(s0 | (s1 << 8));
     };
-    auto pair_steps = [&](int cb0, int stage) -> int {  // uniform arguments only
-        return __builtin_amdgcn_readfirstlane(pair_steps_lane(cb0, stage));
-    };
-    auto copies_of = [](int st, bool first_stage) {  // 1 KB pieces of the weight fragments of a stage kept in LDS
-        int n = max(st & 0xff, st >> 8);
-        if (first_stage) n = max(n, 1);
-        return min(n, kGrSteps) * 2 * kTM;
-    };
-
     // ---- copy state: the tile whose stages are being fetched ----
     int c_cb0 = 0;
     const char* x_ptr[kGrXPerWave];
@@ -345,13 +335,15 @@ __global__ __launch_bounds__(256, 1) void conv3x3_gather_rows_kernel(const T* __
     };
     // One copy instruction (64 lanes x 16 bytes) of stage `stage` of the copy state's tile into region `par`: slots
     // 0 .. kGrAPerWave-1 move weight fragments (a_src0/1: the two blocks' fragments of that stage), the rest activations.
-    auto issue_copy_slot = [&](int cslot, int stage, int par, int a_count, const char* a_src0, const char* a_src1) {
+    auto issue_copy_slot = [&](int cslot, int stage, int par, const char* a_src0, const char* a_src1) {
         char* region = smem + par * kGrRegion;
         if (cslot < kGrAPerWave) {
-            // piece kk = 4 * cslot + wave of the region is (step, block, fragment) = (cslot / 2, cslot % 2, wave)
+            // piece kk = 4 * cslot + wave of the region is (step, block, fragment) = (cslot / 2, cslot % 2, wave).  All
+            // kGrSteps steps are copied whatever the stage's own count (what lies behind a block's last step in the
+            // blob is never multiplied): a count would put a branch around every copy, and branches between the
+            // matrix instructions cost more than the surplus copies.
             const int kk = cslot * 4 + wave;
-            if (kk < a_count)  // wave-uniform
-                copy16_to_lds(((cslot & 1) ? a_src1 : a_src0) + ((cslot >> 1) * kTM + wave) * kFrag, region + kk * 1024);
+            copy16_to_lds(((cslot & 1) ? a_src1 : a_src0) + ((cslot >> 1) * kTM + wave) * kFrag, region + kk * 1024);
         } else {
             const int k = cslot - kGrAPerWave;
             copy16_to_lds(x_ptr[k] + stage * 64, region + kGrABytes + (k * 4 + wave) * 1024);
@@ -363,6 +355,47 @@ __global__ __launch_bounds__(256, 1) void conv3x3_gather_rows_kernel(const T* __
     u32x4 a_cur[kTM], a_nxt[kTM], b_cur[kTall], b_nxt[kTall];
     int gpar = 0;  // region that holds the stage about to be multiplied
 
+    // A tile's table entries (stage, block of the pair, quarter): the offsets in the activation tile of the taps of
+    // steps 0..7, and per stage the two step counts.  A thread fetches up to two entries from the headers in global
+    // memory into registers (prefetch_headers, a tile ahead) and writes them to LDS when the tile starts.
+    u32x4 hdr_off[2];
+    int hdr_steps[2];
+    auto prefetch_headers = [&](int cb0) {
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const int e = tid + 256 * r;
+            hdr_off[r] = u32x4{0, 0, 0, 0};
+            hdr_steps[r] = 0;
+            if (e < stages * 8) {
+                const int stage = e >> 3, half = (e >> 2) & 1, q = e & 3;
+                const bool there = half == 0 || cb0 + 1 < cblocks;
+                const GatherHeader* h = headers + (size_t)stage * cblocks + cb0 + (there ? half : 0);
+                uint32_t o[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int t = h->tap[q][i];
+                    o[i] = (uint32_t)(((t / 3) * kLW + (t % 3)) * kPosBytes);
+                }
+                hdr_off[r] = u32x4{o[0] | (o[1] << 16), o[2] | (o[3] << 16), o[4] | (o[5] << 16), o[6] | (o[7] << 16)};
+                if (half == 0 && q == 0) {
+                    int st = pair_steps_lane(cb0, stage);
+                    if (stage == 0) st = max(st & 0xff, 1) | (max(st >> 8, 1) << 8);  // every accumulator starts with step 0
+                    hdr_steps[r] = st;
+                }
+            }
+        }
+    };
+    auto store_headers = [&]() {
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const int e = tid + 256 * r;
+            if (e < stages * 8) {
+                *(u32x4*)(lds_off + e * kGrOffPitch) = hdr_off[r];
+                if ((e & 7) == 0) lds_steps[e >> 3] = hdr_steps[r];
+            }
+        }
+    };
+
     // ---- one tile of TN rows per wave ----
     auto run_tile = [&](auto tn_tag, const TileCoord& cur, bool has_next, const TileCoord& nxt, bool nxt_tall) {
         constexpr int TN = decltype(tn_tag)::value;
@@ -370,21 +403,9 @@ __global__ __launch_bounds__(256, 1) void conv3x3_gather_rows_kernel(const T* __
         const int nxt_in_rows = nxt_tall ? 4 * kTall + 2 : 4 * kShort + 2;
         const int cb0 = cur.mt0 / kTM;
 
-        // the tile's step counts and tap offsets -> LDS (nobody reads the previous tile's any more: its last
-        // stage ended at a barrier)
-        for (int e = tid; e < stages * 80; e += 256) {
-            const int stage = e / 80, i = e % 80, half = i / 40, r = i % 40;
-            const bool there = half == 0 || cb0 + 1 < cblocks;
-            const GatherHeader* h = headers + (size_t)stage * cblocks + cb0 + (there ? half : 0);
-            if (r < 36) {
-                const int t = h->tap[r / 9][r % 9];
-                lds_off[((stage * 2 + half) * 4 + r / 9) * kGrOffPitch + r % 9] = (int16_t)(((t / 3) * kLW + (t % 3)) * kPosBytes);
-            } else if (r == 36 && half == 0) {
-                int st = pair_steps_lane(cb0, stage);
-                if (stage == 0) st = max(st & 0xff, 1) | (max(st >> 8, 1) << 8);  // every accumulator starts with step 0
-                lds_steps[stage] = st;
-            }
-        }
+        // the tile's step counts and tap offsets, fetched from the headers while the previous tile was still being
+        // multiplied, -> LDS (nobody reads the previous tile's any more: its last stage ended at a barrier)
+        store_headers();
         __syncthreads();
 
         // A stage's tap offsets (steps 0..7 of both blocks, this lane's quarter) are read one stage ahead into
@@ -417,10 +438,12 @@ __global__ __launch_bounds__(256, 1) void conv3x3_gather_rows_kernel(const T* __
             const int st0 = st & 0xff, st1 = st >> 8, steps = max(st0, st1);
             const bool last_stage = stage + 1 == stages;
             const int copy_stage = last_stage ? 0 : stage + 1;
-            if (last_stage && has_next) setup_tile_sources(nxt, nxt_in_rows);
+            if (last_stage && has_next) {
+                setup_tile_sources(nxt, nxt_in_rows);
+                prefetch_headers(nxt.mt0 / kTM);
+            }
             // (in the very last stage of the last tile nothing is left to fetch; stage 0 of the same tile is fetched
             // again into the free region, which keeps this code free of branches)
-            const int a_count = copies_of(last_stage ? pair_steps(c_cb0, 0) : __builtin_amdgcn_readfirstlane(lds_steps[stage + 1]), last_stage);
             if (!last_stage) load_offsets(stage + 1, off_nxt);
             // sources of the next stage's weight fragments, per block of the pair (no second block: the first one
             // again, never stored)
@@ -442,7 +465,7 @@ __global__ __launch_bounds__(256, 1) void conv3x3_gather_rows_kernel(const T* __
             auto hand_over = [&](int first_unissued) {
                 static_for<kGrCopySlots>([&](auto C) {
                     constexpr int c = decltype(C)::value;
-                    if (c >= first_unissued) issue_copy_slot(c, copy_stage, gpar ^ 1, a_count, a_src0, a_src1);
+                    if (c >= first_unissued) issue_copy_slot(c, copy_stage, gpar ^ 1, a_src0, a_src1);
                 });
                 asm volatile("" ::: "memory");
                 __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
@@ -459,7 +482,9 @@ __global__ __launch_bounds__(256, 1) void conv3x3_gather_rows_kernel(const T* __
             // stage.)
             auto static_body = [&](auto steps_tag) {
                 constexpr int STEPS = decltype(steps_tag)::value;
-                constexpr int HS = 2 * STEPS - 1;  // half-steps that carry copies
+                // half-steps that carry copies: the first half of the stage, so that the last copy has the other half to
+                // land before the hand-over waits for it (a stage is short; issued late, the copies' latency shows)
+                constexpr int HS = STEPS;
                 // matrix instructions of one half-step with copy slots [c0, c1) issued between them
                 auto half_step = [&](auto half_tag, auto first_step_tag, auto c0_tag, auto c1_tag, const u32x4 (&a)[kTM],
                                      const u32x4 (&b)[kTall]) {
@@ -473,7 +498,7 @@ __global__ __launch_bounds__(256, 1) void conv3x3_gather_rows_kernel(const T* __
                         // when a short stage has more copies than matrix instructions in a half-step)
                         static_for<(n > 0 ? n : 0)>([&](auto K) {
                             constexpr int k = decltype(K)::value;
-                            if constexpr (i == k * total / (n > 0 ? n : 1)) issue_copy_slot(c0 + k, copy_stage, gpar ^ 1, a_count, a_src0, a_src1);
+                            if constexpr (i == k * total / (n > 0 ? n : 1)) issue_copy_slot(c0 + k, copy_stage, gpar ^ 1, a_src0, a_src1);
                         });
                         __builtin_amdgcn_sched_barrier(0);
                     });
@@ -483,8 +508,8 @@ __global__ __launch_bounds__(256, 1) void conv3x3_gather_rows_kernel(const T* __
                     constexpr int h0 = 2 * s, h1 = 2 * s + 1;
                     load_operands(gpar, s, 1, offset_of(off_cur, 1, s), a_nxt, b_nxt);
                     half_step(std::integral_constant<int, 0>{}, std::integral_constant<bool, FIRST && s == 0>{},
-                              std::integral_constant<int, h0 * kGrCopySlots / HS>{}, std::integral_constant<int, (h0 + 1) * kGrCopySlots / HS>{},
-                              a_cur, b_cur);
+                              std::integral_constant<int, (h0 < HS ? h0 : HS) * kGrCopySlots / HS>{},
+                              std::integral_constant<int, (h0 + 1 < HS ? h0 + 1 : HS) * kGrCopySlots / HS>{}, a_cur, b_cur);
                     if constexpr (s + 1 == STEPS) {
                         hand_over(kGrCopySlots);  // (every copy has been issued)
                         half_step(std::integral_constant<int, 1>{}, std::integral_constant<bool, FIRST && s == 0>{},
@@ -492,8 +517,8 @@ __global__ __launch_bounds__(256, 1) void conv3x3_gather_rows_kernel(const T* __
                     } else {
                         load_operands(gpar, s + 1, 0, offset_of(off_cur, 0, s + 1), a_cur, b_cur);
                         half_step(std::integral_constant<int, 1>{}, std::integral_constant<bool, FIRST && s == 0>{},
-                                  std::integral_constant<int, h1 * kGrCopySlots / HS>{}, std::integral_constant<int, (h1 + 1) * kGrCopySlots / HS>{},
-                                  a_nxt, b_nxt);
+                                  std::integral_constant<int, (h1 < HS ? h1 : HS) * kGrCopySlots / HS>{},
+                                  std::integral_constant<int, (h1 + 1 < HS ? h1 + 1 : HS) * kGrCopySlots / HS>{}, a_nxt, b_nxt);
                     }
                 });
             };
@@ -503,7 +528,7 @@ __global__ __launch_bounds__(256, 1) void conv3x3_gather_rows_kernel(const T* __
             // of them the region holds) and the matrix instructions unconditional: a block that has no step s
             // multiplies by zero, which keeps the accumulators out of every branch.
             auto generic_body = [&]() {
-                static_for<kGrCopySlots>([&](auto C) { issue_copy_slot(decltype(C)::value, copy_stage, gpar ^ 1, a_count, a_src0, a_src1); });
+                static_for<kGrCopySlots>([&](auto C) { issue_copy_slot(decltype(C)::value, copy_stage, gpar ^ 1, a_src0, a_src1); });
                 const char* X = smem + gpar * kGrRegion + kGrABytes + xrd;
                 auto step = [&](auto first_step_tag, int st_i) {
                     static_for<2>([&](auto HF) {
@@ -517,7 +542,13 @@ __global__ __launch_bounds__(256, 1) void conv3x3_gather_rows_kernel(const T* __
 #pragma unroll
                             for (int m = 0; m < kTM; ++m) a[m] = *(const u32x4*)(Ag + m * kFrag);
                         }
-                        const int off = lds_off[((stage * 2 + half) * 4 + qq) * kGrOffPitch + st_i];
+                        int off;
+                        if (st_i < 8) {
+                            off = lds_off[((stage * 2 + half) * 4 + qq) * kGrOffPitch + st_i];
+                        } else {  // the table holds steps 0..7
+                            const int t = headers[(size_t)stage * cblocks + cb].tap[qq][8];
+                            off = ((t / 3) * kLW + (t % 3)) * kPosBytes;
+                        }
 #pragma unroll
                         for (int j = 0; j < TN; ++j) b[j] = *(const u32x4*)(X + j * kLW * kPosBytes + off);
                         multiply(HF, first_step_tag, a, b);
@@ -594,13 +625,13 @@ __global__ __launch_bounds__(256, 1) void conv3x3_gather_rows_kernel(const T* __
     TileCoord cur = decode_entry(plan, cur_tall, cur_tall ? tall_next : short_next);
     if (cur_tall) tall_next += slots;
     else short_next += slots;
+    prefetch_headers(cur.mt0 / kTM);
     setup_tile_sources(cur, cur_tall ? 4 * kTall + 2 : 4 * kShort + 2);
     {
-        const int a_count = copies_of(pair_steps(c_cb0, 0), true);
         const char* const a_src0 = wfrag + (int64_t)c_cb0 * kBlockBytes + lane * 16;
         const char* const a_src1 = a_src0 + (c_cb0 + 1 < cblocks ? kBlockBytes : 0);
 #pragma unroll
-        for (int c = 0; c < kGrCopySlots; ++c) issue_copy_slot(c, 0, 0, a_count, a_src0, a_src1);
+        for (int c = 0; c < kGrCopySlots; ++c) issue_copy_slot(c, 0, 0, a_src0, a_src1);
     }
     bool first_tile = true;
     for (;;) {
