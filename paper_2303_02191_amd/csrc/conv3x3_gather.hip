@@ -336,7 +336,8 @@ __global__ __launch_bounds__(256, 1) void conv3x3_gather_rows_kernel(const T* __
     // One copy instruction (64 lanes x 16 bytes) of stage `stage` of the copy state's tile into region `par`: slots
     // 0 .. kGrAPerWave-1 move weight fragments (a_src0/1: the two blocks' fragments of that stage), the rest activations.
     auto issue_copy_slot = [&](int cslot, int stage, int par, const char* a_src0, const char* a_src1) {
-        char* region = smem + par * kGrRegion;
+        // (the LDS address of a copy travels in a scalar register: keep the region's offset scalar)
+        char* region = smem + __builtin_amdgcn_readfirstlane(par * kGrRegion);
         if (cslot < kGrAPerWave) {
             // piece kk = 4 * cslot + wave of the region is (step, block, fragment) = (cslot / 2, cslot % 2, wave).  All
             // kGrSteps steps are copied whatever the stage's own count (what lies behind a block's last step in the
@@ -420,8 +421,9 @@ __global__ __launch_bounds__(256, 1) void conv3x3_gather_rows_kernel(const T* __
         };
         // operands of a half-step: the weight fragments of (step, block) and, per output row, this quarter's tap
         auto load_operands = [&](int par, int st, int half, int off, u32x4 (&a)[kTM], u32x4 (&b)[kTall]) {
-            const char* A = smem + par * kGrRegion + lane * 16 + ((st * 2 + half) * kTM) * kFrag;
-            const char* X = smem + par * kGrRegion + kGrABytes + xrd + off;
+            const int region = __builtin_amdgcn_readfirstlane(par * kGrRegion);
+            const char* A = smem + region + lane * 16 + ((st * 2 + half) * kTM) * kFrag;
+            const char* X = smem + region + kGrABytes + xrd + off;
 #pragma unroll
             for (int m = 0; m < kTM; ++m) a[m] = *(const u32x4*)(A + m * kFrag);
 #pragma unroll
