@@ -128,8 +128,13 @@ class Parity:
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=300,
+                    help="untimed steps in front of the timed ones.  The chip needs tens of milliseconds of load to reach "
+                         "its steady clocks: the first steps after an idle phase run about 15 %% slower than the rest")
+    ap.add_argument("--prewarm-ms", type=float, default=100.0,
+                    help="besides the warm-up steps: keep running untimed steps until this much wall time has passed, so "
+                         "that a small --warmup still measures steady clocks (0: off)")
     ap.add_argument("--workload", choices=sorted(WORKLOADS), default="cfg4",
                     help="cfg4 (RetinaNet-shaped head, the largest shapes) is the headline workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -156,6 +161,8 @@ def parse():
 
 class Workload:
     """Device-resident tensors of one configuration and the three phases of a step."""
+
+    prewarm_ms = 100.0  # see --prewarm-ms
 
     def __init__(self, cfg, dev, dict_top=0):
         import torch
@@ -256,11 +263,17 @@ class Workload:
             if events:
                 events[3].record()
 
+        t_start_warm = time.perf_counter()
         if before_warmup:
             before_warmup()
         for _ in range(warmup):
             step()
         torch.cuda.synchronize()
+        t_end = time.perf_counter() + self.prewarm_ms * 1e-3 - (time.perf_counter() - t_start_warm)
+        while time.perf_counter() < t_end:  # (untimed: brings the clocks to their steady state)
+            for _ in range(10):
+                step()
+            torch.cuda.synchronize()
         all_events = [[ev() for _ in range(4)] for _ in range(steps)]
         t0 = time.perf_counter()
         for s in range(steps):
@@ -375,6 +388,7 @@ def main():
         import dataclasses
         cfg = dataclasses.replace(cfg, k=args.k, name="%s_k%d" % (cfg.name, args.k))
     eb = wl.ELEM_BYTES[cfg.dtype]
+    Workload.prewarm_ms = args.prewarm_ms
     work = Workload(cfg, dev, args.dict_top)
     masks, dict_counts = work.masks, work.dict_counts
     ev = lambda: torch.cuda.Event(enable_timing=True)
@@ -387,6 +401,24 @@ def main():
             torch.add(src, 1.0, out=dst)  # one elementwise kernel: reads 256 MiB, writes 256 MiB
             torch.cuda.synchronize()
 
+    def time_call(fn, iters=20):
+        """Mean ms per call of fn at steady clocks: untimed calls for at least 60 ms (and at least 5), then `iters`."""
+        t0 = time.perf_counter()
+        n = 0
+        while n < 5 or time.perf_counter() - t0 < 0.06:
+            fn()
+            n += 1
+            if n % 5 == 0:
+                torch.cuda.synchronize()
+        torch.cuda.synchronize()
+        a, b = ev(), ev()
+        a.record()
+        for _ in range(iters):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / iters
+
     ms_per_step, sel_ms, pack_ms, conv_ms = work.time_steps(args.steps, args.warmup, use_graph, copy_probe)
     nz_flops = 2.0 * cfg.nonzero_macs()
     value = nz_flops / (ms_per_step * 1e-3) / 1e12
@@ -396,18 +428,11 @@ def main():
     if args.per_layer:
         print("layer  Ci   Co    H  ks s   conv_us  hbm_ideal_us  mfma_ideal_us(nz)", file=sys.stderr)
         for i, (L, lay, x, y) in enumerate(zip(cfg.layers, layers, xs, ys)):
-            for _ in range(3):
-                lay.conv(x, stride=L.stride, relu=L.relu, y=y)
-            a, b = ev(), ev()
-            a.record()
-            for _ in range(20):
-                lay.conv(x, stride=L.stride, relu=L.relu, y=y)
-            b.record()
-            torch.cuda.synchronize()
+            t_layer = time_call(lambda: lay.conv(x, stride=L.stride, relu=L.relu, y=y))
             byts = cfg.N * (L.Ci * L.H * L.W + L.Co * L.Ho * L.Wo) * eb + L.groups * (cfg.k * eb + 1)
             nz = 2.0 * cfg.N * L.Ho * L.Wo * cfg.k * L.groups
             print("%3d %5d %4d %4d  %d %d  %8.1f  %8.2f  %8.2f" % (i, L.Ci, L.Co, L.H, L.ksize, L.stride,
-                  a.elapsed_time(b) / 20 * 1e3, byts / PEAK_HBM_GBS / 1e3, nz / PEAK_MFMA_16BIT_TFLOPS / 1e6), file=sys.stderr)
+                  t_layer * 1e3, byts / PEAK_HBM_GBS / 1e3, nz / PEAK_MFMA_16BIT_TFLOPS / 1e6), file=sys.stderr)
 
     # ---- parity of what was just timed ----
     parity = Parity(cfg.dtype == wl.F32)
@@ -424,16 +449,7 @@ def main():
             for L, (ws, _), x in zip(cfg.layers, w_host, xs):
                 wt = pl.to_device(ws, cfg.dtype).contiguous(memory_format=torch.channels_last)
                 xt = x.permute(0, 3, 1, 2)  # NCHW view of channels-last storage
-                for _ in range(3):
-                    torch.nn.functional.conv2d(xt, wt, stride=L.stride, padding=L.pad)
-                torch.cuda.synchronize()
-                a, b = ev(), ev()
-                a.record()
-                for _ in range(10):
-                    torch.nn.functional.conv2d(xt, wt, stride=L.stride, padding=L.pad)
-                b.record()
-                torch.cuda.synchronize()
-                dense_ms += a.elapsed_time(b) / 10
+                dense_ms += time_call(lambda: torch.nn.functional.conv2d(xt, wt, stride=L.stride, padding=L.pad))
         except Exception as e:  # comparator only
             dense_ms = None
             print("dense comparator failed: %r" % (e,), file=sys.stderr)
@@ -450,19 +466,11 @@ def main():
             idx9 = torch.zeros(max(L.n_weights // 9, 1), dtype=torch.uint8, device=dev)
             lay9 = pl.PackedLayer(L.Co, L.Ci, L.ksize, 9, cfg.dtype, masks9).pack(w, idx9)
             yd = torch.empty_like(y)
-            for _ in range(3):
-                lay9.conv(x, stride=L.stride, relu=L.relu, y=yd)
-            torch.cuda.synchronize()
-            a, b = ev(), ev()
-            a.record()
-            for _ in range(10):
-                lay9.conv(x, stride=L.stride, relu=L.relu, y=yd)
-            b.record()
-            torch.cuda.synchronize()
-            dense_own_ms += a.elapsed_time(b) / 10
+            t9 = time_call(lambda: lay9.conv(x, stride=L.stride, relu=L.relu, y=yd))
+            dense_own_ms += t9
             if args.per_layer:
                 print("dense mode, own kernel: Ci %4d Co %4d H %3d ks %d s %d  %8.1f us" %
-                      (L.Ci, L.Co, L.H, L.ksize, L.stride, a.elapsed_time(b) / 10 * 1e3), file=sys.stderr)
+                      (L.Ci, L.Co, L.H, L.ksize, L.stride, t9 * 1e3), file=sys.stderr)
             del lay9, yd
 
     # ---- block-shared patterns (layers that take over a parent's patterns, shared per run of 8 input channels):
@@ -480,20 +488,8 @@ def main():
             lays = pl.PackedLayer(L.Co, L.Ci, 3, cfg.k, cfg.dtype, masks).pack(w, idxc)
             steps_seen |= set(np.unique(layc.steps()).tolist())
             yd = torch.empty_like(y)
-            for lay, which in ((layc, "g"), (lays, "s")):
-                for _ in range(3):
-                    lay.conv(x, stride=L.stride, relu=L.relu, y=yd)
-                torch.cuda.synchronize()
-                a, b = ev(), ev()
-                a.record()
-                for _ in range(10):
-                    lay.conv(x, stride=L.stride, relu=L.relu, y=yd)
-                b.record()
-                torch.cuda.synchronize()
-                if which == "g":
-                    t_gather += a.elapsed_time(b) / 10
-                else:
-                    t_sparse += a.elapsed_time(b) / 10
+            t_gather += time_call(lambda: layc.conv(x, stride=L.stride, relu=L.relu, y=yd))
+            t_sparse += time_call(lambda: lays.conv(x, stride=L.stride, relu=L.relu, y=yd))
             del layc, lays, yd
         coherent = {"patterns": "one per run of 8 input channels, shared by all output channels",
                     "dense_steps_per_stage": sorted(int(v) for v in steps_seen),
@@ -524,7 +520,7 @@ def main():
     out = {
         "metric": "effective TFLOP/s on non-zero MACs, select+pack+pattern-sparse conv",
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "prewarm_ms": args.prewarm_ms, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.DTYPE_NAMES[cfg.dtype], "data": "synthetic",
         "launch": "hip_graph" if use_graph else "eager",
         "config": {"workload": cfg.name, "batch": cfg.N, "layers": len(cfg.layers), "k": cfg.k,
