@@ -262,32 +262,40 @@ __global__ __launch_bounds__(256) void conv3x3_gather_kernel(const T* __restrict
 
 // ---------------------------------------------------------------------------------------------------------
 // Pipelined variant over strips of rows: the tiling, persistent workgroups, double-buffered stages and direct
-// epilogue of conv3x3_rows.hip (stride 1, 128 output channels x 16 columns x 4*TN rows per workgroup, wave v owns
-// TN rows), around a much simpler stage: `steps` dense steps, each 8*TN matrix instructions on operands read
-// straight from LDS -- one 16-byte read per output row gives the B operand of all 8 channel fragments (the step's
-// tap is a per-quarter LDS offset), no transposes.  A workgroup covers two channel blocks of 64 with their own tap
-// lists; a block with fewer steps than its partner skips its half of the surplus steps.  Up to kGrSteps steps of
-// a stage live in LDS; a stage with more (patterns that are not shared after all) takes the rest of its weight
+// epilogue of conv3x3_rows.hip (stride 1, 128 output channels x 16 columns x 4*TN rows per workgroup), around a
+// much simpler stage.  The workgroup is 8 waves, two per SIMD: wave (v, h) owns TN rows of the tile and block h of
+// the pair of 64-channel blocks, with that block's own tap lists.  A step is 4*TN dense matrix instructions on
+// operands read straight from LDS at the start of the step -- four weight fragments and one 16-byte activation
+// read per output row (the step's tap is a per-quarter LDS offset), no transposes, no prefetch registers: the
+// partner wave's matrix instructions cover the reads.  (Eight waves leave each 128 vector registers next to its
+// 80 accumulators; a four-wave form with the operands of the next half-step prefetched into a second register
+// set measured 5 % slower.)  Up to kGrSteps steps of a stage live in LDS; a tile with more, or with different
+// counts in its blocks or stages (patterns that are not shared after all), takes the general body: weight
 // fragments from global memory, slowly but correctly.
 // ---------------------------------------------------------------------------------------------------------
 constexpr int kGrSteps = 5;
-__device__ __forceinline__ int c_cb0_of_tile(int cb0, int half, int cblocks) { return cb0 + (half && cb0 + 1 < cblocks ? 1 : 0); }
+constexpr int kGrWaves = 8;                           // two per SIMD: wave = (row group, block of the pair)
 constexpr int kGrABytes = kGrSteps * 2 * kStepBytes;  // [step][block of the pair][fragment]: 40 KB
 constexpr int kGrXChunks = (4 * kTall + 2) * kLW * 4;
-constexpr int kGrXPerWave = ((kGrXChunks + 63) / 64 + 3) / 4;
-constexpr int kGrXArea = kGrXPerWave * 4 * 1024;
+constexpr int kGrXPerWave = ((kGrXChunks + 63) / 64 + kGrWaves - 1) / kGrWaves;
+constexpr int kGrXArea = kGrXPerWave * kGrWaves * 1024;
 constexpr int kGrRegion = kGrABytes + kGrXArea;
-constexpr int kGrAPerWave = kGrABytes / 1024 / 4;
+constexpr int kGrAPerWave = kGrABytes / 1024 / kGrWaves;
 constexpr int kGrCopySlots = kGrAPerWave + kGrXPerWave;
 constexpr int kGrOffPitch = 8;  // int16 entries per (stage, block, quarter): steps 0..7, one 16-byte read
 constexpr size_t kGrSmem = 2 * (size_t)kGrRegion + kMaxStages * 4 + (size_t)kMaxStages * 2 * 4 * kGrOffPitch * 2;
+static_assert(kGrABytes / 1024 == kGrAPerWave * kGrWaves, "every wave issues the same number of weight copies");
+static_assert(kMaxStages * 8 <= 64 * kGrWaves, "one table entry per thread");
+
+__device__ __forceinline__ int pair_block(int cb0, int half, int cblocks) { return cb0 + (half && cb0 + 1 < cblocks ? 1 : 0); }
 
 template <typename T, typename TO>
-__global__ __launch_bounds__(256, 1) void conv3x3_gather_rows_kernel(const T* __restrict__ x, TO* __restrict__ y,
-                                                                     const GatherHeader* __restrict__ headers,
-                                                                     const char* __restrict__ wfrag,
-                                                                     const char* __restrict__ zeros, int H, int W, int Ci,
-                                                                     int Co, int cblocks, RowPlan plan, float relu_floor, int ldy)
+__global__ __launch_bounds__(64 * kGrWaves, 1) void conv3x3_gather_rows_kernel(const T* __restrict__ x, TO* __restrict__ y,
+                                                                                const GatherHeader* __restrict__ headers,
+                                                                                const char* __restrict__ wfrag,
+                                                                                const char* __restrict__ zeros, int H, int W,
+                                                                                int Ci, int Co, int cblocks, RowPlan plan,
+                                                                                float relu_floor, int ldy)
 {
     static_assert(sizeof(TO) == 2, "direct epilogue: 16-bit output");
     extern __shared__ __attribute__((aligned(16))) char smem[];  // two regions, then the tile's step counts and tap offsets
@@ -297,6 +305,8 @@ __global__ __launch_bounds__(256, 1) void conv3x3_gather_rows_kernel(const T* __
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int vrow = wave & 3;   // which TN rows of the tile
+    const int hsel = wave >> 2;  // which 64-channel block of the pair
     const int stages = Ci / 32;
     const int Ho = H, Wo = W;  // stride 1, padding 1
 
@@ -308,14 +318,6 @@ __global__ __launch_bounds__(256, 1) void conv3x3_gather_rows_kernel(const T* __
     int short_next = xcd * plan.short_per_xcd + (slots - 1 - slot);
     if (tall_next >= tall_end && short_next >= short_end) return;
 
-    // steps of the two blocks of channel-block pair cb0 in stage `stage`, from the headers in global memory
-    auto pair_steps_lane = [&](int cb0, int stage) -> int {
-        const GatherHeader* h = headers + (size_t)stage * cblocks + cb0;
-        unsigned s0 = h->steps, s1 = cb0 + 1 < cblocks ? h[1].steps : 0u;
-        s0 = s0 > 9u ? 9u : s0;  // (a corrupt header cannot run the loops out of bounds)
-        s1 = s1 > 9u ? 9u : s1;
-        return (int)(s0 | (s1 << 8));
-    };
     // ---- copy state: the tile whose stages are being fetched ----
     int c_cb0 = 0;
     const char* x_ptr[kGrXPerWave];
@@ -324,7 +326,7 @@ __global__ __launch_bounds__(256, 1) void conv3x3_gather_rows_kernel(const T* __
         const int ih0 = t.oh0 - 1, iw0 = t.ow0 - 1;
 #pragma unroll
         for (int k = 0; k < kGrXPerWave; ++k) {
-            const int c = ((k * 4 + wave) * 64 + lane);
+            const int c = ((k * kGrWaves + wave) * 64 + lane);
             const int pos = c >> 2, q = c & 3;
             const int pr = pos / kLW, pc = pos - pr * kLW;
             const int ih = ih0 + pr, iw = iw0 + pc;
@@ -334,73 +336,74 @@ __global__ __launch_bounds__(256, 1) void conv3x3_gather_rows_kernel(const T* __
         }
     };
     // One copy instruction (64 lanes x 16 bytes) of stage `stage` of the copy state's tile into region `par`: slots
-    // 0 .. kGrAPerWave-1 move weight fragments (a_src0/1: the two blocks' fragments of that stage), the rest activations.
-    auto issue_copy_slot = [&](int cslot, int stage, int par, const char* a_src0, const char* a_src1) {
+    // 0 .. kGrAPerWave-1 move weight fragments (a_src: this wave's block's fragments of that stage), the rest activations.
+    auto issue_copy_slot = [&](int cslot, int stage, int par, const char* a_src) {
         // (the LDS address of a copy travels in a scalar register: keep the region's offset scalar)
         char* region = smem + __builtin_amdgcn_readfirstlane(par * kGrRegion);
         if (cslot < kGrAPerWave) {
-            // piece kk = 4 * cslot + wave of the region is (step, block, fragment) = (cslot / 2, cslot % 2, wave).  All
+            // piece 8 * cslot + wave of the region is (step, block, fragment) = (cslot, wave / 4, wave % 4).  All
             // kGrSteps steps are copied whatever the stage's own count (what lies behind a block's last step in the
             // blob is never multiplied): a count would put a branch around every copy, and branches between the
             // matrix instructions cost more than the surplus copies.
-            const int kk = cslot * 4 + wave;
-            copy16_to_lds(((cslot & 1) ? a_src1 : a_src0) + ((cslot >> 1) * kTM + wave) * kFrag, region + kk * 1024);
+            copy16_to_lds(a_src + (cslot * kTM + vrow) * kFrag, region + (cslot * kGrWaves + wave) * 1024);
         } else {
             const int k = cslot - kGrAPerWave;
-            copy16_to_lds(x_ptr[k] + stage * 64, region + kGrABytes + (k * 4 + wave) * 1024);
+            copy16_to_lds(x_ptr[k] + stage * 64, region + kGrABytes + (k * kGrWaves + wave) * 1024);
         }
+    };
+    // this wave's share of the weight fragments of stage `stage` of the copy state's tile: fragment wave % 4 of its
+    // block (no second block in the pair: the first one again, never stored)
+    auto weight_source = [&](int stage) {
+        return wfrag + ((int64_t)stage * cblocks + pair_block(c_cb0, hsel, cblocks)) * kBlockBytes + lane * 16;
     };
 
     const int nn = lane & 15, qq = lane >> 4;
-    f32x4 acc[2 * kTM][kTall];
-    u32x4 a_cur[kTM], a_nxt[kTM], b_cur[kTall], b_nxt[kTall];
-    int gpar = 0;  // region that holds the stage about to be multiplied
+    f32x4 acc[kTM][kTall];
+    u32x4 a_op[kTM], b_op[kTall];  // operands of the step being multiplied (the partner wave on the SIMD covers their latency)
+    int gpar = 0;                        // region that holds the stage about to be multiplied
 
     // A tile's table entries (stage, block of the pair, quarter): the offsets in the activation tile of the taps of
-    // steps 0..7, and per stage the two step counts.  A thread fetches up to two entries from the headers in global
-    // memory into registers (prefetch_headers, a tile ahead) and writes them to LDS when the tile starts.
-    u32x4 hdr_off[2];
-    int hdr_steps[2];
+    // steps 0..7, and per stage the two step counts.  A thread fetches one entry from the headers in global memory
+    // into registers (prefetch_headers, a tile ahead) and writes it to LDS when the tile starts.
+    u32x4 hdr_off;
+    int hdr_steps;
     auto prefetch_headers = [&](int cb0) {
+        hdr_off = u32x4{0, 0, 0, 0};
+        hdr_steps = 0;
+        if (tid < stages * 8) {
+            const int stage = tid >> 3, half = (tid >> 2) & 1, q = tid & 3;
+            const GatherHeader* h = headers + (size_t)stage * cblocks + pair_block(cb0, half, cblocks);
+            uint32_t o[8];
 #pragma unroll
-        for (int r = 0; r < 2; ++r) {
-            const int e = tid + 256 * r;
-            hdr_off[r] = u32x4{0, 0, 0, 0};
-            hdr_steps[r] = 0;
-            if (e < stages * 8) {
-                const int stage = e >> 3, half = (e >> 2) & 1, q = e & 3;
-                const bool there = half == 0 || cb0 + 1 < cblocks;
-                const GatherHeader* h = headers + (size_t)stage * cblocks + cb0 + (there ? half : 0);
-                uint32_t o[8];
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const int t = h->tap[q][i];
-                    o[i] = (uint32_t)(((t / 3) * kLW + (t % 3)) * kPosBytes);
+            for (int i = 0; i < 8; ++i) {
+                const int t = h->tap[q][i];
+                o[i] = (uint32_t)(((t / 3) * kLW + (t % 3)) * kPosBytes);
+            }
+            hdr_off = u32x4{o[0] | (o[1] << 16), o[2] | (o[3] << 16), o[4] | (o[5] << 16), o[6] | (o[7] << 16)};
+            if (half == 0 && q == 0) {
+                const GatherHeader* h0 = headers + (size_t)stage * cblocks + cb0;
+                unsigned s0 = h0->steps, s1 = cb0 + 1 < cblocks ? h0[1].steps : 0u;
+                s0 = s0 > 9u ? 9u : s0;  // (a corrupt header cannot run the loops out of bounds)
+                s1 = s1 > 9u ? 9u : s1;
+                if (stage == 0) {  // every accumulator starts with step 0
+                    s0 = s0 ? s0 : 1u;
+                    s1 = s1 ? s1 : 1u;
                 }
-                hdr_off[r] = u32x4{o[0] | (o[1] << 16), o[2] | (o[3] << 16), o[4] | (o[5] << 16), o[6] | (o[7] << 16)};
-                if (half == 0 && q == 0) {
-                    int st = pair_steps_lane(cb0, stage);
-                    if (stage == 0) st = max(st & 0xff, 1) | (max(st >> 8, 1) << 8);  // every accumulator starts with step 0
-                    hdr_steps[r] = st;
-                }
+                hdr_steps = (int)(s0 | (s1 << 8));
             }
         }
     };
     auto store_headers = [&]() {
-#pragma unroll
-        for (int r = 0; r < 2; ++r) {
-            const int e = tid + 256 * r;
-            if (e < stages * 8) {
-                *(u32x4*)(lds_off + e * kGrOffPitch) = hdr_off[r];
-                if ((e & 7) == 0) lds_steps[e >> 3] = hdr_steps[r];
-            }
+        if (tid < stages * 8) {
+            *(u32x4*)(lds_off + tid * kGrOffPitch) = hdr_off;
+            if ((tid & 7) == 0) lds_steps[tid >> 3] = hdr_steps;
         }
     };
 
     // ---- one tile of TN rows per wave ----
     auto run_tile = [&](auto tn_tag, const TileCoord& cur, bool has_next, const TileCoord& nxt, bool nxt_tall) {
         constexpr int TN = decltype(tn_tag)::value;
-        const int xrd = ((wave * TN) * kLW + nn) * kPosBytes + qq * 16;
+        const int xrd = ((vrow * TN) * kLW + nn) * kPosBytes + qq * 16;
         const int nxt_in_rows = nxt_tall ? 4 * kTall + 2 : 4 * kShort + 2;
         const int cb0 = cur.mt0 / kTM;
 
@@ -409,35 +412,31 @@ __global__ __launch_bounds__(256, 1) void conv3x3_gather_rows_kernel(const T* __
         store_headers();
         __syncthreads();
 
-        // A stage's tap offsets (steps 0..7 of both blocks, this lane's quarter) are read one stage ahead into
+        // A stage's tap offsets (steps 0..7 of this wave's block, this lane's quarter) are read one stage ahead into
         // registers, so that no operand read waits for a table look-up.
-        auto load_offsets = [&](int stage, u32x4 (&pk)[2]) {
-#pragma unroll
-            for (int half = 0; half < 2; ++half)
-                pk[half] = *(const u32x4*)(lds_off + ((stage * 2 + half) * 4 + qq) * kGrOffPitch);
+        auto load_offsets = [&](int stage) -> u32x4 {
+            return *(const u32x4*)(lds_off + ((stage * 2 + hsel) * 4 + qq) * kGrOffPitch);
         };
-        auto offset_of = [](const u32x4 (&pk)[2], int half, int st) -> int {  // st < 8, compile-time after unrolling
-            return (int)((pk[half][st >> 1] >> ((st & 1) * 16)) & 0xffffu);
+        auto offset_of = [](const u32x4& pk, int st) -> int {  // st < 8, compile-time after unrolling
+            return (int)((pk[st >> 1] >> ((st & 1) * 16)) & 0xffffu);
         };
-        // operands of a half-step: the weight fragments of (step, block) and, per output row, this quarter's tap
-        auto load_operands = [&](int par, int st, int half, int off, u32x4 (&a)[kTM], u32x4 (&b)[kTall]) {
+        // operands of a step: the block's four weight fragments and, per output row, this quarter's tap
+        auto load_operands = [&](int par, int st, int off, u32x4 (&a)[kTM], u32x4 (&b)[kTall]) {
             const int region = __builtin_amdgcn_readfirstlane(par * kGrRegion);
-            const char* A = smem + region + lane * 16 + ((st * 2 + half) * kTM) * kFrag;
+            const char* A = smem + region + lane * 16 + ((st * 2) * kTM) * kFrag + hsel * (kTM * kFrag);
             const char* X = smem + region + kGrABytes + xrd + off;
 #pragma unroll
             for (int m = 0; m < kTM; ++m) a[m] = *(const u32x4*)(A + m * kFrag);
 #pragma unroll
             for (int j = 0; j < TN; ++j) b[j] = *(const u32x4*)(X + j * kLW * kPosBytes);
         };
-        u32x4 off_cur[2], off_nxt[2];
-        load_offsets(0, off_cur);
-        load_operands(gpar, 0, 0, offset_of(off_cur, 0, 0), a_cur, b_cur);
+        u32x4 off_cur = load_offsets(0), off_nxt = off_cur;
 
         auto run_stage = [&](auto first_tag, auto body_tag, int stage) {
             constexpr bool FIRST = decltype(first_tag)::value;
             constexpr int BODY = decltype(body_tag)::value;  // steps of the branch-free body, 0: the general body
             const int st = __builtin_amdgcn_readfirstlane(lds_steps[stage]);
-            const int st0 = st & 0xff, st1 = st >> 8, steps = max(st0, st1);
+            const int my_steps = hsel ? st >> 8 : st & 0xff, steps = max(st & 0xff, st >> 8);
             const bool last_stage = stage + 1 == stages;
             const int copy_stage = last_stage ? 0 : stage + 1;
             if (last_stage && has_next) {
@@ -446,82 +445,54 @@ __global__ __launch_bounds__(256, 1) void conv3x3_gather_rows_kernel(const T* __
             }
             // (in the very last stage of the last tile nothing is left to fetch; stage 0 of the same tile is fetched
             // again into the free region, which keeps this code free of branches)
-            if (!last_stage) load_offsets(stage + 1, off_nxt);
-            // sources of the next stage's weight fragments, per block of the pair (no second block: the first one
-            // again, never stored)
-            const char* const a_src0 = wfrag + ((int64_t)copy_stage * cblocks + c_cb0) * kBlockBytes + lane * 16;
-            const char* const a_src1 = a_src0 + (c_cb0 + 1 < cblocks ? kBlockBytes : 0);
-            auto multiply = [&](auto half_tag, auto first_step_tag, const u32x4 (&a)[kTM], const u32x4 (&b)[kTall]) {
-                constexpr int half = decltype(half_tag)::value;
-#pragma unroll
-                for (int m = 0; m < kTM; ++m)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j) {
-                        if constexpr (decltype(first_step_tag)::value) Mat<T>::dense_first(a[m], b[j], acc[half * kTM + m][j]);
-                        else Mat<T>::dense(a[m], b[j], acc[half * kTM + m][j]);
-                    }
+            if (!last_stage) off_nxt = load_offsets(stage + 1);
+            const char* const a_src = weight_source(copy_stage);
+            auto multiply = [&](auto first_step_tag, const u32x4 (&a)[kTM], const u32x4 (&b)[kTall], auto&& between) {
+                static_for<kTM * TN>([&](auto I) {
+                    constexpr int i = decltype(I)::value, m = i / TN, j = i % TN;
+                    if constexpr (decltype(first_step_tag)::value) Mat<T>::dense_first(a[m], b[j], acc[m][j]);
+                    else Mat<T>::dense(a[m], b[j], acc[m][j]);
+                    between(I);
+                    __builtin_amdgcn_sched_barrier(0);
+                });
             };
             // Stage hand-over: every copy of the next stage issued, this wave's landed and its reads of this region
-            // done, a bare barrier, then the next stage's first operands (they arrive under the matrix instructions
-            // that follow).  At a tile's end the next tile reads its own first operands (other tap lists).
+            // done, a bare barrier.
             auto hand_over = [&](int first_unissued) {
                 static_for<kGrCopySlots>([&](auto C) {
                     constexpr int c = decltype(C)::value;
-                    if (c >= first_unissued) issue_copy_slot(c, copy_stage, gpar ^ 1, a_src0, a_src1);
+                    if (c >= first_unissued) issue_copy_slot(c, copy_stage, gpar ^ 1, a_src);
                 });
                 asm volatile("" ::: "memory");
                 __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
                 __builtin_amdgcn_s_barrier();
                 asm volatile("" ::: "memory");
-                if (!last_stage) load_operands(gpar ^ 1, 0, 0, offset_of(off_nxt, 0, 0), a_cur, b_cur);
             };
-            // A stage whose two blocks take the same number of steps, at most kGrSteps -- every stage, when the
-            // patterns are shared the way the packer hopes -- runs a body without a single branch: STEPS is a
-            // compile-time constant, the copies of the next stage are dealt over the half-steps before the last and
-            // the hand-over sits in front of the last half-step's matrix instructions.  (With branches between the
-            // half-steps the compiler's wait-count bookkeeping falls back to waiting for every outstanding LDS read in
-            // front of each block of matrix instructions, which exposes the operand reads' latency twelve times a
-            // stage.)
+            // A tile whose stages all take the same number of steps, at most kGrSteps, in both blocks -- every tile,
+            // when the patterns are shared the way the packer hopes -- runs a body without a single branch: STEPS is
+            // a compile-time constant, the copies of the next stage are dealt over the early steps and the hand-over
+            // sits between the last step's operand reads and its matrix instructions.  (With branches between the
+            // steps the compiler's wait-count bookkeeping falls back to waiting for every outstanding LDS read in
+            // front of each block of matrix instructions.)  Operands are read at the start of the step that uses them:
+            // two waves share a SIMD, and one's matrix instructions cover the other's reads.
             auto static_body = [&](auto steps_tag) {
                 constexpr int STEPS = decltype(steps_tag)::value;
-                // half-steps that carry copies: the first half of the stage, so that the last copy has the other half to
-                // land before the hand-over waits for it (a stage is short; issued late, the copies' latency shows)
-                constexpr int HS = STEPS;
-                // matrix instructions of one half-step with copy slots [c0, c1) issued between them
-                auto half_step = [&](auto half_tag, auto first_step_tag, auto c0_tag, auto c1_tag, const u32x4 (&a)[kTM],
-                                     const u32x4 (&b)[kTall]) {
-                    constexpr int half = decltype(half_tag)::value, c0 = decltype(c0_tag)::value, c1 = decltype(c1_tag)::value;
-                    constexpr int n = c1 - c0, total = kTM * TN;
-                    static_for<total>([&](auto I) {
-                        constexpr int i = decltype(I)::value, m = i / TN, j = i % TN;
-                        if constexpr (decltype(first_step_tag)::value) Mat<T>::dense_first(a[m], b[j], acc[half * kTM + m][j]);
-                        else Mat<T>::dense(a[m], b[j], acc[half * kTM + m][j]);
-                        // copy k of this half-step goes behind matrix instruction k * total / n (several per instruction
-                        // when a short stage has more copies than matrix instructions in a half-step)
-                        static_for<(n > 0 ? n : 0)>([&](auto K) {
-                            constexpr int k = decltype(K)::value;
-                            if constexpr (i == k * total / (n > 0 ? n : 1)) issue_copy_slot(c0 + k, copy_stage, gpar ^ 1, a_src0, a_src1);
-                        });
-                        __builtin_amdgcn_sched_barrier(0);
-                    });
-                };
+                constexpr int CS = STEPS > 2 ? STEPS / 2 : 1;  // steps that carry copies (the early ones)
                 static_for<STEPS>([&](auto S) {
                     constexpr int s = decltype(S)::value;
-                    constexpr int h0 = 2 * s, h1 = 2 * s + 1;
-                    load_operands(gpar, s, 1, offset_of(off_cur, 1, s), a_nxt, b_nxt);
-                    half_step(std::integral_constant<int, 0>{}, std::integral_constant<bool, FIRST && s == 0>{},
-                              std::integral_constant<int, (h0 < HS ? h0 : HS) * kGrCopySlots / HS>{},
-                              std::integral_constant<int, (h0 + 1 < HS ? h0 + 1 : HS) * kGrCopySlots / HS>{}, a_cur, b_cur);
-                    if constexpr (s + 1 == STEPS) {
-                        hand_over(kGrCopySlots);  // (every copy has been issued)
-                        half_step(std::integral_constant<int, 1>{}, std::integral_constant<bool, FIRST && s == 0>{},
-                                  std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, a_nxt, b_nxt);
-                    } else {
-                        load_operands(gpar, s + 1, 0, offset_of(off_cur, 0, s + 1), a_cur, b_cur);
-                        half_step(std::integral_constant<int, 1>{}, std::integral_constant<bool, FIRST && s == 0>{},
-                                  std::integral_constant<int, (h1 < HS ? h1 : HS) * kGrCopySlots / HS>{},
-                                  std::integral_constant<int, (h1 + 1 < HS ? h1 + 1 : HS) * kGrCopySlots / HS>{}, a_nxt, b_nxt);
-                    }
+                    constexpr int c0 = (s < CS ? s : CS) * kGrCopySlots / CS, c1 = (s + 1 < CS ? s + 1 : CS) * kGrCopySlots / CS;
+                    constexpr int n = STEPS > 1 ? c1 - c0 : 0, total = kTM * TN;
+                    load_operands(gpar, s, offset_of(off_cur, s), a_op, b_op);
+                    if constexpr (s + 1 == STEPS) hand_over(STEPS > 1 ? kGrCopySlots : 0);
+                    multiply(std::integral_constant<bool, FIRST && s == 0>{}, a_op, b_op, [&](auto I) {
+                        constexpr int i = decltype(I)::value;
+                        if constexpr (s + 1 < STEPS) {
+                            static_for<(n > 0 ? n : 0)>([&](auto K) {
+                                constexpr int k = decltype(K)::value;
+                                if constexpr (i == k * total / (n > 0 ? n : 1)) issue_copy_slot(c0 + k, copy_stage, gpar ^ 1, a_src);
+                            });
+                        }
+                    });
                 });
             };
             // The general body, for tiles whose patterns are not shared the way the packer hopes (any step counts, up
@@ -530,31 +501,28 @@ __global__ __launch_bounds__(256, 1) void conv3x3_gather_rows_kernel(const T* __
             // of them the region holds) and the matrix instructions unconditional: a block that has no step s
             // multiplies by zero, which keeps the accumulators out of every branch.
             auto generic_body = [&]() {
-                static_for<kGrCopySlots>([&](auto C) { issue_copy_slot(decltype(C)::value, copy_stage, gpar ^ 1, a_src0, a_src1); });
-                const char* X = smem + gpar * kGrRegion + kGrABytes + xrd;
+                static_for<kGrCopySlots>([&](auto C) { issue_copy_slot(decltype(C)::value, copy_stage, gpar ^ 1, a_src); });
+                const char* X = smem + __builtin_amdgcn_readfirstlane(gpar * kGrRegion) + kGrABytes + xrd;
+                const int cb = pair_block(cb0, hsel, cblocks);
                 auto step = [&](auto first_step_tag, int st_i) {
-                    static_for<2>([&](auto HF) {
-                        constexpr int half = decltype(HF)::value;
-                        const int cb = c_cb0_of_tile(cb0, half, cblocks);
-                        const char* Ag = wfrag + ((int64_t)stage * cblocks + cb) * kBlockBytes + (st_i * kTM) * kFrag + lane * 16;
-                        u32x4 a[kTM], b[kTall];
+                    const char* Ag = wfrag + ((int64_t)stage * cblocks + cb) * kBlockBytes + (st_i * kTM) * kFrag + lane * 16;
+                    u32x4 a[kTM], b[kTall];
 #pragma unroll
-                        for (int m = 0; m < kTM; ++m) a[m] = u32x4{0, 0, 0, 0};
-                        if (st_i < (half ? st1 : st0)) {  // uniform; fragments past a block's own steps are not written
+                    for (int m = 0; m < kTM; ++m) a[m] = u32x4{0, 0, 0, 0};
+                    if (st_i < my_steps) {  // uniform; fragments past a block's own steps are not written
 #pragma unroll
-                            for (int m = 0; m < kTM; ++m) a[m] = *(const u32x4*)(Ag + m * kFrag);
-                        }
-                        int off;
-                        if (st_i < 8) {
-                            off = lds_off[((stage * 2 + half) * 4 + qq) * kGrOffPitch + st_i];
-                        } else {  // the table holds steps 0..7
-                            const int t = headers[(size_t)stage * cblocks + cb].tap[qq][8];
-                            off = ((t / 3) * kLW + (t % 3)) * kPosBytes;
-                        }
+                        for (int m = 0; m < kTM; ++m) a[m] = *(const u32x4*)(Ag + m * kFrag);
+                    }
+                    int off;
+                    if (st_i < 8) {
+                        off = lds_off[((stage * 2 + hsel) * 4 + qq) * kGrOffPitch + st_i];
+                    } else {  // the table holds steps 0..7
+                        const int t = headers[(size_t)stage * cblocks + cb].tap[qq][8];
+                        off = ((t / 3) * kLW + (t % 3)) * kPosBytes;
+                    }
 #pragma unroll
-                        for (int j = 0; j < TN; ++j) b[j] = *(const u32x4*)(X + j * kLW * kPosBytes + off);
-                        multiply(HF, first_step_tag, a, b);
-                    });
+                    for (int j = 0; j < TN; ++j) b[j] = *(const u32x4*)(X + j * kLW * kPosBytes + off);
+                    multiply(first_step_tag, a, b, [](auto) {});
                 };
                 step(std::integral_constant<bool, FIRST>{}, 0);
                 for (int st_i = 1; st_i < steps; ++st_i) step(std::false_type{}, st_i);
@@ -562,10 +530,10 @@ __global__ __launch_bounds__(256, 1) void conv3x3_gather_rows_kernel(const T* __
             };
             if constexpr (BODY > 0) static_body(body_tag);
             else generic_body();
-            off_cur[0] = off_nxt[0];
-            off_cur[1] = off_nxt[1];
+            off_cur = off_nxt;
             gpar ^= 1;
         };
+
         // One path per tile: the stages and the epilogue for a given body.  (Choosing the body per stage would join
         // the paths while the accumulators are live; the compiler then moves accumulators between the registers the
         // paths happen to use, right behind matrix instructions whose latency it does not know.)
@@ -575,35 +543,33 @@ __global__ __launch_bounds__(256, 1) void conv3x3_gather_rows_kernel(const T* __
 
             // the last matrix instructions must have written their accumulators before anything reads them
             asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
-            // ---- epilogue: a lane holds, per block of 64 channels, 16 consecutive channels of column nn of each of
-            // its rows (the packer dealt the rows that way): 32 contiguous bytes per lane and block ----
+            // ---- epilogue: a lane holds 16 consecutive channels of its block for column nn of each of its rows
+            // (the packer dealt the rows that way): 32 contiguous bytes per lane ----
             {
                 int lane_e = lane;
                 asm volatile("" : "+v"(lane_e));
                 const int nn_e = lane_e & 15, qq_e = lane_e >> 4;
-                const int row_first = cur.oh0 + wave * TN;
+                const int row_first = cur.oh0 + vrow * TN;
                 const int64_t pos_tile = ((int64_t)cur.n_img * Ho + cur.oh0) * Wo + cur.ow0;
                 TO* const y_tile = y + pos_tile * ldy;
                 const bool col_inside = cur.ow0 + nn_e < Wo;
+                const int co_lane = 16 * (cur.mt0 + kTM * hsel) + 16 * qq_e;
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
                     const bool inside = col_inside && row_first + j < Ho;
-                    TO* yp = y_tile + ((wave * TN + j) * Wo + nn_e) * ldy + 16 * cur.mt0 + 16 * qq_e;
+                    TO* yp = y_tile + ((vrow * TN + j) * Wo + nn_e) * ldy + co_lane;
+                    uint32_t o[8];
 #pragma unroll
-                    for (int half = 0; half < 2; ++half) {
-                        uint32_t o[8];
+                    for (int m = 0; m < kTM; ++m) {
+                        float r[4];
 #pragma unroll
-                        for (int m = 0; m < kTM; ++m) {
-                            float r[4];
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) asm("v_max_f32 %0, %1, %2" : "=v"(r[e]) : "v"(acc[half * kTM + m][j][e]), "v"(relu_floor));
-                            o[2 * m] = pack2_from_f32<TO>(r[0], r[1]);
-                            o[2 * m + 1] = pack2_from_f32<TO>(r[2], r[3]);
-                        }
-                        if (inside && 16 * (cur.mt0 + 4 * half) + 16 * qq_e < Co) {
-                            *(u32x4*)(yp + 64 * half) = u32x4{o[0], o[1], o[2], o[3]};
-                            *(u32x4*)(yp + 64 * half + 8) = u32x4{o[4], o[5], o[6], o[7]};
-                        }
+                        for (int e = 0; e < 4; ++e) asm("v_max_f32 %0, %1, %2" : "=v"(r[e]) : "v"(acc[m][j][e]), "v"(relu_floor));
+                        o[2 * m] = pack2_from_f32<TO>(r[0], r[1]);
+                        o[2 * m + 1] = pack2_from_f32<TO>(r[2], r[3]);
+                    }
+                    if (inside && co_lane < Co) {
+                        *(u32x4*)(yp) = u32x4{o[0], o[1], o[2], o[3]};
+                        *(u32x4*)(yp + 8) = u32x4{o[4], o[5], o[6], o[7]};
                     }
                 }
             }
@@ -630,10 +596,9 @@ __global__ __launch_bounds__(256, 1) void conv3x3_gather_rows_kernel(const T* __
     prefetch_headers(cur.mt0 / kTM);
     setup_tile_sources(cur, cur_tall ? 4 * kTall + 2 : 4 * kShort + 2);
     {
-        const char* const a_src0 = wfrag + (int64_t)c_cb0 * kBlockBytes + lane * 16;
-        const char* const a_src1 = a_src0 + (c_cb0 + 1 < cblocks ? kBlockBytes : 0);
+        const char* const a_src = weight_source(0);
 #pragma unroll
-        for (int c = 0; c < kGrCopySlots; ++c) issue_copy_slot(c, 0, 0, a_src0, a_src1);
+        for (int c = 0; c < kGrCopySlots; ++c) issue_copy_slot(c, 0, 0, a_src);
     }
     bool first_tile = true;
     for (;;) {
@@ -704,7 +669,7 @@ rtoss_status launch_gather_rows(const rtoss_wdesc& d, const ConvParams& c, const
     const RowPlan plan = plan_rows_for_device(c.N, c.H, c.W, co_blocks, d.Ci / 32, dev.cus, &slots);
     const char* frags = section + header_bytes(d);
     const float relu_floor = c.ep.act == 1 ? 0.f : -__builtin_inff();
-    dim3 grid((unsigned)(slots * 8)), block(256);
+    dim3 grid((unsigned)(slots * 8)), block(64 * kGrWaves);
     kern<<<grid, block, kGrSmem, s>>>((const T*)x, (T*)y, (const GatherHeader*)section, frags, frags + frag_bytes(d), c.H, c.W, d.Ci,
                                       d.Co, channel_blocks(d.Co), plan, relu_floor, c.ep.ldy);
     return check_hip(hipGetLastError(), "conv3x3 gather rows launch");
