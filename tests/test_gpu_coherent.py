@@ -97,3 +97,51 @@ def test_coherent_and_two_of_four_paths_agree_bit_for_bit_on_shared_patterns():
     tol = 2e-3 * np.sqrt(np.mean(ref ** 2))
     for y in (a, b):
         assert np.max(np.abs(wl.nhwc_to_nchw(pl.to_host(y)).astype(np.float64) - ref)) <= tol
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 5])
+def test_pipelined_kernel_every_step_count(k):
+    """The pipelined kernel has one branch-free stage body per step count 1..5: patterns shared per run of 8 input
+    channels give exactly k steps in every stage, on a shape that takes that kernel (tall and short tiles, a ragged
+    last strip, an unpaired last channel block that takes the general body)."""
+    dt, N, Ci, Co, H, W = wl.F16, 13, 96, 144, 50, 64
+    rng = np.random.default_rng(900 + k)
+    masks = B.rtoss_pattern_dict(k)
+    ws = wl.round_to_dtype(rng.standard_normal((Co, Ci, 3, 3)) * 0.05, dt)
+    xs = wl.round_to_dtype(rng.standard_normal((N, Ci, H, W)), dt)
+    idx = _indices("run", rng, Co, Ci, len(masks), None, masks).astype(np.uint8).reshape(-1)
+    ref = oracle.conv2d(wl.to_f64(xs, dt), oracle.mask(wl.to_f64(ws, dt), masks, idx), relu=True)
+    lay = pl.CoherentLayer(Co, Ci, k, dt, masks).pack(pl.to_device(ws, dt), torch.from_numpy(idx).cuda())
+    assert (lay.steps() == k).all()
+    x_dev = pl.to_device(wl.nchw_to_nhwc(xs), dt)
+    y16 = lay.conv(x_dev, relu=True)                    # the pipelined kernel
+    y32 = lay.conv(x_dev, relu=True, out_dt=wl.F32)     # the simple kernel
+    torch.cuda.synchronize()
+    got = wl.nhwc_to_nchw(pl.to_host(y32)).astype(np.float64)
+    assert np.max(np.abs(got - ref)) <= 2e-3 * np.sqrt(np.mean(ref ** 2))
+    assert np.array_equal(wl.nhwc_to_nchw(pl.to_host(y16)), wl.round_to_dtype(got, dt))
+
+
+def test_pipelined_kernel_at_the_largest_channel_count():
+    """Ci = 2048 is 64 stages, the most the header tables hold (one table entry per thread): outputs sampled, each
+    checked against the oracle; the 16-bit output of the pipelined kernel against the simple kernel's fp32 output."""
+    dt, N, Ci, Co, H, W, k = wl.BF16, 50, 2048, 128, 17, 18, 3
+    rng = np.random.default_rng(77)
+    masks = B.rtoss_pattern_dict(k)
+    ws = wl.round_to_dtype(rng.standard_normal((Co, Ci, 3, 3)) * 0.02, dt)
+    xs = wl.round_to_dtype(rng.standard_normal((N, Ci, H, W)), dt)
+    idx = _indices("run", rng, Co, Ci, len(masks), None, masks).astype(np.uint8).reshape(-1)
+    lay = pl.CoherentLayer(Co, Ci, k, dt, masks).pack(pl.to_device(ws, dt), torch.from_numpy(idx).cuda())
+    assert lay.steps().shape == (64, 2) and (lay.steps() == k).all()
+    x_dev = pl.to_device(wl.nchw_to_nhwc(xs), dt)
+    y16 = lay.conv(x_dev)
+    y32 = lay.conv(x_dev, out_dt=wl.F32)
+    torch.cuda.synchronize()
+    got32 = wl.nhwc_to_nchw(pl.to_host(y32)).astype(np.float64)
+    assert np.array_equal(wl.nhwc_to_nchw(pl.to_host(y16)), wl.round_to_dtype(got32, dt))
+    pts = np.stack([rng.integers(0, N, 3000), rng.integers(0, Co, 3000), rng.integers(0, H, 3000), rng.integers(0, W, 3000)], 1)
+    pts[:8] = [[0, 0, 0, 0], [N - 1, Co - 1, H - 1, W - 1], [0, 64, 15, 15], [1, 63, 16, 16], [2, 127, 16, 17], [3, 1, 0, 17],
+               [4, 65, 8, 0], [49, 5, 16, 0]]
+    ref = oracle.conv2d_points(wl.to_f64(xs, dt), oracle.mask(wl.to_f64(ws, dt), masks, idx), pts)
+    vals = got32[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]]
+    assert np.max(np.abs(vals - ref)) <= 2e-3 * np.sqrt(np.mean(ref ** 2))
