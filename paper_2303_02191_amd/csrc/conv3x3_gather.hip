@@ -321,19 +321,42 @@ __global__ __launch_bounds__(64 * kGrWaves, 1) void conv3x3_gather_rows_kernel(c
     // ---- copy state: the tile whose stages are being fetched ----
     int c_cb0 = 0;
     const char* x_ptr[kGrXPerWave];
-    auto setup_tile_sources = [&](const TileCoord& t, int in_rows) {
-        c_cb0 = t.mt0 / kTM;
-        const int ih0 = t.oh0 - 1, iw0 = t.ow0 - 1;
-#pragma unroll
-        for (int k = 0; k < kGrXPerWave; ++k) {
-            const int c = ((k * kGrWaves + wave) * 64 + lane);
-            const int pos = c >> 2, q = c & 3;
-            const int pr = pos / kLW, pc = pos - pr * kLW;
-            const int ih = ih0 + pr, iw = iw0 + pc;
-            const bool inside = pr < in_rows && ih >= 0 && ih < H && iw >= 0 && iw < W;
-            const int off = ((t.n_img * H + ih) * W + iw) * (Ci >> 3) + q;  // 16-byte chunks: fits 31 bits (launcher)
-            x_ptr[k] = inside ? (const char*)x + (int64_t)off * 16 : zeros;
+    // A lane's source of activation copy slot k for tile t, in four parts (position in the tile; image coordinates
+    // and chunk number; address; zero padding), as in conv3x3_rows.hip: the first tile does them in one go, the last
+    // stage of a tile spreads the next tile's over its matrix instructions.  The empty asm statements pin each
+    // part's results where it is written (they are ordered with the matrix instructions).
+    int sp_a = 0, sp_b = 0, sp_off = 0;
+    const char* sp_addr = nullptr;
+    auto source_part = [&](auto K, auto P, const TileCoord& t, int in_rows) {
+        constexpr int k = decltype(K)::value, part = decltype(P)::value;
+        if constexpr (part == 0) {
+            int l = lane;
+            asm volatile("" : "+v"(l));  // recomputed here rather than kept in registers through the K loop
+            const int pos = (k * kGrWaves + wave) * 16 + (l >> 2);
+            sp_a = pos / kLW;
+            sp_b = pos - sp_a * kLW;
+            asm volatile("" : "+v"(sp_a), "+v"(sp_b));
+        } else if constexpr (part == 1) {
+            sp_a += t.oh0 - 1;  // input row and column
+            sp_b += t.ow0 - 1;
+            sp_off = ((t.n_img * H + sp_a) * W + sp_b) * (Ci >> 3) + (lane & 3);  // 16-byte chunks: fits 31 bits (launcher)
+            asm volatile("" : "+v"(sp_a), "+v"(sp_b), "+v"(sp_off));
+        } else if constexpr (part == 2) {
+            sp_addr = (const char*)x + (int64_t)sp_off * 16;
+            asm volatile("" : "+v"(sp_addr));
+        } else {
+            const int row_end = min(H, t.oh0 - 1 + in_rows);  // rows of the tile, and of the image
+            const bool inside = (unsigned)sp_a < (unsigned)row_end && (unsigned)sp_b < (unsigned)W;
+            x_ptr[k] = inside ? sp_addr : zeros;
+            asm volatile("" : "+v"(x_ptr[k]));
         }
+    };
+    constexpr int kSourceParts = 4 * kGrXPerWave;
+    auto setup_tile_sources = [&](const TileCoord& t, int in_rows) {
+        static_for<kSourceParts>([&](auto PN) {
+            constexpr int pn = decltype(PN)::value;
+            source_part(std::integral_constant<int, pn / 4>{}, std::integral_constant<int, pn % 4>{}, t, in_rows);
+        });
     };
     // One copy instruction (64 lanes x 16 bytes) of stage `stage` of the copy state's tile into region `par`: slots
     // 0 .. kGrAPerWave-1 move weight fragments (a_src: this wave's block's fragments of that stage), the rest activations.
@@ -432,20 +455,23 @@ __global__ __launch_bounds__(64 * kGrWaves, 1) void conv3x3_gather_rows_kernel(c
         };
         u32x4 off_cur = load_offsets(0), off_nxt = off_cur;
 
-        auto run_stage = [&](auto first_tag, auto body_tag, int stage) {
-            constexpr bool FIRST = decltype(first_tag)::value;
+        auto run_stage = [&](auto first_tag, auto last_tag, auto body_tag, int stage) {
+            constexpr bool FIRST = decltype(first_tag)::value, LAST = decltype(last_tag)::value;
             constexpr int BODY = decltype(body_tag)::value;  // steps of the branch-free body, 0: the general body
+            // bodies of two steps or more work the next tile's activation sources out between their matrix instructions
+            constexpr bool SPREAD_SOURCES = LAST && BODY > 1;
             const int st = __builtin_amdgcn_readfirstlane(lds_steps[stage]);
             const int my_steps = hsel ? st >> 8 : st & 0xff, steps = max(st & 0xff, st >> 8);
-            const bool last_stage = stage + 1 == stages;
-            const int copy_stage = last_stage ? 0 : stage + 1;
-            if (last_stage && has_next) {
-                setup_tile_sources(nxt, nxt_in_rows);
+            const int copy_stage = LAST ? 0 : stage + 1;
+            // (in the very last stage of the last tile nothing is left to fetch; `nxt` is the same tile then and its
+            // stage 0 is fetched again into the free region, which keeps this code free of branches)
+            if constexpr (LAST) {
+                c_cb0 = nxt.mt0 / kTM;
                 prefetch_headers(nxt.mt0 / kTM);
+                if constexpr (!SPREAD_SOURCES) setup_tile_sources(nxt, nxt_in_rows);
+            } else {
+                off_nxt = load_offsets(stage + 1);
             }
-            // (in the very last stage of the last tile nothing is left to fetch; stage 0 of the same tile is fetched
-            // again into the free region, which keeps this code free of branches)
-            if (!last_stage) off_nxt = load_offsets(stage + 1);
             const char* const a_src = weight_source(copy_stage);
             auto multiply = [&](auto first_step_tag, const u32x4 (&a)[kTM], const u32x4 (&b)[kTall], auto&& between) {
                 static_for<kTM * TN>([&](auto I) {
@@ -486,6 +512,17 @@ __global__ __launch_bounds__(64 * kGrWaves, 1) void conv3x3_gather_rows_kernel(c
                     if constexpr (s + 1 == STEPS) hand_over(STEPS > 1 ? kGrCopySlots : 0);
                     multiply(std::integral_constant<bool, FIRST && s == 0>{}, a_op, b_op, [&](auto I) {
                         constexpr int i = decltype(I)::value;
+                        if constexpr (SPREAD_SOURCES && s == 0) {
+                            // part pn behind matrix instruction pn * D / parts of step 0, in order (the parts share
+                            // their temporaries); D: the instruction behind which the last activation copy is issued
+                            // when step 0 carries all copies (slot c of n goes behind instruction c * total / n)
+                            constexpr int D = CS == 1 ? (kGrCopySlots - 1) * total / kGrCopySlots : total;
+                            static_for<kSourceParts>([&](auto PN) {
+                                constexpr int pn = decltype(PN)::value;
+                                if constexpr (i == pn * D / kSourceParts)
+                                    source_part(std::integral_constant<int, pn / 4>{}, std::integral_constant<int, pn % 4>{}, nxt, nxt_in_rows);
+                            });
+                        }
                         if constexpr (s + 1 < STEPS) {
                             static_for<(n > 0 ? n : 0)>([&](auto K) {
                                 constexpr int k = decltype(K)::value;
@@ -538,8 +575,9 @@ __global__ __launch_bounds__(64 * kGrWaves, 1) void conv3x3_gather_rows_kernel(c
         // the paths while the accumulators are live; the compiler then moves accumulators between the registers the
         // paths happen to use, right behind matrix instructions whose latency it does not know.)
         auto tile_path = [&](auto body_tag) {
-            run_stage(std::true_type{}, body_tag, 0);
-            for (int stage = 1; stage < stages; ++stage) run_stage(std::false_type{}, body_tag, stage);
+            run_stage(std::true_type{}, std::false_type{}, body_tag, 0);  // (the launcher admits Ci >= 96: three stages or more)
+            for (int stage = 1; stage + 1 < stages; ++stage) run_stage(std::false_type{}, std::false_type{}, body_tag, stage);
+            run_stage(std::false_type{}, std::true_type{}, body_tag, stages - 1);
 
             // the last matrix instructions must have written their accumulators before anything reads them
             asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
@@ -594,6 +632,7 @@ __global__ __launch_bounds__(64 * kGrWaves, 1) void conv3x3_gather_rows_kernel(c
     if (cur_tall) tall_next += slots;
     else short_next += slots;
     prefetch_headers(cur.mt0 / kTM);
+    c_cb0 = cur.mt0 / kTM;
     setup_tile_sources(cur, cur_tall ? 4 * kTall + 2 : 4 * kShort + 2);
     {
         const char* const a_src = weight_source(0);
@@ -663,6 +702,7 @@ rtoss_status launch_gather_rows(const rtoss_wdesc& d, const ConvParams& c, const
     DeviceInfo dev;
     if (rtoss_status st = current_device(&dev)) return st;
     const int co_blocks = ((d.Co + 15) / 16 + kRowsTM - 1) / kRowsTM;
+    if (c.stride != 1 || d.Ci % 32 || d.Ci < 96) return fail(RTOSS_ESHAPE, "conv: the pipelined kernel needs stride 1 and three or more stages of 32 input channels");
     if ((int64_t)c.N * c.H * c.W * d.Ci / 8 > 0x7fffffff) return fail(RTOSS_ESHAPE, "conv: input too large for 32-bit chunk offsets");
     if ((int64_t)c.N * ((c.W + 15) / 16) * ((c.H + 15) / 16 + 1) * co_blocks > 0x3fffffff) return fail(RTOSS_ESHAPE, "conv: too many tiles");
     int slots = 0;

@@ -128,20 +128,43 @@ __global__ __launch_bounds__(256, 1) void conv3x3_rows_kernel(const T* __restric
     // 64 bytes stays inside it). ----
     int c_mt0 = 0;
     const char* x_ptr[X_PER_WAVE];  // per lane and copy slot: source address for stage 0
+    // A lane's source of activation copy slot k for tile t, worked out in four parts (position in the tile;
+    // image coordinates and chunk number; address; zero padding).  The first tile does them in one go; after
+    // that the last stage of a tile spreads the parts of the next tile's sources over its matrix instructions
+    // (as one block in front of a stage they cost ~1.3 k cycles with nothing to overlap them).  The empty asm
+    // statements pin each part's results where it is written: they are ordered with the matrix instructions.
+    int sp_a = 0, sp_b = 0, sp_off = 0;
+    const char* sp_addr = nullptr;
+    auto source_part = [&](auto K, auto P, const TileCoord& t, int in_rows) {
+        constexpr int k = decltype(K)::value, part = decltype(P)::value;
+        if constexpr (part == 0) {
+            int l = lane;
+            asm volatile("" : "+v"(l));  // recomputed here rather than kept in registers through the K loop
+            const int pos = (k * 4 + wave) * 16 + (l >> 2);
+            sp_a = pos / kLW;
+            sp_b = pos - sp_a * kLW;
+            asm volatile("" : "+v"(sp_a), "+v"(sp_b));
+        } else if constexpr (part == 1) {
+            sp_a += t.oh0 - 1;  // input row and column
+            sp_b += t.ow0 - 1;
+            // offset in 16-byte chunks: fits 31 bits (checked by the launcher)
+            sp_off = ((t.n_img * H + sp_a) * W + sp_b) * (Ci >> 3) + (lane & 3);
+            asm volatile("" : "+v"(sp_a), "+v"(sp_b), "+v"(sp_off));
+        } else if constexpr (part == 2) {
+            sp_addr = (const char*)x + (int64_t)sp_off * 16;
+            asm volatile("" : "+v"(sp_addr));
+        } else {
+            const int row_end = min(H, t.oh0 - 1 + in_rows);  // rows of the tile, and of the image
+            const bool inside = (unsigned)sp_a < (unsigned)row_end && (unsigned)sp_b < (unsigned)W;
+            x_ptr[k] = inside ? sp_addr : zeros;
+            asm volatile("" : "+v"(x_ptr[k]));
+        }
+    };
     auto setup_tile_sources = [&](const TileCoord& t, int in_rows) {
         c_mt0 = t.mt0;
-        const int ih0 = t.oh0 - 1, iw0 = t.ow0 - 1;
-#pragma unroll
-        for (int k = 0; k < X_PER_WAVE; ++k) {
-            const int c = ((k * 4 + wave) * 64 + lane);
-            const int pos = c >> 2, q = c & 3;
-            const int pr = pos / kLW, pc = pos - pr * kLW;
-            const int ih = ih0 + pr, iw = iw0 + pc;
-            const bool inside = pr < in_rows && ih >= 0 && ih < H && iw >= 0 && iw < W;
-            // offset in 16-byte chunks: fits 31 bits (checked by the launcher)
-            const int off = ((t.n_img * H + ih) * W + iw) * (Ci >> 3) + q;
-            x_ptr[k] = inside ? (const char*)x + (int64_t)off * 16 : zeros;
-        }
+        static_for<X_PER_WAVE>([&](auto K) {
+            static_for<4>([&](auto P) { source_part(K, P, t, in_rows); });
+        });
     };
     // One copy instruction (64 lanes x 16 bytes) of stage `stage` of the copy state's tile into region
     // `par`: slots 0 .. A_PER_WAVE-1 move weight fragments, the rest move activations.
@@ -208,14 +231,15 @@ __global__ __launch_bounds__(256, 1) void conv3x3_rows_kernel(const T* __restric
         // mma.h.  So a tile starts with reads of its own.)
         load_stage_prologue(gpar, xrd);
 
-        auto run_stage = [&](auto first_tag, int stage) {
-            constexpr bool FIRST = decltype(first_tag)::value;
+        auto run_stage = [&](auto first_tag, auto last_tag, int stage) {
+            constexpr bool FIRST = decltype(first_tag)::value, LAST = decltype(last_tag)::value;
             // the stage copied while this one is multiplied: the tile's next stage, or the next tile's first
-            // (in the very last stage of the last tile there is nothing left to fetch; stage 0 of the
-            // same tile is fetched again into the free region, which keeps this code free of branches)
-            const bool last_stage = stage + 1 == stages;
-            const int copy_stage = last_stage ? 0 : stage + 1;
-            if (last_stage && has_next) setup_tile_sources(nxt, nxt_in_rows);
+            // (in the very last stage of the last tile there is nothing left to fetch; `nxt` is the same
+            // tile then and its stage 0 is fetched again into the free region, which keeps this code free of
+            // branches).  The last stage works out the next tile's activation sources as it goes: slot k in
+            // unit k, before the unit (>= 5) that issues the slot's copy.
+            const int copy_stage = LAST ? 0 : stage + 1;
+            if constexpr (LAST) c_mt0 = nxt.mt0;
             const char* A = smem + gpar * REGION + lane * 16;
             const char* AI = smem + gpar * REGION + 5 * kFragBytes + lane * 4;
             const char* X = smem + gpar * REGION + A_BYTES;
@@ -249,6 +273,11 @@ __global__ __launch_bounds__(256, 1) void conv3x3_rows_kernel(const T* __restric
                     if constexpr (phase == 2) Mat<T>::template sparse<1>(a_cur[mi], bfc[1][j], acc[m][j], i_cur[mi]);
                     if constexpr (phase == 3) Mat<T>::template sparse<0>(a_cur[mi], bfe[0][j], acc[m][j], i_cur[mi]);
                     if constexpr (phase == 4) Mat<T>::template sparse<1>(a_cur[mi], bfe[1][j], acc[m][j], i_cur[mi]);
+                    if constexpr (LAST && u < X_PER_WAVE) {
+                        constexpr int part = i == 1 ? 0 : i == 3 ? 1 : i == 4 ? 2 : i == 5 ? 3 : -1;
+                        if constexpr (part >= 0)
+                            source_part(std::integral_constant<int, u>{}, std::integral_constant<int, part>{}, nxt, nxt_in_rows);
+                    }
                     if constexpr (i == 2 && 2 * u < COPY_SLOTS) issue_copy_slot(2 * u, copy_stage, gpar ^ 1);
                     if constexpr (i == 2 + TN && 2 * u + 1 < COPY_SLOTS) issue_copy_slot(2 * u + 1, copy_stage, gpar ^ 1);
                     if constexpr (i == 0) {  // issue the next unit's LDS reads behind the first matrix instruction
@@ -303,8 +332,9 @@ __global__ __launch_bounds__(256, 1) void conv3x3_rows_kernel(const T* __restric
             });
             gpar ^= 1;
         };
-        run_stage(std::true_type{}, 0);
-        for (int stage = 1; stage < stages; ++stage) run_stage(std::false_type{}, stage);
+        run_stage(std::true_type{}, std::false_type{}, 0);  // (the launcher admits Ci >= 96: three stages or more)
+        for (int stage = 1; stage + 1 < stages; ++stage) run_stage(std::false_type{}, std::false_type{}, stage);
+        run_stage(std::false_type{}, std::true_type{}, stages - 1);
 
         // the last matrix instructions must have written their accumulators before anything reads them
         asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
@@ -609,6 +639,7 @@ rtoss_status launch_rows(const rtoss_wdesc& d, const ConvParams& c, const char* 
     DeviceInfo dev;
     if (rtoss_status st = current_device(&dev)) return st;
     const int co_blocks = ((d.Co + 15) / 16 + kRowsTM - 1) / kRowsTM;
+    if (c.stride != 1 || d.Ci % 32 || d.Ci < 96) return fail(RTOSS_ESHAPE, "conv: the pipelined kernel needs stride 1 and three or more stages of 32 input channels");
     if ((int64_t)c.N * c.H * c.W * d.Ci / 8 > 0x7fffffff) return fail(RTOSS_ESHAPE, "conv: input too large for 32-bit chunk offsets");
     if ((int64_t)c.N * ((c.W + 15) / 16) * ((c.H + 15) / 16 + 1) * co_blocks > 0x3fffffff) return fail(RTOSS_ESHAPE, "conv: too many tiles");
     int slots = 0;
