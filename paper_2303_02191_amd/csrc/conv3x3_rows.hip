@@ -330,7 +330,7 @@ __global__ __launch_bounds__(256, 1) void conv3x3_rows_kernel(const T* __restric
                     }
                 }
             });
-            gpar ^= 1;
+            gpar = __builtin_amdgcn_readfirstlane(gpar ^ 1);  // (kept scalar: it feeds the LDS address of every copy)
         };
         run_stage(std::true_type{}, std::false_type{}, 0);  // (the launcher admits Ci >= 96: three stages or more)
         for (int stage = 1; stage + 1 < stages; ++stage) run_stage(std::false_type{}, std::false_type{}, stage);
