@@ -202,7 +202,10 @@ __global__ __launch_bounds__(256) void pack_sparse3x3_batch_kernel(SparsePackBat
 // pipelined kernel's 128-channel, 8-stage appetite: TM = 4 covers 64 output channels per workgroup.
 // LAY: tap layout (sparse_frag.h).  Layout 1 (4-entry dictionaries) has three tap groups and no dense centre
 // step; it always takes the one-group-at-a-time schedule.
-template <typename T, typename TO, int S, int TM, int TN, int RT, int CT, bool AHEAD, int LAY = 0>
+// DB: two LDS buffers; the copies of the next stage are issued right after the barrier that opens a stage and land
+// while it is multiplied (one barrier per stage).  For deep stride-1 layers, whose schedule with operand reads ahead
+// is held to two workgroups per compute unit by its registers anyway: two buffers of 38 KB each still fit twice.
+template <typename T, typename TO, int S, int TM, int TN, int RT, int CT, bool AHEAD, int LAY = 0, bool DB = false>
 __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restrict__ x, TO* __restrict__ y,
                                                                 const char* __restrict__ wfrag,
                                                                 const char* __restrict__ zeros, int H, int W, int Ci,
@@ -220,7 +223,8 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
     constexpr int X_CHUNKS = G::x_bytes / 16;                // including the pad chunk of every position
     constexpr int X_PER_WAVE = ((X_CHUNKS + 63) / 64 + 3) / 4;
     static_assert(A_BYTES % 1024 == 0, "weight fragments are whole copy instructions");
-    extern __shared__ __attribute__((aligned(16))) char smem[];  // [weights][activations, rounded up to whole copies]
+    extern __shared__ __attribute__((aligned(16))) char smem[];  // [weights][activations, rounded up to whole copies] (x2 with DB)
+    constexpr int BUF = A_BYTES + X_PER_WAVE * 4096;
     char* lds_a = smem;
     char* lds_x = smem + A_BYTES;
 
@@ -271,17 +275,30 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
     f32x4 acc[TM][TN];
     // (no clearing of the accumulators: the centre step comes first in a stage, and the first stage's
     // writes a * b instead of adding to it)
-    auto run_stage = [&](auto first_tag, int stage) {
-        constexpr bool FIRST = decltype(first_tag)::value;
-        __syncthreads();  // every wave is done reading the previous stage
+    auto issue_copies = [&](int stage, char* buf) {
 #pragma unroll
         for (int k = 0; k < A_PER_WAVE; ++k)
             if (k * 4 + wave < A_WAVE_COPIES)  // wave-uniform
-                copy16_to_lds(a_src + stage * a_stage_stride + (k * 4 + wave) * 1024, lds_a + (k * 4 + wave) * 1024);
+                copy16_to_lds(a_src + stage * a_stage_stride + (k * 4 + wave) * 1024, buf + (k * 4 + wave) * 1024);
 #pragma unroll
-        for (int k = 0; k < X_PER_WAVE; ++k) copy16_to_lds(x_ptr[k] + stage * 64, lds_x + (k * 4 + wave) * 1024);
-        __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's copies have landed in LDS
-        __syncthreads();                     // ... and everybody's
+        for (int k = 0; k < X_PER_WAVE; ++k) copy16_to_lds(x_ptr[k] + stage * 64, buf + A_BYTES + (k * 4 + wave) * 1024);
+    };
+    if constexpr (DB) issue_copies(0, smem);
+    auto run_stage = [&](auto first_tag, int stage) {
+        constexpr bool FIRST = decltype(first_tag)::value;
+        if constexpr (DB) {
+            __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's copies of this stage have landed in LDS
+            __syncthreads();                     // ... and everybody's; and every wave is done reading the other buffer
+            const int par = stage & 1;
+            if (stage + 1 < stages) issue_copies(stage + 1, smem + (par ^ 1) * BUF);
+            lds_a = smem + par * BUF;
+            lds_x = lds_a + A_BYTES;
+        } else {
+            __syncthreads();  // every wave is done reading the previous stage
+            issue_copies(stage, smem);
+            __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's copies have landed in LDS
+            __syncthreads();                     // ... and everybody's
+        }
 
         // AHEAD: operand reads run ahead of the matrix instructions that use them: the centre step's and
         // the corner group's are issued together, the edge group's behind the centre step.  (The matrix
@@ -437,7 +454,7 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
     }
 }
 
-template <typename T, typename TO, int S, int TM, int TN, int RT, int CT, bool AHEAD = true, int LAY = 0>
+template <typename T, typename TO, int S, int TM, int TN, int RT, int CT, bool AHEAD = true, int LAY = 0, bool DB = false>
 rtoss_status launch_variant_sb(const rtoss_wdesc& d, const ConvParams& c, const char* wfrag, const void* x, void* y,
                             hipStream_t s)
 {
@@ -447,8 +464,8 @@ rtoss_status launch_variant_sb(const rtoss_wdesc& d, const ConvParams& c, const 
     const int m_tiles_total = padded_m_tiles(d.Co);  // pitch of the packed section
     const int co_blocks = ((d.Co + 15) / 16 + TM - 1) / TM;
     constexpr int x_copies_per_wave = ((G::x_bytes / 16 + 63) / 64 + 3) / 4;
-    const size_t smem = (size_t)TM * layout_tile_bytes(kLayouts[LAY]) + (size_t)x_copies_per_wave * 4096;
-    auto kern = conv3x3_sparse_sb_kernel<T, TO, S, TM, TN, RT, CT, AHEAD, LAY>;
+    const size_t smem = (DB ? 2 : 1) * ((size_t)TM * layout_tile_bytes(kLayouts[LAY]) + (size_t)x_copies_per_wave * 4096);
+    auto kern = conv3x3_sparse_sb_kernel<T, TO, S, TM, TN, RT, CT, AHEAD, LAY, DB>;
     static LaunchOnce lds_once;  // per instantiation
     if (rtoss_status st = ensure_dynamic_lds((const void*)kern, smem, lds_once, "conv3x3 shared memory attribute")) return st;
     const int64_t total = (int64_t)tiles_r * tiles_c * co_blocks * c.N;
@@ -487,17 +504,16 @@ rtoss_status launch_typed(const rtoss_wdesc& d, const ConvParams& c, const char*
     // The fragment section is padded to a multiple of 8 channel tiles, so any TM <= 8 may over-read rows
     // that hold zeros; outputs beyond Co are never stored.
     // Layers with at most 64 output channels, or too few stages to amortise the pipelined kernel's
-    // prologue, take the single-buffered kernel with 64 channels per workgroup.
-    const bool small = d.Co <= 64 || d.Ci <= 64;
+    // prologue, come here: 64 channels per workgroup.
     if (c.stride == 1) {
-        // 8x16-position tiles for these: 38 KB of LDS, four workgroups per compute unit.  (Measured: more
-        // resident workgroups beat double-buffering inside one, and beat 16x16 tiles, on every such layer.)
-        // (up to 64 input channels are one or two stages: nothing to gain inside a workgroup, see AHEAD)
+        // 8x16-position tiles for these: 38 KB of LDS per buffer.  (Measured: several resident workgroups beat one
+        // workgroup per compute unit with larger buffers, and beat 16x16 tiles, on every such layer.)
+        // (up to 64 input channels are one or two stages: nothing to gain inside a workgroup, see AHEAD; one buffer,
+        // four workgroups per compute unit)
         if (d.Ci <= 64) return launch_variant_sb<T, TO, 1, 4, 2, 2, 4, false>(d, c, wfrag, x, y, s);
-        if (small) return launch_variant_sb<T, TO, 1, 4, 2, 2, 4>(d, c, wfrag, x, y, s);
-        // ... and so do launches that would leave compute units idle with 128 channels per workgroup
-        if (!takes_pipelined_kernel(d, c)) return launch_variant_sb<T, TO, 1, 4, 2, 2, 4>(d, c, wfrag, x, y, s);
-        return launch_variant_sb<T, TO, 1, 4, 2, 2, 4>(d, c, wfrag, x, y, s);  // (not reached: see takes_pipelined_kernel)
+        // deeper layers: two buffers per workgroup (still two workgroups per compute unit); also the launches that
+        // would leave compute units idle with the pipelined kernel's 128 channels per workgroup
+        return launch_variant_sb<T, TO, 1, 4, 2, 2, 4, true, 0, true>(d, c, wfrag, x, y, s);
     }
     // Stride 2: the input tile of a 16x16 output tile (33x33 positions) nearly fills the LDS by itself.
     // Half-height tiles (8x16 outputs, 17x33 inputs) with 64 channels per workgroup need 72 KB, so two
