@@ -145,3 +145,27 @@ def test_pipelined_kernel_at_the_largest_channel_count():
     ref = oracle.conv2d_points(wl.to_f64(xs, dt), oracle.mask(wl.to_f64(ws, dt), masks, idx), pts)
     vals = got32[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]]
     assert np.max(np.abs(vals - ref)) <= 2e-3 * np.sqrt(np.mean(ref ** 2))
+
+
+def test_pipelined_kernel_many_tiles_per_workgroup():
+    """Four rounds of tiles and more per persistent workgroup (tall after tall, short after short): each tile's last
+    stage works out the next tile's copy sources between its matrix instructions."""
+    dt, N, Ci, Co, H, W, k = wl.BF16, 44, 96, 256, 84, 64, 3
+    rng = np.random.default_rng(78)
+    masks = B.rtoss_pattern_dict(k)
+    ws = wl.round_to_dtype(rng.standard_normal((Co, Ci, 3, 3)) * 0.05, dt)
+    xs = wl.round_to_dtype(rng.standard_normal((N, Ci, H, W)), dt)
+    idx = _indices("run", rng, Co, Ci, len(masks), None, masks).astype(np.uint8).reshape(-1)
+    lay = pl.CoherentLayer(Co, Ci, k, dt, masks).pack(pl.to_device(ws, dt), torch.from_numpy(idx).cuda())
+    assert (lay.steps() == k).all()
+    x_dev = pl.to_device(wl.nchw_to_nhwc(xs), dt)
+    y16 = lay.conv(x_dev, relu=True)
+    y32 = lay.conv(x_dev, relu=True, out_dt=wl.F32)
+    torch.cuda.synchronize()
+    got32 = wl.nhwc_to_nchw(pl.to_host(y32)).astype(np.float64)
+    assert np.array_equal(wl.nhwc_to_nchw(pl.to_host(y16)), wl.round_to_dtype(got32, dt))
+    pts = np.stack([rng.integers(0, N, 4000), rng.integers(0, Co, 4000), rng.integers(0, H, 4000), rng.integers(0, W, 4000)], 1)
+    pts[:4] = [[0, 0, 0, 0], [N - 1, Co - 1, H - 1, W - 1], [N - 1, 128, 83, 0], [7, 255, 40, 63]]
+    ref = oracle.conv2d_points(wl.to_f64(xs, dt), oracle.mask(wl.to_f64(ws, dt), masks, idx), pts, relu=True)
+    vals = got32[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]]
+    assert np.max(np.abs(vals - ref)) <= 2e-3 * np.sqrt(np.mean(ref ** 2))

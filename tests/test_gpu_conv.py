@@ -332,6 +332,28 @@ def _check_layer_full(cfg, L, xs, xv, ws, wv, masks, relu, seed, npts=4000):
     return g, y32
 
 
+@pytest.mark.parametrize("dt", [wl.F16, wl.BF16])
+def test_pipelined_kernel_many_tiles_per_workgroup(dt):
+    """About seven tiles per persistent workgroup (176 strips of 84 rows x 2 channel blocks on 256 compute units):
+    every workgroup walks several tall tiles and then short ones, each tile's last stage working out the next
+    tile's copy sources.  Sampled outputs against the oracle; stored 16-bit output against the fp32 output."""
+    N, Ci, Co, H, W, k = 44, 96, 256, 84, 64, 3
+    rng = np.random.default_rng(4242 + dt)
+    masks = B.rtoss_pattern_dict(k)
+    xs = wl.round_to_dtype(rng.standard_normal((N, Ci, H, W)), dt)
+    ws = wl.round_to_dtype(rng.standard_normal((Co, Ci, 3, 3)) * 0.05, dt)
+    xv, wv = wl.to_f64(xs, dt), wl.to_f64(ws, dt)
+    idx = oracle.select(wv, masks)
+    g = GpuLayer(ws, dt, masks, k)
+    assert np.array_equal(g.idx_host(), idx)
+    y32 = g.conv_nchw(xs, relu=True, out_dt=wl.F32)
+    y16 = g.conv_nchw(xs, relu=True)
+    assert np.array_equal(y16, wl.round_to_dtype(y32.astype(np.float64), dt))
+    pts = _sample_points(rng, N, Co, H, W, 6000)
+    ref = oracle.conv2d_points(xv, oracle.mask(wv, masks, idx), pts, relu=True)
+    check(y32[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]], ref, dt)
+
+
 def test_cfg2_full_layers():
     cfg = wl.get_config(2)
     rng = wl.make_rng(cfg)
