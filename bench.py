@@ -6,7 +6,8 @@ over every weight tensor of the workload, packing of every layer, and the patter
 convolution of every layer.  Inputs are resident in HBM before the timed region starts.
 Prints ONE JSON line.  `value` is effective TFLOP/s counted on non-zero MACs only
 (2 * N*Ho*Wo*k*groups / time), whole step; `roofline` describes the dominant kernel (the
-convolution) from HIP-event timings taken inside the timed region; `cpu_baseline` is the
+convolution) from HIP-event timings taken inside the timed region (on every --event-every-th
+step: the records themselves cost stream time); `cpu_baseline` is the
 fp64 CPU oracle timed on a bounded sample of the same workload.
 
 The run proves what it prints: the convolutions of the oracle's sample are repeated with fp32
@@ -132,6 +133,10 @@ def parse():
     ap.add_argument("--warmup", type=int, default=300,
                     help="untimed steps in front of the timed ones.  The chip needs tens of milliseconds of load to reach "
                          "its steady clocks: the first steps after an idle phase run about 15 %% slower than the rest")
+    ap.add_argument("--event-every", type=int, default=10,
+                    help="record the HIP events that time the three phases on every Nth timed step only: an event "
+                         "record costs about 3 us of stream time (kernels on either side of it do not overlap), "
+                         "and four per step took 6 %% off the throughput of a 0.2 ms step")
     ap.add_argument("--prewarm-ms", type=float, default=100.0,
                     help="besides the warm-up steps: keep running untimed steps until this much wall time has passed, so "
                          "that a small --warmup still measures steady clocks (0: off)")
@@ -163,6 +168,7 @@ class Workload:
     """Device-resident tensors of one configuration and the three phases of a step."""
 
     prewarm_ms = 100.0  # see --prewarm-ms
+    event_every = 10    # see --event-every
 
     def __init__(self, cfg, dev, dict_top=0):
         import torch
@@ -274,10 +280,11 @@ class Workload:
             for _ in range(10):
                 step()
             torch.cuda.synchronize()
-        all_events = [[ev() for _ in range(4)] for _ in range(steps)]
+        every = max(1, min(self.event_every, steps))
+        all_events = [[ev() for _ in range(4)] for _ in range((steps + every - 1) // every)]
         t0 = time.perf_counter()
         for s in range(steps):
-            step(all_events[s])
+            step(all_events[s // every] if s % every == 0 else None)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         ms = (t1 - t0) * 1e3 / steps
@@ -389,6 +396,7 @@ def main():
         cfg = dataclasses.replace(cfg, k=args.k, name="%s_k%d" % (cfg.name, args.k))
     eb = wl.ELEM_BYTES[cfg.dtype]
     Workload.prewarm_ms = args.prewarm_ms
+    Workload.event_every = args.event_every
     work = Workload(cfg, dev, args.dict_top)
     masks, dict_counts = work.masks, work.dict_counts
     ev = lambda: torch.cuda.Event(enable_timing=True)
@@ -520,7 +528,7 @@ def main():
     out = {
         "metric": "effective TFLOP/s on non-zero MACs, select+pack+pattern-sparse conv",
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "prewarm_ms": args.prewarm_ms, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "prewarm_ms": args.prewarm_ms, "phase_events_every": args.event_every, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.DTYPE_NAMES[cfg.dtype], "data": "synthetic",
         "launch": "hip_graph" if use_graph else "eager",
         "config": {"workload": cfg.name, "batch": cfg.N, "layers": len(cfg.layers), "k": cfg.k,
