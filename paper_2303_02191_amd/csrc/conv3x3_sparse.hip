@@ -515,12 +515,15 @@ rtoss_status launch_typed(const rtoss_wdesc& d, const ConvParams& c, const char*
         // would leave compute units idle with the pipelined kernel's 128 channels per workgroup
         return launch_variant_sb<T, TO, 1, 4, 2, 2, 4, true, 0, true>(d, c, wfrag, x, y, s);
     }
-    // Stride 2: the input tile of a 16x16 output tile (33x33 positions) nearly fills the LDS by itself.
-    // Half-height tiles (8x16 outputs, 17x33 inputs) with 64 channels per workgroup need 72 KB, so two
-    // workgroups share a compute unit and overlap each other's copies, and small images pad less.
-    // (a single-stage layer is all copy, short multiply, store: quarter-height tiles put three workgroups on a unit)
-    if (d.Ci == 32) return launch_variant_sb<T, TO, 2, 4, 1, 1, 4>(d, c, wfrag, x, y, s);
-    return launch_variant_sb<T, TO, 2, 4, 2, 2, 4>(d, c, wfrag, x, y, s);
+    // Stride 2: an output position needs four input positions, so the activation tile dominates the LDS and the
+    // copies.  Small tiles of 64 output positions (50 KB with 64 channels per workgroup: three workgroups per compute
+    // unit, which overlap each other's copies) measured faster than 8x16 tiles on every stride-2 layer of a
+    // YOLOv5s-shaped model; 8x8 where that shape pads the image less than 4x16 (40x40 and 20x20 outputs), else 4x16.
+    const int Ho = (c.H - 1) / 2 + 1, Wo = (c.W - 1) / 2 + 1;
+    const int64_t padded_4x16 = (int64_t)((Ho + 3) / 4 * 4) * ((Wo + 15) / 16 * 16);
+    const int64_t padded_8x8 = (int64_t)((Ho + 7) / 8 * 8) * ((Wo + 7) / 8 * 8);
+    if (padded_8x8 < padded_4x16) return launch_variant_sb<T, TO, 2, 4, 1, 2, 2>(d, c, wfrag, x, y, s);
+    return launch_variant_sb<T, TO, 2, 4, 1, 1, 4>(d, c, wfrag, x, y, s);
 }
 
 }  // namespace
