@@ -56,6 +56,8 @@ __device__ __forceinline__ int stage_channel(int q, int g, int half)
     return 8 * (2 * (q & 1) + (g >> 1)) + 4 * half + 2 * (q >> 1) + (g & 1);
 }
 
+constexpr int kMaxTapGroups = 3;  // tap groups of a layout (TapLayout::tap)
+
 struct SparsePackArgs {
     const void* w;
     const uint8_t* idx;
@@ -81,6 +83,8 @@ __device__ __forceinline__ void pack_sparse3x3_body(const SparsePackArgs& a, con
     __shared__ uint16_t masks[256];
     __shared__ __attribute__((aligned(16))) uint16_t wl[16][32 * 9];  // [row][channel][tap]
     __shared__ __attribute__((aligned(16))) uint8_t il[16][32];       // [row][channel]
+    __shared__ uint16_t slots[256 * kMaxTapGroups];
+    constexpr unsigned kNoTaps = 15u | (15u << 4) | (0u << 8) | (1u << 10);  // a row past Co: zeros, slots 0 and 1
     masks[threadIdx.x] = dict.mask[threadIdx.x];
     if (block < job.blocks) {  // the first blocks write the blob's public section
         __syncthreads();
@@ -95,6 +99,27 @@ __device__ __forceinline__ void pack_sparse3x3_body(const SparsePackArgs& a, con
         return;
     }
     const int mt = tile % m_tiles, cb = tile / m_tiles;
+    // slots[p][group]: taps of pattern p's first and second live tap in the group (bits 0-3, 4-7; 15: none) and the
+    // slots they take (bits 8-9, 10-11; a missing second value points at the slot after the first, a group without
+    // live taps at slots 0 and 1: padding values of 0 may point anywhere, as long as the two differ)
+    for (int e = threadIdx.x; e < dict.P * kMaxTapGroups; e += 256) {
+        const int p = e / kMaxTapGroups, group = e % kMaxTapGroups;
+        unsigned tp[2] = {15u, 15u}, f[2] = {0u, 1u};
+        if (group < lay.groups) {
+            const unsigned m = dict.mask[p];
+            int n = 0;
+            for (int sl = 0; sl < 4; ++sl) {
+                const int tt = lay.tap[group][sl];
+                if (tt >= 0 && ((m >> tt) & 1u) && n < 2) {
+                    tp[n] = (unsigned)tt;
+                    f[n] = (unsigned)sl;
+                    ++n;
+                }
+            }
+            if (n == 1) f[1] = (f[0] + 1) & 3;
+        }
+        slots[e] = (uint16_t)(tp[0] | (tp[1] << 4) | (f[0] << 8) | (f[1] << 10));
+    }
     // ---- stage: 16 rows x 36 chunks of weights, 16 rows x 2 chunks of indices (rows past Co are zeros) ----
     // (rows start at multiples of 576 and 32 bytes from the tensors' first elements; the interface asks for
     // element alignment only, so tensors that do not start on a 16-byte boundary are staged element-wise)
@@ -127,41 +152,34 @@ __device__ __forceinline__ void pack_sparse3x3_body(const SparsePackArgs& a, con
         }
     }
     __syncthreads();
-    // ---- assemble: item = (fragment, lane) ----
+    // ---- assemble: item = (fragment, lane).  What a pattern puts into a tap group -- which of the group's four slots
+    // its (at most two) live taps take, and which taps those are -- comes from the table built above, so the walk over
+    // the 4 x 4 (channel, slot) pairs of an item has no data-dependent branch. ----
     char* tile_out = out + (size_t)tile * tile_bytes;
     for (int item = threadIdx.x; item < 64 * frags; item += 256) {
-        const int lane = item % 64, step = item / 64;
+        const int lane = item % 64, step = item / 64;  // (step is uniform over a wave)
         const int r = lane % 16, q = lane / 16;
         const bool row_live = tile_row_channel(mt, r) < Co;
         uint16_t vals[8];
         if (step == 2 * lay.groups) {  // dense centre tap: K = 8q + j
+#pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const int c = 8 * q + j;
-                vals[j] = (row_live && ((masks[il[r][c]] >> 4) & 1u)) ? wl[r][c * 9 + 4] : (uint16_t)0;
+                const uint16_t v = wl[r][c * 9 + 4];
+                vals[j] = (row_live && ((masks[il[r][c]] >> 4) & 1u)) ? v : (uint16_t)0;
             }
         } else {
             const int group = step >> 1, half = step & 1;
             unsigned fields = 0;
+#pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int c = stage_channel(q, g, half);
-                uint16_t v[2] = {0, 0};
-                int f[2] = {0, 1};
-                if (row_live) {
-                    const unsigned m = masks[il[r][c]];
-                    int n = 0;
-                    for (int sl = 0; sl < 4; ++sl) {
-                        const int t = lay.tap[group][sl];
-                        if (t >= 0 && ((m >> t) & 1u) && n < 2) {
-                            v[n] = wl[r][c * 9 + t];
-                            f[n] = sl;
-                            ++n;
-                        }
-                    }
-                    if (n == 1) f[1] = (f[0] + 1) & 3;  // padding value 0 may point anywhere
-                }
-                vals[2 * g] = v[0];
-                vals[2 * g + 1] = v[1];
-                fields |= (unsigned)(f[0] | (f[1] << 2)) << (4 * g);
+                const unsigned e = row_live ? slots[il[r][c] * kMaxTapGroups + group] : kNoTaps;
+                const unsigned t0 = e & 15u, t1 = (e >> 4) & 15u;  // taps of the two values (15: none)
+                const uint16_t v0 = wl[r][c * 9 + (t0 < 9 ? t0 : 0)], v1 = wl[r][c * 9 + (t1 < 9 ? t1 : 0)];
+                vals[2 * g] = t0 < 9 ? v0 : (uint16_t)0;
+                vals[2 * g + 1] = t1 < 9 ? v1 : (uint16_t)0;
+                fields |= ((e >> 8) & 15u) << (4 * g);  // slot of the first value | slot of the second << 2
             }
             uint16_t* ip = (uint16_t*)(tile_out + frags * kFragBytes + (group * 64 + lane) * 4 + half * 2);
             *ip = (uint16_t)fields;
