@@ -61,3 +61,18 @@ def test_fp32_tensors_use_the_max_bound():
     assert b == 1e-5 and e > b
     e, b = bench.conv_error(ref + 2e-6 * np.max(np.abs(ref)), ref, True)
     assert e <= b
+
+
+def test_more_than_one_gpu_is_refused_with_a_message(monkeypatch, capsys):
+    # one device only: the command line says so and exits non-zero before anything touches a GPU
+    monkeypatch.setattr(sys, "argv", ["bench.py", "--gpus", "2"])
+    assert bench.main() == 2
+    assert "one GPU only" in capsys.readouterr().err
+
+
+def test_default_command_line():
+    # the defaults the measurement protocol relies on: steady clocks before the timed region, sampled phase events
+    import unittest.mock as mock
+    with mock.patch.object(sys, "argv", ["bench.py"]):
+        args = bench.parse()
+    assert args.gpus == 1 and args.steps == 100 and args.warmup >= 300 and args.prewarm_ms >= 100 and args.event_every == 10
