@@ -262,6 +262,18 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
     const int ih0 = oh0 * S - 1, iw0 = ow0 * S - 1;
     const int stages = Ci / 32;
 
+    const char* a_src = wfrag + (int64_t)mt0 * TILE + lane * 16;
+    const int64_t a_stage_stride = (int64_t)m_tiles_total * TILE;
+    auto issue_weight_copies = [&](int stage, char* buf) {
+#pragma unroll
+        for (int k = 0; k < A_PER_WAVE; ++k)
+            if (k * 4 + wave < A_WAVE_COPIES)  // wave-uniform
+                copy16_to_lds(a_src + stage * a_stage_stride + (k * 4 + wave) * 1024, buf + (k * 4 + wave) * 1024);
+    };
+    // (the weight fragments of stage 0 need only the channel block: they are under way while the lanes work out
+    // their activation sources)
+    issue_weight_copies(0, smem);
+
     // Copy sources of stage 0.  Every lane copies 16 bytes in every copy instruction; a lane whose LDS
     // slot is zero padding of the tile (or a pad chunk) reads the block of zeros behind the fragments.
     const char* x_ptr[X_PER_WAVE];
@@ -276,8 +288,6 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
         const int off = ((n_img * H + ih) * W + iw) * (Ci >> 3) + q;
         x_ptr[k] = inside ? (const char*)x + (int64_t)off * 16 : zeros;
     }
-    const char* a_src = wfrag + (int64_t)mt0 * TILE + lane * 16;
-    const int64_t a_stage_stride = (int64_t)m_tiles_total * TILE;
 
     // ---- per-lane read addresses of the B operand ----
     const int nn = lane & 15, qq = lane >> 4;
@@ -293,27 +303,24 @@ __global__ __launch_bounds__(256) void conv3x3_sparse_sb_kernel(const T* __restr
     f32x4 acc[TM][TN];
     // (no clearing of the accumulators: the centre step comes first in a stage, and the first stage's
     // writes a * b instead of adding to it)
-    auto issue_copies = [&](int stage, char* buf) {
-#pragma unroll
-        for (int k = 0; k < A_PER_WAVE; ++k)
-            if (k * 4 + wave < A_WAVE_COPIES)  // wave-uniform
-                copy16_to_lds(a_src + stage * a_stage_stride + (k * 4 + wave) * 1024, buf + (k * 4 + wave) * 1024);
+    auto issue_copies = [&](int stage, char* buf, bool with_weights) {
+        if (with_weights) issue_weight_copies(stage, buf);
 #pragma unroll
         for (int k = 0; k < X_PER_WAVE; ++k) copy16_to_lds(x_ptr[k] + stage * 64, buf + A_BYTES + (k * 4 + wave) * 1024);
     };
-    if constexpr (DB) issue_copies(0, smem);
+    if constexpr (DB) issue_copies(0, smem, false);
     auto run_stage = [&](auto first_tag, int stage) {
         constexpr bool FIRST = decltype(first_tag)::value;
         if constexpr (DB) {
             __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's copies of this stage have landed in LDS
             __syncthreads();                     // ... and everybody's; and every wave is done reading the other buffer
             const int par = stage & 1;
-            if (stage + 1 < stages) issue_copies(stage + 1, smem + (par ^ 1) * BUF);
+            if (stage + 1 < stages) issue_copies(stage + 1, smem + (par ^ 1) * BUF, true);
             lds_a = smem + par * BUF;
             lds_x = lds_a + A_BYTES;
         } else {
             __syncthreads();  // every wave is done reading the previous stage
-            issue_copies(stage, smem);
+            issue_copies(stage, smem, !FIRST);  // (stage 0's weight fragments are already under way)
             __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's copies have landed in LDS
             __syncthreads();                     // ... and everybody's
         }
